@@ -1,0 +1,213 @@
+/*
+ * rocketkv.h -- C ABI of the MI355X (gfx950) RocketKV hot path.
+ *
+ * RocketKV (arXiv 2502.14051) compresses the KV cache of a decoder LLM in two
+ * stages: a one-time, GQA-aware SnapKV eviction of prompt tokens (Section 3.3)
+ * and, at every decode step, hybrid sparse attention (HSA, Section 3.4 and
+ * Algorithm 1): page-wise min/max key summaries, a top-k1 channel pick per GQA
+ * group, approximate page scores, a top-k page pick and exact attention over
+ * the picked pages only.
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ *  - All data pointers are DEVICE pointers unless marked "host".  The struct
+ *    `rocketkv_cache_t` itself lives in host memory and is read during the
+ *    call only.
+ *  - bf16 tensors are passed as `void*` / `const void*` (2 bytes per element,
+ *    upper half of an IEEE binary32).
+ *  - `stream` is a `hipStream_t` passed as `void*` (NULL = the null stream).
+ *    Work is enqueued on it and the call returns without synchronising.  No
+ *    entry point allocates or frees device memory; scratch comes from the
+ *    caller's `workspace` (size from rocketkv_workspace_bytes, 256-byte
+ *    aligned).  The workspace needs no initialisation, and two calls that
+ *    overlap in time must not share one.
+ *  - Return value: ROCKETKV_OK (0) or a negative rocketkv_status_t.  Argument
+ *    validation runs on the host before anything is launched; on error
+ *    nothing has been enqueued and rocketkv_last_error() describes the
+ *    reason (thread-local, valid until the next call on the same thread).
+ *  - The caller owns every buffer.  The library keeps no state between calls.
+ *
+ * Cache layout (chosen for CDNA4 matrix-core operand order)
+ * ---------------------------------------------------------
+ * A cache is a pool of physical pages of `page_size` tokens.  For a physical
+ * page `pp` and KV head `g` the tile starts at element
+ *        pp * stride_page + g * stride_head
+ * of the pool and holds `page_size * head_dim` contiguous bf16 values:
+ *        K tile: [page_size][head_dim]   (token-major, channels contiguous)
+ *        V tile: [head_dim][page_size]   (channel-major, tokens contiguous)
+ * Sequence b's logical page p (tokens p*page_size ...) is physical page
+ * `block_table[b*pages_cap + p]`, or `b*pages_cap + p` when block_table is
+ * NULL.  `seq_lens[b]` is the number of valid tokens of sequence b (all KV
+ * heads of a sequence hold the same number of tokens).  Entries of the block
+ * table outside [0, n_phys_pages) are treated as absent pages.
+ *
+ * Page summaries (Section 3.4 Step 1) are two bf16 tensors
+ *        kmax, kmin: [batch][n_kv_heads][head_dim][pages_cap]
+ * i.e. channel-major with the page index contiguous, so that each channel
+ * picked in Step 2 is one contiguous row.  Columns >= ceil(seq_len/page_size)
+ * are never read.
+ *
+ * Limits of this build: head_dim == 128; n_q_heads a multiple of n_kv_heads
+ * with group size <= 16; page_size == 16 for the attention entry points
+ * (summaries and selection accept 1..64); pages_cap a multiple of 8 and at
+ * most ROCKETKV_MAX_PAGES for selection.
+ */
+#ifndef ROCKETKV_H
+#define ROCKETKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ROCKETKV_MAX_PAGES 8192
+
+typedef enum {
+  ROCKETKV_OK = 0,
+  ROCKETKV_INVALID_ARG = -1,         /* NULL pointer, bad shape, bad budget ...      */
+  ROCKETKV_UNSUPPORTED = -2,         /* valid request outside this build's limits    */
+  ROCKETKV_WORKSPACE_TOO_SMALL = -3, /* workspace_bytes < rocketkv_workspace_bytes() */
+  ROCKETKV_HIP_ERROR = -4            /* a HIP runtime call failed                    */
+} rocketkv_status_t;
+
+typedef enum {
+  ROCKETKV_OP_HSA_DECODE = 0,   /* a = token_budget                       */
+  ROCKETKV_OP_DENSE_DECODE = 1, /* no extra arguments                     */
+  ROCKETKV_OP_SNAPKV = 2,       /* a = window, b = keep_budget            */
+  ROCKETKV_OP_ATTEND = 3        /* a = pages_row_len (0 = every page)     */
+} rocketkv_op_t;
+
+typedef struct rocketkv_cache {
+  int32_t batch;
+  int32_t n_q_heads;
+  int32_t n_kv_heads;
+  int32_t head_dim;
+  int32_t page_size;
+  int32_t pages_cap;          /* logical pages per sequence: row length of block_table / summaries */
+  int64_t n_phys_pages;       /* pages in the pools */
+  int64_t stride_page;        /* elements between physical pages (same for K and V pools) */
+  int64_t stride_head;        /* elements between KV heads inside a page, >= page_size*head_dim */
+  int32_t* seq_lens;          /* device [batch]; written by snapkv_compress (dst) and append_kv */
+  const int32_t* block_table; /* device [batch][pages_cap] or NULL (identity) */
+  void* k_pool;               /* device bf16 */
+  void* v_pool;               /* device bf16 */
+} rocketkv_cache_t;
+
+/* Scratch bytes needed by an operation on `cache` (host struct; device
+ * pointers inside it are not dereferenced).  Returns 0 for an invalid
+ * request (see rocketkv_last_error). */
+size_t rocketkv_workspace_bytes(int32_t op, const rocketkv_cache_t* cache, int32_t a, int32_t b);
+
+/*
+ * HSA Step 1 (Section 3.4): element-wise max and min of the keys of each page,
+ * over the valid tokens of the page only, for logical pages
+ * [first_page, first_page + n_pages) of every (sequence, KV head); n_pages < 0
+ * means "through the last page".  Pages at or beyond ceil(seq_len/page_size)
+ * are skipped.  Exact: results are bf16 values present in K.
+ * kmax, kmin: device bf16 [batch][n_kv_heads][head_dim][pages_cap], written.
+ */
+int32_t rocketkv_build_page_summaries(const rocketkv_cache_t* cache, void* kmax, void* kmin,
+                                      int32_t first_page, int32_t n_pages, void* stream);
+
+/*
+ * HSA Step 2 (Algorithm 1, i1 / g / P / s1 / i2): per (sequence, KV head)
+ *   a[c] = sum over the group's heads of |q[h][c]|,  s[c] = sum of q[h][c]  (fp32, head order)
+ *   i1   = the channel_budget channels with the largest a (ties: lower channel)
+ *   score[p] = sum over c in i1 of s[c] * (s[c] >= 0 ? kmax[c][p] : kmin[c][p])   (fp32)
+ *   i2   = the kp pages with the largest score (ties: lower page), where
+ *          kp = P if token_budget >= seq_len, else max(1, min(P, token_budget / page_size)),
+ *          P = ceil(seq_len / page_size); the last min(n_recent_pages, kp) pages are always in.
+ * q: bf16 [batch][n_q_heads][head_dim].
+ * out_pages: int32 [batch][n_kv_heads][pages_row_len], ascending page ids, -1 padded;
+ *            pages_row_len must be >= min(pages_cap, ceil(token_budget / page_size)).
+ * out_channels: optional int32 [batch][n_kv_heads][channel_budget], ascending.
+ * out_scores: optional fp32 [batch][n_kv_heads][pages_cap] (first P entries written).
+ */
+int32_t rocketkv_hsa_select(const rocketkv_cache_t* cache, const void* q, const void* kmax,
+                            const void* kmin, int32_t channel_budget, int32_t token_budget,
+                            int32_t n_recent_pages, int32_t* out_pages, int32_t pages_row_len,
+                            int32_t* out_channels, float* out_scores, void* stream);
+
+/*
+ * HSA Step 3 (Algorithm 1, y = attn(q, K[i2], V[i2])): exact softmax attention
+ * (scale 1/sqrt(head_dim)) of every query head over the valid tokens of the
+ * listed pages of its KV head; bf16 operands, fp32 accumulation, bf16 result
+ * rounded to nearest even.
+ * pages: int32 [batch][n_kv_heads][pages_row_len] logical page ids; entries
+ *        < 0 or >= ceil(seq_len/page_size) are ignored.  NULL = every page of
+ *        the sequence (full-KV attention, the Full-KV row of Table 1).
+ * out: bf16 [batch][n_q_heads][head_dim]; a sequence with no attended token
+ *      gets zeros.  out_lse: optional fp32 [batch][n_q_heads], natural-log
+ *      sum-exp of the scaled logits (-inf when nothing was attended).
+ * workspace: rocketkv_workspace_bytes(ROCKETKV_OP_ATTEND, cache, pages_row_len, 0).
+ */
+int32_t rocketkv_attend(const rocketkv_cache_t* cache, const void* q, const int32_t* pages,
+                        int32_t pages_row_len, void* out, float* out_lse, void* workspace,
+                        size_t workspace_bytes, void* stream);
+
+/*
+ * One HSA decode step over a cache whose summaries are current: Step 2 then
+ * Step 3 (Algorithm 1 end to end).  Arguments as in rocketkv_hsa_select and
+ * rocketkv_attend; out_pages (row length min(pages_cap, ceil(token_budget /
+ * page_size))), out_channels and out_lse are optional.
+ * workspace: rocketkv_workspace_bytes(ROCKETKV_OP_HSA_DECODE, cache, token_budget, 0).
+ */
+int32_t rocketkv_hsa_decode(const rocketkv_cache_t* cache, const void* q, const void* kmax,
+                            const void* kmin, int32_t channel_budget, int32_t token_budget,
+                            int32_t n_recent_pages, void* out, float* out_lse,
+                            int32_t* out_pages, int32_t* out_channels, void* workspace,
+                            size_t workspace_bytes, void* stream);
+
+/*
+ * Full-KV decode attention (Table 1, first row; the baseline every figure of
+ * Section 4.3 is normalised to): rocketkv_attend with every page.
+ * workspace: rocketkv_workspace_bytes(ROCKETKV_OP_DENSE_DECODE, cache, 0, 0).
+ */
+int32_t rocketkv_dense_decode(const rocketkv_cache_t* cache, const void* q, void* out,
+                              float* out_lse, void* workspace, size_t workspace_bytes,
+                              void* stream);
+
+/*
+ * Appending one generated token per sequence (Section 3.4 Step 1, last
+ * sentence: the summaries follow every new key): writes k_new / v_new
+ * (bf16 [batch][n_kv_heads][head_dim]) at position seq_lens[b], folds the key
+ * into the tail page's kmax / kmin, then increments seq_lens[b].  A sequence
+ * already holding pages_cap * page_size tokens is left unchanged.
+ */
+int32_t rocketkv_append_kv(const rocketkv_cache_t* cache, const void* k_new, const void* v_new,
+                           void* kmax, void* kmin, void* stream);
+
+/*
+ * Stage 1 (Section 3.3; window and kernel sizes from Appendix A.3): GQA-aware
+ * SnapKV.  Per (sequence, KV head) with prompt length S = src->seq_lens[b]:
+ *   if S <= keep_budget every token is kept; otherwise
+ *   A[h][w][j] = causal softmax over j <= S-window+w of q_obs[h][w] . K[j] / sqrt(head_dim)
+ *   vote[j] = sum over heads of the group and window rows of A[h][w][j],  j < S-window
+ *   pooled  = stride-1 max-pool of vote with odd kernel pool_kernel, clipped at the ends
+ *   kept    = top-(keep_budget - window) of pooled (ties: lower position) plus the window
+ * and K/V of the kept tokens are copied, in ascending position, into `dst`
+ * (same head counts, head_dim and page_size; dst->pages_cap*page_size >=
+ * keep_budget), dst->seq_lens[b] = min(S, keep_budget).
+ * q_obs: bf16 [batch][n_q_heads][window][head_dim], queries of the last
+ *        `window` prompt positions.  A sequence with keep_budget < S < window
+ *        is rejected on the device side by keeping its first keep_budget tokens.
+ * kept_idx: optional int32 [batch][n_kv_heads][keep_budget], -1 padded.
+ * workspace: rocketkv_workspace_bytes(ROCKETKV_OP_SNAPKV, src, window, keep_budget).
+ */
+int32_t rocketkv_snapkv_compress(const void* q_obs, const rocketkv_cache_t* src, int32_t window,
+                                 int32_t pool_kernel, int32_t keep_budget,
+                                 const rocketkv_cache_t* dst, int32_t* kept_idx, void* workspace,
+                                 size_t workspace_bytes, void* stream);
+
+/* Thread-local description of the last error returned on this thread ("" if none). */
+const char* rocketkv_last_error(void);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int32_t rocketkv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ROCKETKV_H */

@@ -1,0 +1,338 @@
+// C-ABI front end: argument validation on the host, workspace carving, kernel launches.
+// Every exported function validates before it enqueues anything and never synchronises.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "common.h"
+
+namespace rkv {
+void tune_attend(int target_wgs, int min_chunk);
+}
+
+using namespace rkv;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+int hip_fail(hipError_t e, const char* what) {
+  return fail(ROCKETKV_HIP_ERROR, "%s: %s", what, hipGetErrorString(e));
+}
+
+// Checks the host-visible part of a cache description.  `need_pools` is false for queries that only
+// size a workspace.
+int check_cache(const rocketkv_cache_t* c, bool need_pools, const char* who) {
+  if (!c) return fail(ROCKETKV_INVALID_ARG, "%s: cache is NULL", who);
+  if (c->batch < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1)
+    return fail(ROCKETKV_INVALID_ARG, "%s: batch and head counts must be positive", who);
+  if (c->n_q_heads % c->n_kv_heads != 0)
+    return fail(ROCKETKV_INVALID_ARG, "%s: n_q_heads (%d) is not a multiple of n_kv_heads (%d)", who,
+                c->n_q_heads, c->n_kv_heads);
+  if (c->head_dim != kHeadDim)
+    return fail(c->head_dim < 1 ? ROCKETKV_INVALID_ARG : ROCKETKV_UNSUPPORTED,
+                "%s: head_dim %d (this build handles %d)", who, c->head_dim, kHeadDim);
+  if (c->n_q_heads / c->n_kv_heads > kMaxGroup)
+    return fail(ROCKETKV_UNSUPPORTED, "%s: group size %d exceeds %d", who,
+                c->n_q_heads / c->n_kv_heads, kMaxGroup);
+  if (c->page_size < 1) return fail(ROCKETKV_INVALID_ARG, "%s: page_size must be >= 1", who);
+  if (c->page_size > 64) return fail(ROCKETKV_UNSUPPORTED, "%s: page_size %d > 64", who, c->page_size);
+  if (c->pages_cap < 1 || c->pages_cap % 8 != 0)
+    return fail(ROCKETKV_INVALID_ARG, "%s: pages_cap (%d) must be a positive multiple of 8", who,
+                c->pages_cap);
+  if ((int64_t)c->pages_cap * c->page_size > (int64_t)1 << 30)
+    return fail(ROCKETKV_INVALID_ARG, "%s: pages_cap * page_size overflows", who);
+  if (need_pools) {
+    if (!c->seq_lens || !c->k_pool || !c->v_pool)
+      return fail(ROCKETKV_INVALID_ARG, "%s: seq_lens / k_pool / v_pool must not be NULL", who);
+    const int64_t tile = (int64_t)c->page_size * kHeadDim;
+    if (c->stride_head < tile || c->stride_page < (int64_t)c->n_kv_heads * tile || c->stride_head % 8 ||
+        c->stride_page % 8)
+      return fail(ROCKETKV_INVALID_ARG,
+                  "%s: strides must be multiples of 8 elements with stride_head >= page_size*head_dim "
+                  "and stride_page >= n_kv_heads*page_size*head_dim", who);
+    if (c->n_phys_pages < 1) return fail(ROCKETKV_INVALID_ARG, "%s: n_phys_pages must be positive", who);
+    if (!c->block_table && c->n_phys_pages < (int64_t)c->batch * c->pages_cap)
+      return fail(ROCKETKV_INVALID_ARG,
+                  "%s: identity block table needs n_phys_pages >= batch * pages_cap", who);
+    if (((uintptr_t)c->k_pool | (uintptr_t)c->v_pool) & 15)
+      return fail(ROCKETKV_INVALID_ARG, "%s: pools must be 16-byte aligned", who);
+  }
+  return ROCKETKV_OK;
+}
+
+CacheView view_of(const rocketkv_cache_t* c) {
+  CacheView v;
+  v.batch = c->batch;
+  v.n_q_heads = c->n_q_heads;
+  v.n_kv_heads = c->n_kv_heads;
+  v.group = c->n_q_heads / c->n_kv_heads;
+  v.page_size = c->page_size;
+  v.pages_cap = c->pages_cap;
+  v.n_phys_pages = c->n_phys_pages;
+  v.stride_page = c->stride_page;
+  v.stride_head = c->stride_head;
+  v.seq_lens = c->seq_lens;
+  v.block_table = c->block_table;
+  v.k_pool = static_cast<bf16_t*>(c->k_pool);
+  v.v_pool = static_cast<bf16_t*>(c->v_pool);
+  return v;
+}
+
+int list_len_for_budget(const rocketkv_cache_t* c, int T) {
+  int64_t need = ((int64_t)T + c->page_size - 1) / c->page_size;
+  if (need < 1) need = 1;
+  if (need > c->pages_cap) need = c->pages_cap;
+  return (int)need;
+}
+
+int check_select_args(const rocketkv_cache_t* c, const void* q, const void* kmax, const void* kmin,
+                      int k1, int T, int n_recent, const char* who) {
+  if (!q || !kmax || !kmin) return fail(ROCKETKV_INVALID_ARG, "%s: q / kmax / kmin must not be NULL", who);
+  if (k1 < 1 || k1 > c->head_dim)
+    return fail(ROCKETKV_INVALID_ARG, "%s: channel_budget %d outside [1, %d]", who, k1, c->head_dim);
+  if (T < 1) return fail(ROCKETKV_INVALID_ARG, "%s: token_budget must be >= 1", who);
+  if (n_recent < 0) return fail(ROCKETKV_INVALID_ARG, "%s: n_recent_pages must be >= 0", who);
+  if (c->pages_cap > ROCKETKV_MAX_PAGES)
+    return fail(ROCKETKV_UNSUPPORTED, "%s: pages_cap %d exceeds %d", who, c->pages_cap, ROCKETKV_MAX_PAGES);
+  if (((uintptr_t)q | (uintptr_t)kmax | (uintptr_t)kmin) & 15)
+    return fail(ROCKETKV_INVALID_ARG, "%s: q / kmax / kmin must be 16-byte aligned", who);
+  return ROCKETKV_OK;
+}
+
+int check_attend_shape(const rocketkv_cache_t* c, const char* who) {
+  if (c->page_size != kAttnPage)
+    return fail(ROCKETKV_UNSUPPORTED, "%s: attention needs page_size %d (got %d)", who, kAttnPage,
+                c->page_size);
+  return ROCKETKV_OK;
+}
+
+struct DecodePlan {
+  AttendPlan attend;
+  int row_len;
+  size_t list_off, attend_off, total;
+};
+
+DecodePlan plan_decode(const rocketkv_cache_t* c, int T) {
+  DecodePlan d;
+  const CacheView v = view_of(c);
+  d.row_len = list_len_for_budget(c, T);
+  d.attend = plan_attend(v, d.row_len);
+  size_t off = 0;
+  d.list_off = off;
+  off += ((size_t)c->batch * c->n_kv_heads * d.row_len * sizeof(int32_t) + 255) / 256 * 256;
+  d.attend_off = off;
+  off += d.attend.total_bytes;
+  d.total = off;
+  return d;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* rocketkv_last_error(void) { return g_err; }
+
+int32_t rocketkv_version(void) { return 100; }
+
+// Internal tuning hook for benchmarks: workgroup target and minimum entries per workgroup of the
+// attention split.  Not part of the documented interface.
+void rocketkv_tune_attend(int32_t target_wgs, int32_t min_chunk) { tune_attend(target_wgs, min_chunk); }
+
+size_t rocketkv_workspace_bytes(int32_t op, const rocketkv_cache_t* cache, int32_t a, int32_t b) {
+  g_err[0] = 0;
+  if (check_cache(cache, false, "rocketkv_workspace_bytes")) return 0;
+  const CacheView v = view_of(cache);
+  switch (op) {
+    case ROCKETKV_OP_HSA_DECODE:
+      if (a < 1) { fail(ROCKETKV_INVALID_ARG, "rocketkv_workspace_bytes: token_budget must be >= 1"); return 0; }
+      return plan_decode(cache, a).total;
+    case ROCKETKV_OP_DENSE_DECODE:
+      return plan_attend(v, cache->pages_cap).total_bytes;
+    case ROCKETKV_OP_ATTEND:
+      if (a < 0) { fail(ROCKETKV_INVALID_ARG, "rocketkv_workspace_bytes: pages_row_len must be >= 0"); return 0; }
+      return plan_attend(v, a > 0 ? a : cache->pages_cap).total_bytes;
+    case ROCKETKV_OP_SNAPKV:
+      if (a < 1 || b <= a) { fail(ROCKETKV_INVALID_ARG, "rocketkv_workspace_bytes: need 1 <= window < keep_budget"); return 0; }
+      return plan_snapkv(v, a, b).total_bytes;
+    default:
+      fail(ROCKETKV_INVALID_ARG, "rocketkv_workspace_bytes: unknown op %d", op);
+      return 0;
+  }
+}
+
+int32_t rocketkv_build_page_summaries(const rocketkv_cache_t* cache, void* kmax, void* kmin,
+                                      int32_t first_page, int32_t n_pages, void* stream) {
+  g_err[0] = 0;
+  if (int r = check_cache(cache, true, "rocketkv_build_page_summaries")) return r;
+  if (!kmax || !kmin) return fail(ROCKETKV_INVALID_ARG, "rocketkv_build_page_summaries: kmax / kmin must not be NULL");
+  if (first_page < 0 || first_page > cache->pages_cap)
+    return fail(ROCKETKV_INVALID_ARG, "rocketkv_build_page_summaries: first_page %d outside [0, %d]",
+                first_page, cache->pages_cap);
+  const hipError_t e = launch_page_summaries(view_of(cache), static_cast<bf16_t*>(kmax),
+                                             static_cast<bf16_t*>(kmin), first_page, n_pages,
+                                             static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? ROCKETKV_OK : hip_fail(e, "rocketkv_build_page_summaries");
+}
+
+int32_t rocketkv_hsa_select(const rocketkv_cache_t* cache, const void* q, const void* kmax,
+                            const void* kmin, int32_t channel_budget, int32_t token_budget,
+                            int32_t n_recent_pages, int32_t* out_pages, int32_t pages_row_len,
+                            int32_t* out_channels, float* out_scores, void* stream) {
+  g_err[0] = 0;
+  const char* who = "rocketkv_hsa_select";
+  if (int r = check_cache(cache, true, who)) return r;
+  if (int r = check_select_args(cache, q, kmax, kmin, channel_budget, token_budget, n_recent_pages, who)) return r;
+  if (!out_pages) return fail(ROCKETKV_INVALID_ARG, "%s: out_pages must not be NULL", who);
+  if (pages_row_len < list_len_for_budget(cache, token_budget))
+    return fail(ROCKETKV_INVALID_ARG, "%s: pages_row_len %d < %d needed for this budget", who,
+                pages_row_len, list_len_for_budget(cache, token_budget));
+  SelectArgs a;
+  a.q = static_cast<const bf16_t*>(q);
+  a.kmax = static_cast<const bf16_t*>(kmax);
+  a.kmin = static_cast<const bf16_t*>(kmin);
+  a.k1 = channel_budget;
+  a.T = token_budget;
+  a.n_recent = n_recent_pages;
+  a.out_pages = out_pages;
+  a.row_len = pages_row_len;
+  a.out_pages2 = nullptr;
+  a.row_len2 = 0;
+  a.out_channels = out_channels;
+  a.out_scores = out_scores;
+  const hipError_t e = launch_hsa_select(view_of(cache), a, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? ROCKETKV_OK : hip_fail(e, who);
+}
+
+int32_t rocketkv_attend(const rocketkv_cache_t* cache, const void* q, const int32_t* pages,
+                        int32_t pages_row_len, void* out, float* out_lse, void* workspace,
+                        size_t workspace_bytes, void* stream) {
+  g_err[0] = 0;
+  const char* who = "rocketkv_attend";
+  if (int r = check_cache(cache, true, who)) return r;
+  if (int r = check_attend_shape(cache, who)) return r;
+  if (!q || !out) return fail(ROCKETKV_INVALID_ARG, "%s: q / out must not be NULL", who);
+  if (((uintptr_t)q) & 15) return fail(ROCKETKV_INVALID_ARG, "%s: q must be 16-byte aligned", who);
+  if (pages && pages_row_len < 1) return fail(ROCKETKV_INVALID_ARG, "%s: pages_row_len must be >= 1", who);
+  const int row_len = pages ? pages_row_len : cache->pages_cap;
+  const CacheView v = view_of(cache);
+  const AttendPlan plan = plan_attend(v, row_len);
+  if (plan.total_bytes && (!workspace || workspace_bytes < plan.total_bytes))
+    return fail(ROCKETKV_WORKSPACE_TOO_SMALL, "%s: workspace %zu bytes < %zu needed", who,
+                workspace ? workspace_bytes : (size_t)0, plan.total_bytes);
+  const hipError_t e = launch_attend(v, static_cast<const bf16_t*>(q), pages, row_len,
+                                     static_cast<bf16_t*>(out), out_lse, workspace, plan,
+                                     static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? ROCKETKV_OK : hip_fail(e, who);
+}
+
+int32_t rocketkv_dense_decode(const rocketkv_cache_t* cache, const void* q, void* out,
+                              float* out_lse, void* workspace, size_t workspace_bytes,
+                              void* stream) {
+  return rocketkv_attend(cache, q, nullptr, 0, out, out_lse, workspace, workspace_bytes, stream);
+}
+
+int32_t rocketkv_hsa_decode(const rocketkv_cache_t* cache, const void* q, const void* kmax,
+                            const void* kmin, int32_t channel_budget, int32_t token_budget,
+                            int32_t n_recent_pages, void* out, float* out_lse,
+                            int32_t* out_pages, int32_t* out_channels, void* workspace,
+                            size_t workspace_bytes, void* stream) {
+  g_err[0] = 0;
+  const char* who = "rocketkv_hsa_decode";
+  if (int r = check_cache(cache, true, who)) return r;
+  if (int r = check_attend_shape(cache, who)) return r;
+  if (int r = check_select_args(cache, q, kmax, kmin, channel_budget, token_budget, n_recent_pages, who)) return r;
+  if (!out) return fail(ROCKETKV_INVALID_ARG, "%s: out must not be NULL", who);
+  const DecodePlan d = plan_decode(cache, token_budget);
+  if (!workspace || workspace_bytes < d.total)
+    return fail(ROCKETKV_WORKSPACE_TOO_SMALL, "%s: workspace %zu bytes < %zu needed", who,
+                workspace ? workspace_bytes : (size_t)0, d.total);
+  if ((uintptr_t)workspace & 255) return fail(ROCKETKV_INVALID_ARG, "%s: workspace must be 256-byte aligned", who);
+  const CacheView v = view_of(cache);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+  SelectArgs a;
+  a.q = static_cast<const bf16_t*>(q);
+  a.kmax = static_cast<const bf16_t*>(kmax);
+  a.kmin = static_cast<const bf16_t*>(kmin);
+  a.k1 = channel_budget;
+  a.T = token_budget;
+  a.n_recent = n_recent_pages;
+  a.out_pages = reinterpret_cast<int32_t*>(ws + d.list_off);
+  a.row_len = d.row_len;
+  a.out_pages2 = out_pages;
+  a.row_len2 = d.row_len;
+  a.out_channels = out_channels;
+  a.out_scores = nullptr;
+  hipError_t e = launch_hsa_select(v, a, st);
+  if (e != hipSuccess) return hip_fail(e, who);
+  e = launch_attend(v, a.q, a.out_pages, d.row_len, static_cast<bf16_t*>(out), out_lse,
+                    ws + d.attend_off, d.attend, st);
+  return e == hipSuccess ? ROCKETKV_OK : hip_fail(e, who);
+}
+
+int32_t rocketkv_append_kv(const rocketkv_cache_t* cache, const void* k_new, const void* v_new,
+                           void* kmax, void* kmin, void* stream) {
+  g_err[0] = 0;
+  const char* who = "rocketkv_append_kv";
+  if (int r = check_cache(cache, true, who)) return r;
+  if (!k_new || !v_new || !kmax || !kmin)
+    return fail(ROCKETKV_INVALID_ARG, "%s: k_new / v_new / kmax / kmin must not be NULL", who);
+  const hipError_t e = launch_append(view_of(cache), static_cast<const bf16_t*>(k_new),
+                                     static_cast<const bf16_t*>(v_new), static_cast<bf16_t*>(kmax),
+                                     static_cast<bf16_t*>(kmin), static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? ROCKETKV_OK : hip_fail(e, who);
+}
+
+int32_t rocketkv_snapkv_compress(const void* q_obs, const rocketkv_cache_t* src, int32_t window,
+                                 int32_t pool_kernel, int32_t keep_budget,
+                                 const rocketkv_cache_t* dst, int32_t* kept_idx, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+  g_err[0] = 0;
+  const char* who = "rocketkv_snapkv_compress";
+  if (int r = check_cache(src, true, who)) return r;
+  if (int r = check_cache(dst, true, who)) return r;
+  if (!q_obs) return fail(ROCKETKV_INVALID_ARG, "%s: q_obs must not be NULL", who);
+  if (((uintptr_t)q_obs) & 15) return fail(ROCKETKV_INVALID_ARG, "%s: q_obs must be 16-byte aligned", who);
+  if (src->batch != dst->batch || src->n_q_heads != dst->n_q_heads || src->n_kv_heads != dst->n_kv_heads ||
+      src->page_size != dst->page_size)
+    return fail(ROCKETKV_INVALID_ARG, "%s: src and dst must agree on batch, heads and page_size", who);
+  if (src->page_size != kAttnPage)
+    return fail(ROCKETKV_UNSUPPORTED, "%s: needs page_size %d (got %d)", who, kAttnPage, src->page_size);
+  if (window < 1 || window > 128 || window % 16 != 0)
+    return fail(window < 1 ? ROCKETKV_INVALID_ARG : ROCKETKV_UNSUPPORTED,
+                "%s: window %d must be a multiple of 16 in [16, 128]", who, window);
+  if ((src->n_q_heads / src->n_kv_heads) * window > 256)
+    return fail(ROCKETKV_UNSUPPORTED, "%s: group size x window (%d) exceeds 256", who,
+                (src->n_q_heads / src->n_kv_heads) * window);
+  if (pool_kernel < 1 || pool_kernel % 2 == 0)
+    return fail(ROCKETKV_INVALID_ARG, "%s: pool_kernel %d must be odd and positive", who, pool_kernel);
+  if (pool_kernel > 1023) return fail(ROCKETKV_UNSUPPORTED, "%s: pool_kernel %d > 1023", who, pool_kernel);
+  if (keep_budget <= window)
+    return fail(ROCKETKV_INVALID_ARG, "%s: keep_budget %d must exceed window %d", who, keep_budget, window);
+  if ((int64_t)dst->pages_cap * dst->page_size < keep_budget)
+    return fail(ROCKETKV_INVALID_ARG, "%s: dst holds %lld tokens per sequence < keep_budget %d", who,
+                (long long)dst->pages_cap * dst->page_size, keep_budget);
+  if (src->k_pool == dst->k_pool || src->v_pool == dst->v_pool)
+    return fail(ROCKETKV_INVALID_ARG, "%s: src and dst pools must be distinct", who);
+  const CacheView sv = view_of(src), dv = view_of(dst);
+  const SnapPlan plan = plan_snapkv(sv, window, keep_budget);
+  if (!workspace || workspace_bytes < plan.total_bytes)
+    return fail(ROCKETKV_WORKSPACE_TOO_SMALL, "%s: workspace %zu bytes < %zu needed", who,
+                workspace ? workspace_bytes : (size_t)0, plan.total_bytes);
+  if ((uintptr_t)workspace & 255) return fail(ROCKETKV_INVALID_ARG, "%s: workspace must be 256-byte aligned", who);
+  const hipError_t e = launch_snapkv(static_cast<const bf16_t*>(q_obs), sv, window, pool_kernel,
+                                     keep_budget, dv, kept_idx, workspace, plan,
+                                     static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? ROCKETKV_OK : hip_fail(e, who);
+}
+
+}  // extern "C"

@@ -1,0 +1,102 @@
+// Internal declarations shared by the gfx950 kernels and the C-ABI front end.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "rocketkv.h"
+
+namespace rkv {
+
+constexpr int kHeadDim = 128;      // channels per head handled by every kernel
+constexpr int kWave = 64;          // CDNA wavefront
+constexpr int kMaxGroup = 16;      // query heads per KV head that fit one MFMA tile
+constexpr int kAttnPage = 16;      // page size of the matrix-core attention path
+
+typedef uint16_t bf16_t;           // raw bf16 bits
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) {
+  return __uint_as_float(((uint32_t)b) << 16);
+}
+__device__ __forceinline__ float bf16lo_to_f32(uint32_t pair) { return __uint_as_float(pair << 16); }
+__device__ __forceinline__ float bf16hi_to_f32(uint32_t pair) { return __uint_as_float(pair & 0xffff0000u); }
+
+// round-to-nearest-even fp32 -> bf16 bits (finite inputs; NaN stays NaN)
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+// Device view of a cache (copied by value into kernel arguments).
+struct CacheView {
+  int32_t batch, n_q_heads, n_kv_heads, group;
+  int32_t page_size, pages_cap;
+  int64_t n_phys_pages, stride_page, stride_head;
+  int32_t* seq_lens;
+  const int32_t* block_table;
+  bf16_t* k_pool;
+  bf16_t* v_pool;
+};
+
+// physical page of logical page p of sequence b, or -1 when absent
+__device__ __forceinline__ int64_t phys_page(const CacheView& c, int b, int p) {
+  int64_t pp = c.block_table ? (int64_t)c.block_table[(int64_t)b * c.pages_cap + p]
+                             : (int64_t)b * c.pages_cap + p;
+  return (pp >= 0 && pp < c.n_phys_pages) ? pp : -1;
+}
+
+__host__ __device__ __forceinline__ int pages_to_pick(int n, int ps, int T) {
+  int P = (n + ps - 1) / ps;
+  if (P == 0) return 0;
+  if (T >= n) return P;
+  int kp = T / ps;
+  if (kp < 1) kp = 1;
+  return kp < P ? kp : P;
+}
+
+// ---- launchers (defined next to their kernels); all return hipError_t ----
+hipError_t launch_page_summaries(const CacheView& c, bf16_t* kmax, bf16_t* kmin, int first_page,
+                                 int n_pages, hipStream_t st);
+
+struct SelectArgs {
+  const bf16_t* q;
+  const bf16_t* kmax;
+  const bf16_t* kmin;
+  int k1, T, n_recent;
+  int32_t* out_pages;     // [units][row_len], may be the workspace list
+  int row_len;
+  int32_t* out_pages2;    // optional second copy (caller's out_pages) with its own row length
+  int row_len2;
+  int32_t* out_channels;  // optional
+  float* out_scores;      // optional
+};
+hipError_t launch_hsa_select(const CacheView& c, const SelectArgs& a, hipStream_t st);
+
+struct AttendPlan {
+  int n_split;        // workgroups per (sequence, KV head)
+  int chunk;          // page-list entries per workgroup
+  size_t partial_off; // workspace offsets (bytes)
+  size_t counter_off;
+  size_t total_bytes;
+};
+AttendPlan plan_attend(const CacheView& c, int row_len);
+hipError_t launch_attend(const CacheView& c, const bf16_t* q, const int32_t* pages, int row_len,
+                         bf16_t* out, float* out_lse, void* ws, const AttendPlan& plan,
+                         hipStream_t st);
+
+hipError_t launch_append(const CacheView& c, const bf16_t* k_new, const bf16_t* v_new, bf16_t* kmax,
+                         bf16_t* kmin, hipStream_t st);
+
+struct SnapPlan {
+  size_t stats_off, votes_off, pooled_off, kept_off, total_bytes;
+  int n_chunks;  // key-axis chunks per (sequence, head group) in the two score passes
+  int chunk_pages;
+};
+SnapPlan plan_snapkv(const CacheView& src, int window, int keep);
+hipError_t launch_snapkv(const bf16_t* q_obs, const CacheView& src, int window, int pool_kernel,
+                         int keep, const CacheView& dst, int32_t* kept_idx, void* ws,
+                         const SnapPlan& plan, hipStream_t st);
+
+}  // namespace rkv

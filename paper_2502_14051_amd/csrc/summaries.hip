@@ -1,0 +1,135 @@
+// HSA Step 1 (Section 3.4 of arXiv 2502.14051): per-page element-wise max / min of the keys,
+// stored channel-major with the page index contiguous, plus the per-token append that keeps the
+// tail page's summary current.
+//
+// Bandwidth-bound: one pass over K.  A wavefront reads a page as coalesced 1 KiB slabs (16 lanes x
+// 16 B cover one 256 B token row, four rows per load), reduces the four row groups with two
+// cross-lane steps, and the workgroup transposes its 64 pages through LDS so that every summary
+// row is written as one 128 B run.
+#include "common.h"
+
+namespace rkv {
+
+constexpr int kSumPages = 64;   // pages per workgroup
+constexpr int kSumPad = 66;     // LDS row pitch in bf16 (33 dwords: conflict-free column writes)
+
+__global__ __launch_bounds__(256) void page_summaries_kernel(CacheView c, bf16_t* __restrict__ kmax,
+                                                             bf16_t* __restrict__ kmin,
+                                                             int first_page, int last_page) {
+  __shared__ bf16_t tmax[kHeadDim * kSumPad];
+  __shared__ bf16_t tmin[kHeadDim * kSumPad];
+  const int unit = blockIdx.y;
+  const int b = unit / c.n_kv_heads, g = unit % c.n_kv_heads;
+  const int n = c.seq_lens[b];
+  const int ps = c.page_size;
+  int P = (n + ps - 1) / ps;
+  if (P > c.pages_cap) P = c.pages_cap;
+  const int p0 = first_page + blockIdx.x * kSumPages;
+  const int pend = min(min(p0 + kSumPages, last_page), P);
+  if (p0 >= pend) return;
+  const int npg = pend - p0;
+  const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  const int tg = lane / 16, cl = lane % 16;
+
+  for (int pl = wave; pl < npg; pl += 4) {
+    const int p = p0 + pl;
+    const int64_t pp = phys_page(c, b, p);
+    const int ntok = min(ps, n - p * ps);
+    float mx[8], mn[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { mx[i] = -INFINITY; mn[i] = INFINITY; }
+    if (pp >= 0) {
+      const bf16_t* tile = c.k_pool + pp * c.stride_page + (int64_t)g * c.stride_head;
+      for (int t = tg; t < ntok; t += 4) {
+        const uint4 v = *reinterpret_cast<const uint4*>(tile + t * kHeadDim + cl * 8);
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float lo = bf16lo_to_f32(w[i]), hi = bf16hi_to_f32(w[i]);
+          mx[2 * i] = fmaxf(mx[2 * i], lo); mn[2 * i] = fminf(mn[2 * i], lo);
+          mx[2 * i + 1] = fmaxf(mx[2 * i + 1], hi); mn[2 * i + 1] = fminf(mn[2 * i + 1], hi);
+        }
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      mx[i] = fmaxf(mx[i], __shfl_xor(mx[i], 16)); mx[i] = fmaxf(mx[i], __shfl_xor(mx[i], 32));
+      mn[i] = fminf(mn[i], __shfl_xor(mn[i], 16)); mn[i] = fminf(mn[i], __shfl_xor(mn[i], 32));
+    }
+    if (tg == 0) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        // an absent page contributes neutral zeros
+        const float a = pp >= 0 ? mx[i] : 0.f, z = pp >= 0 ? mn[i] : 0.f;
+        tmax[(cl * 8 + i) * kSumPad + pl] = (bf16_t)(__float_as_uint(a) >> 16);
+        tmin[(cl * 8 + i) * kSumPad + pl] = (bf16_t)(__float_as_uint(z) >> 16);
+      }
+    }
+  }
+  __syncthreads();
+  const int64_t row0 = (int64_t)unit * kHeadDim;
+  for (int idx = threadIdx.x; idx < kHeadDim * kSumPages; idx += 256) {
+    const int ch = idx / kSumPages, pl = idx % kSumPages;
+    if (pl < npg) {
+      const int64_t o = (row0 + ch) * c.pages_cap + p0 + pl;
+      kmax[o] = tmax[ch * kSumPad + pl];
+      kmin[o] = tmin[ch * kSumPad + pl];
+    }
+  }
+}
+
+hipError_t launch_page_summaries(const CacheView& c, bf16_t* kmax, bf16_t* kmin, int first_page,
+                                 int n_pages, hipStream_t st) {
+  int last = (n_pages < 0) ? c.pages_cap : first_page + n_pages;
+  if (last > c.pages_cap) last = c.pages_cap;
+  if (first_page >= last) return hipSuccess;
+  dim3 grid((last - first_page + kSumPages - 1) / kSumPages, c.batch * c.n_kv_heads);
+  hipLaunchKernelGGL(page_summaries_kernel, grid, dim3(256), 0, st, c, kmax, kmin, first_page, last);
+  return hipGetLastError();
+}
+
+// One generated token per sequence: write its key row and value column into the tail page, fold the
+// key into that page's summary, then bump the length.  One workgroup per sequence; every thread
+// reads the old length before the barrier that precedes the increment.
+__global__ __launch_bounds__(256) void append_kv_kernel(CacheView c, const bf16_t* __restrict__ k_new,
+                                                        const bf16_t* __restrict__ v_new,
+                                                        bf16_t* __restrict__ kmax,
+                                                        bf16_t* __restrict__ kmin) {
+  const int b = blockIdx.x;
+  const int n = c.seq_lens[b];
+  const int ps = c.page_size;
+  const bool room = n < c.pages_cap * ps;
+  if (room) {
+    const int p = n / ps, slot = n % ps;
+    const int64_t pp = phys_page(c, b, p);
+    for (int idx = threadIdx.x; idx < c.n_kv_heads * kHeadDim; idx += 256) {
+      const int g = idx / kHeadDim, ch = idx % kHeadDim;
+      const bf16_t kb = k_new[((int64_t)b * c.n_kv_heads + g) * kHeadDim + ch];
+      const bf16_t vb = v_new[((int64_t)b * c.n_kv_heads + g) * kHeadDim + ch];
+      if (pp >= 0) {
+        const int64_t base = pp * c.stride_page + (int64_t)g * c.stride_head;
+        c.k_pool[base + slot * kHeadDim + ch] = kb;
+        c.v_pool[base + ch * ps + slot] = vb;
+      }
+      const int64_t o = (((int64_t)b * c.n_kv_heads + g) * kHeadDim + ch) * c.pages_cap + p;
+      if (slot == 0) {
+        kmax[o] = kb;
+        kmin[o] = kb;
+      } else {
+        const float x = bf16_to_f32(kb);
+        if (x > bf16_to_f32(kmax[o])) kmax[o] = kb;
+        if (x < bf16_to_f32(kmin[o])) kmin[o] = kb;
+      }
+    }
+  }
+  __syncthreads();
+  if (room && threadIdx.x == 0) c.seq_lens[b] = n + 1;
+}
+
+hipError_t launch_append(const CacheView& c, const bf16_t* k_new, const bf16_t* v_new, bf16_t* kmax,
+                         bf16_t* kmin, hipStream_t st) {
+  hipLaunchKernelGGL(append_kv_kernel, dim3(c.batch), dim3(256), 0, st, c, k_new, v_new, kmax, kmin);
+  return hipGetLastError();
+}
+
+}  // namespace rkv

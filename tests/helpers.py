@@ -1,0 +1,64 @@
+"""Shared pieces of the GPU parity tests: tolerances, the band rule, cache construction."""
+import numpy as np
+
+from paper_2502_14051_amd import workloads as wl
+
+# Tolerances of the build target: attention within 1e-2 absolute/relative of the fp64 oracle for bf16
+# operands with fp32 accumulation; selections exact outside a 1e-3 relative band around the threshold.
+ATOL = 1e-2
+RTOL = 1e-2
+BAND = 1e-3
+
+
+def assert_attention_close(got_bits, want_f64, what=""):
+    got = wl.bf16_bits_to_f64(got_bits)
+    err = np.abs(got - want_f64)
+    lim = ATOL + RTOL * np.abs(want_f64)
+    bad = err > lim
+    assert not bad.any(), f"{what}: {bad.sum()} of {bad.size} outside tolerance, max err {err.max():.4g}"
+
+
+def assert_topk_within_band(values, got_idx, k, what=""):
+    """`got_idx` must be a valid top-k of `values` up to a relative band around the k-th value."""
+    values = np.asarray(values, dtype=np.float64)
+    got = np.asarray([i for i in got_idx if i >= 0])
+    assert len(got) == k, f"{what}: {len(got)} picked, expected {k}"
+    assert len(np.unique(got)) == k, f"{what}: duplicates"
+    assert (np.diff(got) > 0).all(), f"{what}: not ascending"
+    if k == 0 or k == len(values):
+        return
+    finite = values[np.isfinite(values)]
+    theta = np.sort(values)[::-1][k - 1]
+    if not np.isfinite(theta):
+        theta_band = 0.0
+    else:
+        theta_band = BAND * max(abs(theta), 1e-6 * (np.abs(finite).max() if finite.size else 1.0))
+    must = np.nonzero(values > theta + theta_band)[0]
+    never = np.nonzero(values < theta - theta_band)[0]
+    assert np.isin(must, got).all(), f"{what}: missing clear winners {np.setdiff1d(must, got)[:8]}"
+    assert not np.isin(never, got).any(), f"{what}: picked clear losers {np.intersect1d(never, got)[:8]}"
+
+
+def make_block_table(rng, batch, pages_cap, n_phys):
+    """A random injective logical->physical page map."""
+    perm = rng.permutation(n_phys)[:batch * pages_cap]
+    return perm.reshape(batch, pages_cap).astype(np.int32)
+
+
+def to_device_cache(rk, torch, d, n_q_heads, page_size, device, pages_cap=None, shuffle_rng=None,
+                    extra_pages=0):
+    """Upload a generated workload (uint16 arrays) as a paged cache. Returns (cache, q tensor)."""
+    K = wl.from_bits(d["K"], device)
+    V = wl.from_bits(d["V"], device)
+    B, Hkv, n, D = d["K"].shape
+    need = max((n + page_size - 1) // page_size, pages_cap or 0, 1)
+    need = (need + 7) // 8 * 8
+    bt = None
+    n_phys = None
+    if shuffle_rng is not None:
+        n_phys = B * need + extra_pages
+        bt = torch.from_numpy(make_block_table(shuffle_rng, B, need, n_phys)).to(device)
+    cache = rk.pack_cache(K, V, d["seq_lens"], n_q_heads, page_size, pages_cap=need, block_table=bt,
+                          n_phys_pages=n_phys)
+    q = wl.from_bits(d["q"], device)
+    return cache, q

@@ -1,0 +1,128 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every function the
+header declares, and rejects bad arguments before launching anything."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2502_14051_amd import rocketkv as rk
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(rk.LIB_PATH):
+        from paper_2502_14051_amd import build
+        build.build()
+    return rk.lib()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "rocketkv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(rocketkv_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_exports_match_header(L):
+    names = declared_functions()
+    assert set(names) == set(rk.EXPORTS)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_version_and_error_string(L):
+    assert L.rocketkv_version() >= 100
+    assert isinstance(rk.last_error(), str)
+
+
+def fake_cache(**kw):
+    d = dict(batch=2, n_q_heads=32, n_kv_heads=8, head_dim=128, page_size=16, pages_cap=256,
+             n_phys_pages=512, stride_page=8 * 16 * 128, stride_head=16 * 128,
+             seq_lens=0x1000, block_table=None, k_pool=0x10000, v_pool=0x20000)
+    d.update(kw)
+    return rk.CacheStruct(**d)
+
+
+def test_workspace_query_needs_no_device(L):
+    st = fake_cache()
+    n = L.rocketkv_workspace_bytes(rk.OP_HSA_DECODE, C.byref(st), 1024, 0)
+    assert n > 0 and n % 256 == 0
+    assert L.rocketkv_workspace_bytes(rk.OP_DENSE_DECODE, C.byref(st), 0, 0) > 0
+    assert L.rocketkv_workspace_bytes(rk.OP_SNAPKV, C.byref(st), 32, 1024) > 0
+    assert L.rocketkv_workspace_bytes(rk.OP_ATTEND, C.byref(st), 64, 0) > 0
+    assert L.rocketkv_workspace_bytes(99, C.byref(st), 0, 0) == 0 and "unknown op" in rk.last_error()
+    assert L.rocketkv_workspace_bytes(rk.OP_HSA_DECODE, C.byref(st), 0, 0) == 0
+    assert L.rocketkv_workspace_bytes(rk.OP_SNAPKV, C.byref(st), 32, 32) == 0
+
+
+BAD_CACHES = [
+    (dict(n_q_heads=30), rk.INVALID_ARG, "multiple"),
+    (dict(head_dim=64), rk.UNSUPPORTED, "head_dim"),
+    (dict(head_dim=0), rk.INVALID_ARG, "head_dim"),
+    (dict(n_q_heads=8 * 32), rk.UNSUPPORTED, "group size"),
+    (dict(page_size=0), rk.INVALID_ARG, "page_size"),
+    (dict(pages_cap=250), rk.INVALID_ARG, "pages_cap"),
+    (dict(batch=0), rk.INVALID_ARG, "positive"),
+    (dict(k_pool=None), rk.INVALID_ARG, "NULL"),
+    (dict(seq_lens=None), rk.INVALID_ARG, "NULL"),
+    (dict(stride_head=100), rk.INVALID_ARG, "strides"),
+    (dict(n_phys_pages=100), rk.INVALID_ARG, "identity block table"),
+    (dict(k_pool=0x10004), rk.INVALID_ARG, "aligned"),
+]
+
+
+@pytest.mark.parametrize("kw,status,needle", BAD_CACHES)
+def test_bad_cache_is_rejected_before_launch(L, kw, status, needle):
+    st = fake_cache(**kw)
+    r = L.rocketkv_build_page_summaries(C.byref(st), 0x100, 0x200, 0, -1, None)
+    assert r == status, rk.last_error()
+    assert needle in rk.last_error()
+
+
+def test_null_and_range_arguments(L):
+    st = fake_cache()
+    q, kx, kn, out, ws = 0x1000, 0x2000, 0x3000, 0x4000, 0x5000
+    assert L.rocketkv_build_page_summaries(None, kx, kn, 0, -1, None) == rk.INVALID_ARG
+    assert L.rocketkv_build_page_summaries(C.byref(st), None, kn, 0, -1, None) == rk.INVALID_ARG
+    assert L.rocketkv_build_page_summaries(C.byref(st), kx, kn, -1, -1, None) == rk.INVALID_ARG
+    dec = lambda **k: L.rocketkv_hsa_decode(C.byref(st), k.get("q", q), kx, kn, k.get("k1", 32),
+                                            k.get("T", 1024), k.get("nr", 0), k.get("out", out),
+                                            None, None, None, k.get("ws", ws), k.get("wsb", 1 << 30),
+                                            None)
+    assert dec(q=None) == rk.INVALID_ARG
+    assert dec(k1=0) == rk.INVALID_ARG and "channel_budget" in rk.last_error()
+    assert dec(k1=129) == rk.INVALID_ARG
+    assert dec(T=0) == rk.INVALID_ARG and "token_budget" in rk.last_error()
+    assert dec(nr=-1) == rk.INVALID_ARG
+    assert dec(out=None) == rk.INVALID_ARG
+    assert dec(ws=None) == rk.WORKSPACE_TOO_SMALL
+    assert dec(wsb=16) == rk.WORKSPACE_TOO_SMALL and "workspace" in rk.last_error()
+    assert dec(ws=0x5010) == rk.INVALID_ARG and "aligned" in rk.last_error()
+    st3 = fake_cache(page_size=3, stride_head=3 * 128, stride_page=8 * 3 * 128)
+    assert L.rocketkv_attend(C.byref(st3), q, None, 0, out, None, ws, 1 << 30, None) == rk.UNSUPPORTED
+    big = fake_cache(pages_cap=rk.MAX_PAGES + 8, n_phys_pages=4 * (rk.MAX_PAGES + 8))
+    assert L.rocketkv_hsa_select(C.byref(big), q, kx, kn, 32, 1024, 0, 0x6000, 64, None, None,
+                                 None) == rk.UNSUPPORTED
+    assert L.rocketkv_hsa_select(C.byref(st), q, kx, kn, 32, 1024, 0, 0x6000, 8, None, None,
+                                 None) == rk.INVALID_ARG and "pages_row_len" in rk.last_error()
+    assert L.rocketkv_append_kv(C.byref(st), None, q, kx, kn, None) == rk.INVALID_ARG
+
+
+def test_snapkv_argument_checks(L):
+    src = fake_cache(pages_cap=2048, n_phys_pages=4096)
+    dst = fake_cache(k_pool=0x30000, v_pool=0x40000)
+    call = lambda **k: L.rocketkv_snapkv_compress(k.get("qobs", 0x1000), C.byref(k.get("src", src)),
+                                                  k.get("W", 32), k.get("ks", 63), k.get("N", 1024),
+                                                  C.byref(k.get("dst", dst)), None, k.get("ws", 0x5000),
+                                                  k.get("wsb", 1 << 40), None)
+    assert call(qobs=None) == rk.INVALID_ARG
+    assert call(ks=62) == rk.INVALID_ARG and "odd" in rk.last_error()
+    assert call(W=0) == rk.INVALID_ARG
+    assert call(W=24) == rk.UNSUPPORTED
+    assert call(N=32) == rk.INVALID_ARG and "exceed" in rk.last_error()
+    assert call(N=8192) == rk.INVALID_ARG and "dst holds" in rk.last_error()
+    assert call(dst=fake_cache(n_kv_heads=4, k_pool=0x30000, v_pool=0x40000)) == rk.INVALID_ARG
+    assert call(dst=src) == rk.INVALID_ARG and "distinct" in rk.last_error()
+    assert call(wsb=1024) == rk.WORKSPACE_TOO_SMALL
