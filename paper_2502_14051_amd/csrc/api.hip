@@ -7,7 +7,7 @@
 #include "common.h"
 
 namespace rkv {
-void tune_attend(int target_wgs, int min_chunk);
+void tune_attend(int waves, int pairs_per_wave, int max_wgs);
 }
 
 using namespace rkv;
@@ -143,9 +143,11 @@ const char* rocketkv_last_error(void) { return g_err; }
 
 int32_t rocketkv_version(void) { return 100; }
 
-// Internal tuning hook for benchmarks: workgroup target and minimum entries per workgroup of the
-// attention split.  Not part of the documented interface.
-void rocketkv_tune_attend(int32_t target_wgs, int32_t min_chunk) { tune_attend(target_wgs, min_chunk); }
+// Internal tuning hook for experiments: wavefronts per workgroup, page pairs per wavefront and the
+// workgroup cap of the attention split (0 keeps a value).  Not part of the documented interface.
+void rocketkv_tune_attend(int32_t waves, int32_t pairs_per_wave, int32_t max_wgs) {
+  tune_attend(waves, pairs_per_wave, max_wgs);
+}
 
 size_t rocketkv_workspace_bytes(int32_t op, const rocketkv_cache_t* cache, int32_t a, int32_t b) {
   g_err[0] = 0;
@@ -208,6 +210,7 @@ int32_t rocketkv_hsa_select(const rocketkv_cache_t* cache, const void* q, const 
   a.row_len2 = 0;
   a.out_channels = out_channels;
   a.out_scores = out_scores;
+  a.zero_counters = nullptr;
   const hipError_t e = launch_hsa_select(view_of(cache), a, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? ROCKETKV_OK : hip_fail(e, who);
 }
@@ -228,8 +231,9 @@ int32_t rocketkv_attend(const rocketkv_cache_t* cache, const void* q, const int3
   if (plan.total_bytes && (!workspace || workspace_bytes < plan.total_bytes))
     return fail(ROCKETKV_WORKSPACE_TOO_SMALL, "%s: workspace %zu bytes < %zu needed", who,
                 workspace ? workspace_bytes : (size_t)0, plan.total_bytes);
+  if ((uintptr_t)workspace & 255) return fail(ROCKETKV_INVALID_ARG, "%s: workspace must be 256-byte aligned", who);
   const hipError_t e = launch_attend(v, static_cast<const bf16_t*>(q), pages, row_len,
-                                     static_cast<bf16_t*>(out), out_lse, workspace, plan,
+                                     static_cast<bf16_t*>(out), out_lse, workspace, plan, false,
                                      static_cast<hipStream_t>(stream));
   return e == hipSuccess ? ROCKETKV_OK : hip_fail(e, who);
 }
@@ -272,10 +276,11 @@ int32_t rocketkv_hsa_decode(const rocketkv_cache_t* cache, const void* q, const 
   a.row_len2 = d.row_len;
   a.out_channels = out_channels;
   a.out_scores = nullptr;
+  a.zero_counters = d.attend.n_split > 1 ? attend_counters(ws + d.attend_off, d.attend) : nullptr;
   hipError_t e = launch_hsa_select(v, a, st);
   if (e != hipSuccess) return hip_fail(e, who);
   e = launch_attend(v, a.q, a.out_pages, d.row_len, static_cast<bf16_t*>(out), out_lse,
-                    ws + d.attend_off, d.attend, st);
+                    ws + d.attend_off, d.attend, true, st);
   return e == hipSuccess ? ROCKETKV_OK : hip_fail(e, who);
 }
 

@@ -6,14 +6,19 @@
 // (G flop per byte plus the softmax) would not fit the vector ALUs beside the stream, so both
 // contractions run on the matrix cores with the query heads of the group padded to one 16-wide tile:
 //
-//   S[token][head]   = K[token][:] . Q[head][:]       A = K tile (rows: 16 tokens), B = Q^T
+//   S[token][head]   = K[token][:] . Q[head][:]            A = K tile (rows: 16 tokens), B = Q^T
 //   O^T[chan][head] += V^T[chan][token] . P[token][head]   A = V tile (rows: 16 channels), B = P
 //
 // Both products have the head index as the MFMA column, so a lane owns one head throughout: its
-// S values, running max / sum and O accumulators never need to move between lanes.  The V pool is
+// S values, running max / sum and O accumulators never move between lanes.  The V pool is
 // channel-major inside a page precisely so that the contraction index (tokens) is contiguous per lane.
 // A 16x16x32 MFMA contracts 32 tokens: two pages per step, lane group kg contributing tokens
 // 4kg..4kg+3 of each, which is exactly how the S tiles come out of the first product.
+//
+// Latency matters as much as bandwidth here (a layer moves only tens of MB): a wavefront reads the
+// page ids of its whole share with one load, keeps the next page pair's 16 KiB in flight while it
+// works on the current one, and the split partials are handed over with write-through stores and a
+// relaxed device-scope counter instead of cache-flushing fences.
 #include "common.h"
 
 namespace rkv {
@@ -21,17 +26,17 @@ namespace rkv {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kAttnThreads = 256;
-constexpr int kAttnWaves = kAttnThreads / kWave;
 constexpr int kPartialStride = kHeadDim + 2;  // O[128], running max (log2 domain), running sum
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kNegBig = -1.0e30f;
 
-union Frag {
-  uint4 u;
-  bf16x8 v;
-};
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// Fragments are plain ext-vector values (no unions or structs of arrays): anything the compiler
+// cannot split into scalars ends up in scratch memory, which costs far more than the arithmetic.
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 struct AttendArgs {
   const bf16_t* q;
@@ -41,215 +46,306 @@ struct AttendArgs {
   float* out_lse;
   float* partial;        // [units][n_split][G][kPartialStride]
   uint32_t* counters;    // [units]
-  int n_split, chunk;
+  int n_split, chunk, per_wave;
 };
+
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// two fp32 -> packed bf16, round to nearest even (one v_cvt_pk_bf16_f32)
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+  const f32x2 v = {lo, hi};
+  const bf16x2 r = __builtin_convertvector(v, bf16x2);
+  return *reinterpret_cast<const uint32_t*>(&r);
 }
 
-__global__ __launch_bounds__(kAttnThreads) void attend_mfma_kernel(CacheView c, AttendArgs a) {
-  __shared__ float sO[kAttnWaves][kMaxGroup][kHeadDim];
-  __shared__ float sM[kAttnWaves][kMaxGroup];
-  __shared__ float sL[kAttnWaves][kMaxGroup];
+__device__ __forceinline__ void st_agent(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_agent(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Online-softmax step over the NP page pairs of one round.  The vector ALUs issue one wave64
+// instruction per four cycles and share the SIMD with the next wave, so instruction count is what
+// this step is built around: one max / rescale per round instead of per page, the logit scale folded
+// into the exponent's FMA, hardware bf16 packing, and the per-token masks compiled only into the
+// MASK variant, which a round takes when it holds an absent page or the sequence's partial tail page.
+template <int NP, bool MASK>
+__device__ __forceinline__ void softmax_round(const u32x4 (&kf)[NP][2][4], u32x2 (&vf)[NP][2][8],
+                                              const int (&ids)[NP][2], const u32x4 (&qf)[4],
+                                              f32x4 (&O)[8], float& m, float& l, bool have_acc, int n,
+                                              int kg, float sc) {
+  f32x4 acc[NP][2];
+#pragma unroll
+  for (int u = 0; u < NP; ++u)
+#pragma unroll
+    for (int x = 0; x < 2; ++x) {
+      acc[u][x] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        acc[u][x] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kf[u][x][j]), as_bf16x8(qf[j]),
+                                                            acc[u][x], 0, 0, 0);
+    }
+  if (MASK) {
+#pragma unroll
+    for (int u = 0; u < NP; ++u)
+#pragma unroll
+      for (int x = 0; x < 2; ++x) {
+        const int tok0 = ids[u][x] * kAttnPage + kg * 4;
+        const bool gone = ids[u][x] < 0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (gone || tok0 + r >= n) acc[u][x][r] = -INFINITY;
+        // what lies in an absent page, or beyond the sequence end in the tail page, may be anything:
+        // its probability is zero, but 0 x NaN is not, so it is cleared out of the V operand too
+#pragma unroll
+        for (int cb = 0; cb < 8; ++cb) {
+          uint32_t w0 = vf[u][x][cb].x, w1 = vf[u][x][cb].y;
+          if (gone || tok0 + 0 >= n) w0 &= 0xffff0000u;
+          if (gone || tok0 + 1 >= n) w0 &= 0x0000ffffu;
+          if (gone || tok0 + 2 >= n) w1 &= 0xffff0000u;
+          if (gone || tok0 + 3 >= n) w1 &= 0x0000ffffu;
+          vf[u][x][cb] = (u32x2){w0, w1};
+        }
+      }
+  }
+  float mx = -INFINITY;
+#pragma unroll
+  for (int u = 0; u < NP; ++u)
+#pragma unroll
+    for (int x = 0; x < 2; ++x)
+      mx = fmaxf(fmaxf(mx, fmaxf(acc[u][x][0], acc[u][x][1])), fmaxf(acc[u][x][2], acc[u][x][3]));
+  mx = fmaxf(mx, __shfl_xor(mx, 16));
+  mx = fmaxf(mx, __shfl_xor(mx, 32));
+  const float m_new = fmaxf(m, mx * sc);  // running max in the scaled log2 domain
+  if (have_acc) {
+    const float alpha = fast_exp2(m - m_new);
+    l *= alpha;
+    if (__any(alpha != 1.f)) {
+#pragma unroll
+      for (int cb = 0; cb < 8; ++cb) O[cb] *= alpha;
+    }
+  }
+  m = m_new;
+  float psum = 0.f;
+  u32x4 pf[NP];
+#pragma unroll
+  for (int u = 0; u < NP; ++u) {
+    float p[2][4];
+#pragma unroll
+    for (int x = 0; x < 2; ++x)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        p[x][r] = fast_exp2(fmaf(acc[u][x][r], sc, -m_new));
+        psum += p[x][r];
+      }
+    pf[u] = (u32x4){pack_bf16x2(p[0][0], p[0][1]), pack_bf16x2(p[0][2], p[0][3]),
+                    pack_bf16x2(p[1][0], p[1][1]), pack_bf16x2(p[1][2], p[1][3])};
+  }
+  l += psum;
+#pragma unroll
+  for (int u = 0; u < NP; ++u)
+#pragma unroll
+    for (int cb = 0; cb < 8; ++cb) {
+      const u32x4 vv = {vf[u][0][cb].x, vf[u][0][cb].y, vf[u][1][cb].x, vf[u][1][cb].y};
+      O[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vv), as_bf16x8(pf[u]), O[cb], 0, 0, 0);
+    }
+}
+
+template <int WAVES, int NP>
+__global__ __launch_bounds__(WAVES* kWave) __attribute__((amdgpu_waves_per_eu(2)))
+void attend_mfma_kernel(CacheView c, AttendArgs a) {
+  extern __shared__ float smem[];  // sO[WAVES][G][128], sM[WAVES][G], sL[WAVES][G]
   __shared__ int s_last;
+  constexpr int kThreads = WAVES * kWave;
 
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
   const int hn = lane % 16, kg = lane / 16;
   const int unit = blockIdx.y, split = blockIdx.x;
   const int b = unit / c.n_kv_heads, g = unit % c.n_kv_heads;
   const int G = c.group;
+  float* sO = smem;
+  float* sM = smem + WAVES * G * kHeadDim;
+  float* sL = sM + WAVES * G;
   const int n = c.seq_lens[b];
   int P = (n + kAttnPage - 1) / kAttnPage;
   if (P > c.pages_cap) P = c.pages_cap;
 
+  // this wave's share of the list
+  const int e_begin = split * a.chunk;
+  const int e_end = min(e_begin + a.chunk, a.row_len);
+  const int wb = e_begin + wave * a.per_wave;
+  const int we = min(wb + a.per_wave, e_end);
+  const int32_t* list = a.pages ? a.pages + (int64_t)unit * a.row_len : nullptr;
+
+  // first batch of page ids: issued before anything else
+  int my_id = -1;
+  if (wb + lane < we) my_id = list ? list[wb + lane] : wb + lane;
+
   // Q as the B operand of the first product: lane (head hn, group kg) holds channels j*32+kg*8..+7
-  Frag qf[4];
-  if (hn < G) {
-    const bf16_t* qp = a.q + ((int64_t)b * c.n_q_heads + (int64_t)g * G + hn) * kHeadDim + kg * 8;
+  u32x4 qf[4];
+  {
+    const bf16_t* qp = a.q + ((int64_t)b * c.n_q_heads + (int64_t)g * G + (hn < G ? hn : 0)) * kHeadDim + kg * 8;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) qf[j].u = *reinterpret_cast<const uint4*>(qp + j * 32);
-  } else {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) qf[j].u = make_uint4(0, 0, 0, 0);
+    for (int j = 0; j < 4; ++j) {
+      qf[j] = *reinterpret_cast<const u32x4*>(qp + j * 32);
+      if (hn >= G) qf[j] = (u32x4){0u, 0u, 0u, 0u};
+    }
   }
 
   f32x4 O[8];
 #pragma unroll
   for (int cb = 0; cb < 8; ++cb) O[cb] = (f32x4){0.f, 0.f, 0.f, 0.f};
   float m = kNegBig, l = 0.f;
+  bool have_acc = false;
   const float sc = kLog2e * 0.08838834764831845f;  // log2(e) / sqrt(128)
+  // lane-dependent part of every tile address
+  const bf16_t* k_lane = c.k_pool + (int64_t)g * c.stride_head + hn * kHeadDim + kg * 8;
+  const bf16_t* v_lane = c.v_pool + (int64_t)g * c.stride_head + hn * kAttnPage + kg * 4;
 
-  const int e_begin = split * a.chunk;
-  const int e_end = min(e_begin + a.chunk, a.row_len);
-  const int32_t* list = a.pages ? a.pages + (int64_t)unit * a.row_len : nullptr;
-  const int64_t head_off = (int64_t)g * c.stride_head;
-
-  for (int e = e_begin + 2 * wave; e < e_end; e += 2 * kAttnWaves) {
-    int id[2];
-    int64_t pp[2];
-#pragma unroll
-    for (int x = 0; x < 2; ++x) {
-      int v = -1;
-      if (e + x < e_end) v = list ? list[e + x] : e + x;
-      if (v < 0 || v >= P) v = -1;
-      v = __builtin_amdgcn_readfirstlane(v);
-      id[x] = v;
-      pp[x] = v >= 0 ? phys_page(c, b, v) : -1;
-      if (pp[x] < 0) id[x] = -1;
+  for (int base = wb; base < we; base += kWave) {
+    if (base != wb) {
+      my_id = -1;
+      if (base + lane < we) my_id = list ? list[base + lane] : base + lane;
     }
-    if (id[0] < 0 && id[1] < 0) continue;
+    if (my_id >= P) my_id = -1;
+    int64_t my_pp = my_id >= 0 ? phys_page(c, b, my_id) : -1;
+    if (my_pp < 0) my_id = -1;
+    // element offset of this lane's page (an absent page reads page 0 and is masked out)
+    const int64_t my_off = (my_id >= 0 ? my_pp : 0) * c.stride_page;
+    const unsigned long long special = __ballot(my_id < 0 || my_id * kAttnPage + kAttnPage > n);
+    const int cnt = min(kWave, we - base);
+    const int npairs = (cnt + 1) / 2;
 
-    Frag kf[2][4];
-    uint2 vf[2][8];
+    // NP pairs per round: all their loads go out back to back (K tiles first, the first product
+    // needs them first), then one softmax step consumes them.  Nothing is carried between rounds in
+    // registers; the other wavefronts of the SIMD cover the gap.
+    for (int i = 0; i < npairs; i += NP) {
+      u32x4 kf[NP][2][4];
+      u32x2 vf[NP][2][8];
+      int ids[NP][2];
+      const bf16_t* vt[NP][2];
+      const int e0 = __builtin_amdgcn_readfirstlane(2 * i);
 #pragma unroll
-    for (int x = 0; x < 2; ++x) {
-      if (id[x] >= 0) {
-        const bf16_t* kt = c.k_pool + pp[x] * c.stride_page + head_off + hn * kHeadDim + kg * 8;
+      for (int u = 0; u < NP; ++u)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) kf[x][j].u = *reinterpret_cast<const uint4*>(kt + j * 32);
-        const bf16_t* vt = c.v_pool + pp[x] * c.stride_page + head_off + hn * kAttnPage + kg * 4;
+        for (int x = 0; x < 2; ++x) {
+          const int e = (e0 + 2 * u + x) & (kWave - 1);
+          ids[u][x] = 2 * (i + u) + x < kWave ? __builtin_amdgcn_readlane(my_id, e) : -1;
+          const int64_t off = ((int64_t)__builtin_amdgcn_readlane((int)(my_off >> 32), e) << 32) |
+                              (uint32_t)__builtin_amdgcn_readlane((int)(my_off & 0xffffffff), e);
+          const bf16_t* kt = k_lane + off;
+          vt[u][x] = v_lane + off;
 #pragma unroll
-        for (int cb = 0; cb < 8; ++cb)
-          vf[x][cb] = *reinterpret_cast<const uint2*>(vt + cb * 16 * kAttnPage);
-      } else {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) kf[x][j].u = make_uint4(0, 0, 0, 0);
-#pragma unroll
-        for (int cb = 0; cb < 8; ++cb) vf[x][cb] = make_uint2(0, 0);
-      }
-    }
-
-    // S tiles: s[x][r] = logit of token id[x]*16 + 4kg + r for head hn
-    float s[2][4];
-    float mx = kNegBig;
-#pragma unroll
-    for (int x = 0; x < 2; ++x) {
-      f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[x][j].v, qf[j].v, acc, 0, 0, 0);
-      const int tok0 = id[x] * kAttnPage + kg * 4;
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const bool ok = id[x] >= 0 && tok0 + r < n;
-        s[x][r] = ok ? acc[r] * sc : -INFINITY;
-        mx = fmaxf(mx, s[x][r]);
-      }
-      // a partial tail page may hold anything beyond the sequence end: keep it out of P.V
-      if (id[x] >= 0 && id[x] * kAttnPage + kAttnPage > n) {
-#pragma unroll
-        for (int cb = 0; cb < 8; ++cb) {
-          uint32_t w0 = vf[x][cb].x, w1 = vf[x][cb].y;
-          if (tok0 + 0 >= n) w0 &= 0xffff0000u;
-          if (tok0 + 1 >= n) w0 &= 0x0000ffffu;
-          if (tok0 + 2 >= n) w1 &= 0xffff0000u;
-          if (tok0 + 3 >= n) w1 &= 0x0000ffffu;
-          vf[x][cb] = make_uint2(w0, w1);
+          for (int j = 0; j < 4; ++j) kf[u][x][j] = *reinterpret_cast<const u32x4*>(kt + j * 32);
         }
-      }
-    }
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m, mx);
-    const float alpha = fast_exp2(m - m_new);
-    m = m_new;
-    float p[2][4], psum = 0.f;
 #pragma unroll
-    for (int x = 0; x < 2; ++x)
+      for (int u = 0; u < NP; ++u)
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        p[x][r] = fast_exp2(s[x][r] - m_new);
-        psum += p[x][r];
-      }
-    l = l * alpha + psum;
+        for (int x = 0; x < 2; ++x)
 #pragma unroll
-    for (int cb = 0; cb < 8; ++cb) O[cb] *= alpha;
-    Frag pf;
-    pf.u = make_uint4(pack_bf16x2(p[0][0], p[0][1]), pack_bf16x2(p[0][2], p[0][3]),
-                      pack_bf16x2(p[1][0], p[1][1]), pack_bf16x2(p[1][2], p[1][3]));
-#pragma unroll
-    for (int cb = 0; cb < 8; ++cb) {
-      Frag vv;
-      vv.u = make_uint4(vf[0][cb].x, vf[0][cb].y, vf[1][cb].x, vf[1][cb].y);
-      O[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vv.v, pf.v, O[cb], 0, 0, 0);
+          for (int cb = 0; cb < 8; ++cb)
+            vf[u][x][cb] = *reinterpret_cast<const u32x2*>(vt[u][x] + cb * 16 * kAttnPage);
+      const bool masked = ((special >> e0) & ((1ull << (2 * NP)) - 1ull)) != 0ull || e0 + 2 * NP > kWave;
+      if (!masked)
+        softmax_round<NP, false>(kf, vf, ids, qf, O, m, l, have_acc, n, kg, sc);
+      else
+        softmax_round<NP, true>(kf, vf, ids, qf, O, m, l, have_acc, n, kg, sc);
+      have_acc = true;
     }
   }
   l += __shfl_xor(l, 16);
   l += __shfl_xor(l, 32);
 
-  // ---- merge the four waves through LDS --------------------------------------------------------
+  // ---- merge the waves through LDS ---------------------------------------------------------------
   if (hn < G) {
 #pragma unroll
     for (int cb = 0; cb < 8; ++cb)
-      *reinterpret_cast<float4*>(&sO[wave][hn][cb * 16 + kg * 4]) =
+      *reinterpret_cast<float4*>(&sO[(wave * G + hn) * kHeadDim + cb * 16 + kg * 4]) =
           make_float4(O[cb][0], O[cb][1], O[cb][2], O[cb][3]);
     if (kg == 0) {
-      sM[wave][hn] = m;
-      sL[wave][hn] = l;
+      sM[wave * G + hn] = m;
+      sL[wave * G + hn] = l;
     }
   }
   __syncthreads();
-  const int ch = tid % kHeadDim;
   const int64_t out_base = ((int64_t)b * c.n_q_heads + (int64_t)g * G) * kHeadDim;
-  for (int h = tid / kHeadDim; h < G; h += kAttnThreads / kHeadDim) {
-    float M = sM[0][h];
+  for (int idx = tid; idx < G * kHeadDim; idx += kThreads) {
+    const int h = idx / kHeadDim, ch = idx % kHeadDim;
+    float M = sM[h];
 #pragma unroll
-    for (int w = 1; w < kAttnWaves; ++w) M = fmaxf(M, sM[w][h]);
+    for (int w = 1; w < WAVES; ++w) M = fmaxf(M, sM[w * G + h]);
     float num = 0.f, den = 0.f;
 #pragma unroll
-    for (int w = 0; w < kAttnWaves; ++w) {
-      const float f = fast_exp2(sM[w][h] - M);
-      num += f * sO[w][h][ch];
-      den += f * sL[w][h];
+    for (int w = 0; w < WAVES; ++w) {
+      const float f = fast_exp2(sM[w * G + h] - M);
+      num += f * sO[(w * G + h) * kHeadDim + ch];
+      den += f * sL[w * G + h];
     }
     if (a.n_split == 1) {
-      a.out[out_base + h * kHeadDim + ch] = f32_to_bf16(den > 0.f ? num / den : 0.f);
+      a.out[out_base + idx] = f32_to_bf16(den > 0.f ? num / den : 0.f);
       if (ch == 0 && a.out_lse)
         a.out_lse[(int64_t)b * c.n_q_heads + g * G + h] = den > 0.f ? (M + log2f(den)) * kLn2 : -INFINITY;
     } else {
+      // write-through stores: visible device-wide once acknowledged, no cache flush needed
       float* pr = a.partial + (((int64_t)unit * a.n_split + split) * G + h) * kPartialStride;
-      pr[ch] = num;
+      st_agent(pr + ch, num);
       if (ch == 0) {
-        pr[kHeadDim] = M;
-        pr[kHeadDim + 1] = den;
+        st_agent(pr + kHeadDim, M);
+        st_agent(pr + kHeadDim + 1, den);
       }
     }
   }
   if (a.n_split == 1) return;
 
   // ---- last workgroup of the unit merges the split partials --------------------------------------
-  __threadfence();
-  __syncthreads();
+  __syncthreads();  // every store of this workgroup has been acknowledged
   if (tid == 0) {
-    const uint32_t old = atomicAdd(&a.counters[unit], 1u);
+    const uint32_t old = __hip_atomic_fetch_add(&a.counters[unit], 1u, __ATOMIC_RELAXED,
+                                                __HIP_MEMORY_SCOPE_AGENT);
     s_last = (old == (uint32_t)a.n_split - 1u);
   }
   __syncthreads();
   if (!s_last) return;
-  __threadfence();
-  for (int h = tid / kHeadDim; h < G; h += kAttnThreads / kHeadDim) {
+  for (int idx = tid; idx < G * kHeadDim; idx += kThreads) {
+    const int h = idx / kHeadDim, ch = idx % kHeadDim;
     const float* pr = a.partial + ((int64_t)unit * a.n_split * G + h) * kPartialStride;
     const int64_t sstride = (int64_t)G * kPartialStride;
-    float M = kNegBig;
-    for (int s2 = 0; s2 < a.n_split; ++s2)
-      M = fmaxf(M, __hip_atomic_load(pr + s2 * sstride + kHeadDim, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-    float num = 0.f, den = 0.f;
-    for (int s2 = 0; s2 < a.n_split; ++s2) {
-      const float ms = __hip_atomic_load(pr + s2 * sstride + kHeadDim, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      const float ls = __hip_atomic_load(pr + s2 * sstride + kHeadDim + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      const float os = __hip_atomic_load(pr + s2 * sstride + ch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      const float f = fast_exp2(ms - M);
-      num += f * os;
-      den += f * ls;
+    float M = kNegBig, num = 0.f, den = 0.f;
+    // eight splits per batch, every load of a batch in flight before the first use
+    for (int s0 = 0; s0 < a.n_split; s0 += 8) {
+      float ms[8], ls[8], os[8];
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        const bool ok = s0 + t < a.n_split;
+        const float* ps = pr + (ok ? s0 + t : s0) * sstride;
+        ms[t] = ld_agent(ps + kHeadDim);
+        ls[t] = ld_agent(ps + kHeadDim + 1);
+        os[t] = ld_agent(ps + ch);
+        if (!ok) { ms[t] = kNegBig; ls[t] = 0.f; os[t] = 0.f; }
+      }
+      float Mb = M;
+#pragma unroll
+      for (int t = 0; t < 8; ++t) Mb = fmaxf(Mb, ms[t]);
+      const float fo = fast_exp2(M - Mb);
+      num *= fo;
+      den *= fo;
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        const float f = fast_exp2(ms[t] - Mb);
+        num += f * os[t];
+        den += f * ls[t];
+      }
+      M = Mb;
     }
-    a.out[out_base + h * kHeadDim + ch] = f32_to_bf16(den > 0.f ? num / den : 0.f);
+    a.out[out_base + idx] = f32_to_bf16(den > 0.f ? num / den : 0.f);
     if (ch == 0 && a.out_lse)
       a.out_lse[(int64_t)b * c.n_q_heads + g * G + h] = den > 0.f ? (M + log2f(den)) * kLn2 : -INFINITY;
   }
-  if (tid == 0) a.counters[unit] = 0;  // leave the counter ready for the next call
+  if (tid == 0) __hip_atomic_store(&a.counters[unit], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 __global__ void zero_u32_kernel(uint32_t* p, int n) {
@@ -257,25 +353,35 @@ __global__ void zero_u32_kernel(uint32_t* p, int n) {
   if (i < n) p[i] = 0;
 }
 
-static int g_target_wgs = 512;    // workgroups aimed for along (units x splits)
-static int g_min_chunk = 8;       // page-list entries per workgroup, multiple of 8
+// ---- launch geometry ---------------------------------------------------------------------------------
+static int g_waves = 4;            // wavefronts per workgroup (4 or 8)
+static int g_pairs_per_wave = 2;   // page pairs a wavefront aims to own
+static int g_max_wgs = 2048;       // cap on units x splits (keeps the dense case from over-splitting)
 
-void tune_attend(int target_wgs, int min_chunk) {
-  if (target_wgs > 0) g_target_wgs = target_wgs;
-  if (min_chunk > 0) g_min_chunk = (min_chunk + 7) / 8 * 8;
+void tune_attend(int waves, int pairs_per_wave, int max_wgs) {
+  if (waves == 4 || waves == 8) g_waves = waves;
+  if (pairs_per_wave > 0) g_pairs_per_wave = pairs_per_wave;
+  if (max_wgs > 0) g_max_wgs = max_wgs;
 }
 
 AttendPlan plan_attend(const CacheView& c, int row_len) {
   AttendPlan p;
   const int units = c.batch * c.n_kv_heads;
-  int want = (g_target_wgs + units - 1) / units;
-  const int max_split = (row_len + g_min_chunk - 1) / g_min_chunk;
-  if (want > max_split) want = max_split;
-  if (want < 1) want = 1;
-  int chunk = (row_len + want - 1) / want;
-  chunk = (chunk + 7) / 8 * 8;
-  if (chunk < g_min_chunk) chunk = g_min_chunk;
+  int waves = g_waves;
+  // the LDS merge buffer must fit 64 KiB: waves * G * 130 floats
+  while (waves > 4 && (size_t)waves * c.group * (kHeadDim + 2) * sizeof(float) > 60 * 1024) waves /= 2;
+  p.waves = waves;
+  const int per_wg = 2 * g_pairs_per_wave * waves;  // entries one workgroup wants
+  int n_split = (row_len + per_wg - 1) / per_wg;
+  const int max_split = g_max_wgs / units > 1 ? g_max_wgs / units : 1;
+  if (n_split > max_split) n_split = max_split;
+  if (n_split < 1) n_split = 1;
+  int chunk = (row_len + n_split - 1) / n_split;
+  int per_wave = (chunk + waves - 1) / waves;
+  per_wave = (per_wave + 1) / 2 * 2;  // whole pairs
+  chunk = per_wave * waves;
   p.chunk = chunk;
+  p.per_wave = per_wave;
   p.n_split = (row_len + chunk - 1) / chunk;
   if (p.n_split < 1) p.n_split = 1;
   size_t off = 0;
@@ -287,9 +393,13 @@ AttendPlan plan_attend(const CacheView& c, int row_len) {
   return p;
 }
 
+uint32_t* attend_counters(void* ws, const AttendPlan& plan) {
+  return reinterpret_cast<uint32_t*>(static_cast<char*>(ws) + plan.counter_off);
+}
+
 hipError_t launch_attend(const CacheView& c, const bf16_t* q, const int32_t* pages, int row_len,
                          bf16_t* out, float* out_lse, void* ws, const AttendPlan& plan,
-                         hipStream_t st) {
+                         bool counters_are_zero, hipStream_t st) {
   const int units = c.batch * c.n_kv_heads;
   AttendArgs a;
   a.q = q;
@@ -298,13 +408,19 @@ hipError_t launch_attend(const CacheView& c, const bf16_t* q, const int32_t* pag
   a.out = out;
   a.out_lse = out_lse;
   a.partial = reinterpret_cast<float*>(static_cast<char*>(ws) + plan.partial_off);
-  a.counters = reinterpret_cast<uint32_t*>(static_cast<char*>(ws) + plan.counter_off);
+  a.counters = attend_counters(ws, plan);
   a.n_split = plan.n_split;
   a.chunk = plan.chunk;
-  if (plan.n_split > 1) {
+  a.per_wave = plan.per_wave;
+  if (plan.n_split > 1 && !counters_are_zero) {
     hipLaunchKernelGGL(zero_u32_kernel, dim3((units + 255) / 256), dim3(256), 0, st, a.counters, units);
   }
-  hipLaunchKernelGGL(attend_mfma_kernel, dim3(plan.n_split, units), dim3(kAttnThreads), 0, st, c, a);
+  const size_t smem = (size_t)plan.waves * c.group * (kHeadDim + 2) * sizeof(float);
+  const dim3 grid(plan.n_split, units);
+  if (plan.waves == 8)
+    hipLaunchKernelGGL((attend_mfma_kernel<8, 1>), grid, dim3(8 * kWave), smem, st, c, a);
+  else
+    hipLaunchKernelGGL((attend_mfma_kernel<4, 1>), grid, dim3(4 * kWave), smem, st, c, a);
   return hipGetLastError();
 }
 

@@ -71,12 +71,15 @@ struct SelectArgs {
   int row_len2;
   int32_t* out_channels;  // optional
   float* out_scores;      // optional
+  uint32_t* zero_counters;  // optional [units]: cleared for the attention kernel that follows
 };
 hipError_t launch_hsa_select(const CacheView& c, const SelectArgs& a, hipStream_t st);
 
 struct AttendPlan {
+  int waves;          // wavefronts per workgroup (4 or 8)
   int n_split;        // workgroups per (sequence, KV head)
   int chunk;          // page-list entries per workgroup
+  int per_wave;       // page-list entries per wavefront (even)
   size_t partial_off; // workspace offsets (bytes)
   size_t counter_off;
   size_t total_bytes;
@@ -84,7 +87,8 @@ struct AttendPlan {
 AttendPlan plan_attend(const CacheView& c, int row_len);
 hipError_t launch_attend(const CacheView& c, const bf16_t* q, const int32_t* pages, int row_len,
                          bf16_t* out, float* out_lse, void* ws, const AttendPlan& plan,
-                         hipStream_t st);
+                         bool counters_are_zero, hipStream_t st);
+uint32_t* attend_counters(void* ws, const AttendPlan& plan);
 
 hipError_t launch_append(const CacheView& c, const bf16_t* k_new, const bf16_t* v_new, bf16_t* kmax,
                          bf16_t* kmin, hipStream_t st);

@@ -36,13 +36,15 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* wsum /
 
 __global__ __launch_bounds__(kSelThreads) void hsa_select_kernel(CacheView c, SelectArgs a) {
   extern __shared__ uint32_t keys[];  // [ceil8(P)] order keys of the page scores
-  __shared__ float s_abs[kHeadDim], s_sum[kHeadDim];
+  __shared__ __align__(16) float s_abs[kHeadDim];
+  __shared__ float s_sum[kHeadDim];
   __shared__ int s_chan[kHeadDim];
   __shared__ float s_wgt[kHeadDim];
   __shared__ float partial[kSelThreads * 8];
-  __shared__ uint32_t hist[256];
+  __shared__ __align__(16) uint32_t hist[4][256];  // one histogram per radix pass
+  __shared__ int s_rank[kSelThreads];
   __shared__ uint32_t wsum[4];
-  __shared__ uint32_t sh_bucket, sh_k, sh_cnt0;
+  __shared__ uint32_t sh_cnt0;
 
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
   const int unit = blockIdx.x;
@@ -55,6 +57,10 @@ __global__ __launch_bounds__(kSelThreads) void hsa_select_kernel(CacheView c, Se
   if (kp > P) kp = P;
   if (kp > a.row_len) kp = a.row_len;
 
+  if (a.zero_counters && tid == 0) a.zero_counters[unit] = 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) hist[i][tid] = 0;
+
   // -1 padding of the list rows beyond kp
   for (int i = kp + tid; i < a.row_len; i += kSelThreads) a.out_pages[(int64_t)unit * a.row_len + i] = -1;
   if (a.out_pages2)
@@ -64,26 +70,42 @@ __global__ __launch_bounds__(kSelThreads) void hsa_select_kernel(CacheView c, Se
   if (tid < kHeadDim) {
     float sa = 0.f, ss = 0.f;
     const bf16_t* qp = a.q + ((int64_t)b * c.n_q_heads + (int64_t)g * G) * kHeadDim + tid;
-    for (int h = 0; h < G; ++h) {
-      const float x = bf16_to_f32(qp[h * kHeadDim]);
-      sa += fabsf(x);
-      ss += x;
+    bf16_t qv[kMaxGroup];
+#pragma unroll
+    for (int h = 0; h < kMaxGroup; ++h) qv[h] = h < G ? qp[h * kHeadDim] : (bf16_t)0;
+#pragma unroll
+    for (int h = 0; h < kMaxGroup; ++h) {
+      if (h < G) {
+        const float x = bf16_to_f32(qv[h]);
+        sa += fabsf(x);
+        ss += x;
+      }
     }
     s_abs[tid] = sa;
     s_sum[tid] = ss;
   }
   __syncthreads();
   // ---- i1: rank by counting, compact ascending --------------------------------------------------
-  bool sel = false;
-  if (tid < kHeadDim) {
-    const float mine = s_abs[tid];
+  // every thread ranks channel (tid mod 128) against one half of the channels, 4 at a time
+  {
+    const int ch = tid & (kHeadDim - 1), half = tid >> 7;
+    const float mine = s_abs[ch];
+    const float4* v4 = reinterpret_cast<const float4*>(s_abs + half * 64);
     int rank = 0;
-    for (int o = 0; o < kHeadDim; ++o) {
-      const float v = s_abs[o];
-      rank += (v > mine) || (v == mine && o < tid);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const float4 v = v4[i];
+      const int o = half * 64 + 4 * i;
+      rank += (v.x > mine) || (v.x == mine && o + 0 < ch);
+      rank += (v.y > mine) || (v.y == mine && o + 1 < ch);
+      rank += (v.z > mine) || (v.z == mine && o + 2 < ch);
+      rank += (v.w > mine) || (v.w == mine && o + 3 < ch);
     }
-    sel = rank < a.k1;
+    s_rank[tid] = rank;
   }
+  __syncthreads();
+  bool sel = false;
+  if (tid < kHeadDim) sel = s_rank[tid] + s_rank[tid + kHeadDim] < a.k1;
   const unsigned long long bal = __ballot(sel);
   if (tid == 0) sh_cnt0 = (uint32_t)__popcll(bal);
   __syncthreads();
@@ -108,15 +130,29 @@ __global__ __launch_bounds__(kSelThreads) void hsa_select_kernel(CacheView c, Se
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i] = 0.f;
     if (o < n_oct) {
-      for (int j = r; j < a.k1; j += R) {
-        const float w = s_wgt[j];
-        const bf16_t* row = (w >= 0.f ? a.kmax : a.kmin) + (rows + s_chan[j]) * c.pages_cap + o * 8;
-        const uint4 v = *reinterpret_cast<const uint4*>(row);
-        const uint32_t x[4] = {v.x, v.y, v.z, v.w};
+      // eight rows per batch: all loads of a batch are in flight before the first is used
+      for (int j0 = r; j0 < a.k1; j0 += 8 * R) {
+        uint4 v[8];
+        float w[8];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          acc[2 * i] = fmaf(w, bf16lo_to_f32(x[i]), acc[2 * i]);
-          acc[2 * i + 1] = fmaf(w, bf16hi_to_f32(x[i]), acc[2 * i + 1]);
+        for (int t = 0; t < 8; ++t) {
+          const int j = j0 + t * R;
+          w[t] = 0.f;
+          v[t] = make_uint4(0, 0, 0, 0);
+          if (j < a.k1) {
+            w[t] = s_wgt[j];
+            const bf16_t* row = (w[t] >= 0.f ? a.kmax : a.kmin) + (rows + s_chan[j]) * c.pages_cap + o * 8;
+            v[t] = *reinterpret_cast<const uint4*>(row);
+          }
+        }
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+          const uint32_t x[4] = {v[t].x, v[t].y, v[t].z, v[t].w};
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            acc[2 * i] = fmaf(w[t], bf16lo_to_f32(x[i]), acc[2 * i]);
+            acc[2 * i + 1] = fmaf(w[t], bf16hi_to_f32(x[i]), acc[2 * i + 1]);
+          }
         }
       }
     }
@@ -138,15 +174,28 @@ __global__ __launch_bounds__(kSelThreads) void hsa_select_kernel(CacheView c, Se
       float acc[8];
 #pragma unroll
       for (int i = 0; i < 8; ++i) acc[i] = 0.f;
-      for (int j = 0; j < a.k1; ++j) {
-        const float w = s_wgt[j];
-        const bf16_t* row = (w >= 0.f ? a.kmax : a.kmin) + (rows + s_chan[j]) * c.pages_cap + o * 8;
-        const uint4 v = *reinterpret_cast<const uint4*>(row);
-        const uint32_t x[4] = {v.x, v.y, v.z, v.w};
+      for (int j0 = 0; j0 < a.k1; j0 += 8) {
+        uint4 v[8];
+        float w[8];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          acc[2 * i] = fmaf(w, bf16lo_to_f32(x[i]), acc[2 * i]);
-          acc[2 * i + 1] = fmaf(w, bf16hi_to_f32(x[i]), acc[2 * i + 1]);
+        for (int t = 0; t < 8; ++t) {
+          const int j = j0 + t;
+          w[t] = 0.f;
+          v[t] = make_uint4(0, 0, 0, 0);
+          if (j < a.k1) {
+            w[t] = s_wgt[j];
+            const bf16_t* row = (w[t] >= 0.f ? a.kmax : a.kmin) + (rows + s_chan[j]) * c.pages_cap + o * 8;
+            v[t] = *reinterpret_cast<const uint4*>(row);
+          }
+        }
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+          const uint32_t x[4] = {v[t].x, v[t].y, v[t].z, v[t].w};
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            acc[2 * i] = fmaf(w[t], bf16lo_to_f32(x[i]), acc[2 * i]);
+            acc[2 * i + 1] = fmaf(w[t], bf16hi_to_f32(x[i]), acc[2 * i + 1]);
+          }
         }
       }
 #pragma unroll
@@ -168,34 +217,41 @@ __global__ __launch_bounds__(kSelThreads) void hsa_select_kernel(CacheView c, Se
     uint32_t prefix = 0, mask = 0, k = (uint32_t)kp;
     for (int pass = 0; pass < 4; ++pass) {
       const int shift = 24 - 8 * pass;
-      hist[tid] = 0;
-      __syncthreads();
       for (int p = tid; p < P; p += kSelThreads) {
         const uint32_t key = keys[p];
-        if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+        if ((key & mask) == prefix) atomicAdd(&hist[pass][(key >> shift) & 255u], 1u);
       }
       __syncthreads();
-      // suffix sums over the 256 bins: thread t owns bin t
-      const uint32_t v = hist[tid];
-      uint32_t inc = v;
+      // every wavefront finds the bucket holding the k-th largest on its own (no broadcast needed):
+      // lane L owns bins 4L..4L+3; suffix sums inside the lane, then across lanes
+      const uint4 h = *reinterpret_cast<const uint4*>(&hist[pass][4 * lane]);
+      const uint32_t s3 = h.w, s2 = h.z + s3, s1 = h.y + s2, s0 = h.x + s1;
+      uint32_t inc = s0;
 #pragma unroll
       for (int off = 1; off < kWave; off <<= 1) {
         const uint32_t y = __shfl_down(inc, off);
         if (lane + off < kWave) inc += y;
       }
-      if (lane == 0) wsum[wave] = inc;
-      __syncthreads();
-      for (int w = wave + 1; w < 4; ++w) inc += wsum[w];
-      const uint32_t exc = inc - v;
-      if (exc < k && k <= inc) {
-        sh_bucket = (uint32_t)tid;
-        sh_k = k - exc;
+      const uint32_t above = inc - s0;  // keys in bins of higher lanes
+      // bin j of this lane: inclusive suffix = above + s_j, exclusive = that minus its own count
+      const uint32_t in[4] = {above + s0, above + s1, above + s2, above + s3};
+      const uint32_t hc[4] = {h.x, h.y, h.z, h.w};
+      int found = -1;
+      uint32_t newk = 0;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const uint32_t exc = in[j] - hc[j];
+        if (exc < k && k <= in[j]) {
+          found = 4 * lane + j;
+          newk = k - exc;
+        }
       }
-      __syncthreads();
-      prefix |= sh_bucket << shift;
+      const unsigned long long who = __ballot(found >= 0);
+      const int src = __ffsll((long long)who) - 1;
+      const uint32_t bucket = (uint32_t)__shfl(found, src);
+      k = (uint32_t)__shfl((int)newk, src);
+      prefix |= bucket << shift;
       mask |= 0xffu << shift;
-      k = sh_k;
-      __syncthreads();
     }
     tau = prefix;
     need_eq = k;

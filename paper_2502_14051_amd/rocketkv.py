@@ -51,6 +51,9 @@ def lib():
     """Load the native library (built by ``paper_2502_14051_amd.build``)."""
     global _lib
     if _lib is None:
+        # torch first: the library must bind to the HIP runtime torch has already loaded, so that
+        # streams and device pointers are shared with it
+        import torch  # noqa: F401
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2502_14051_amd.build` "
                               "(or __graft_entry__.build()) first; there is no fallback path")
@@ -78,7 +81,7 @@ def lib():
         L.rocketkv_version.restype = i32
         L.rocketkv_version.argtypes = []
         L.rocketkv_tune_attend.restype = None
-        L.rocketkv_tune_attend.argtypes = [i32, i32]
+        L.rocketkv_tune_attend.argtypes = [i32, i32, i32]
         _lib = L
     return _lib
 
@@ -269,5 +272,5 @@ def pages_row_len(cache: Cache, token_budget: int) -> int:
     return max(1, min(cache.pages_cap, (token_budget + cache.page_size - 1) // cache.page_size))
 
 
-def tune_attend(target_wgs: int = 0, min_chunk: int = 0):
-    lib().rocketkv_tune_attend(target_wgs, min_chunk)
+def tune_attend(waves: int = 0, pairs_per_wave: int = 0, max_wgs: int = 0):
+    lib().rocketkv_tune_attend(waves, pairs_per_wave, max_wgs)
