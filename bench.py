@@ -43,6 +43,9 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--kernel-reps", type=int, default=20)
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="also run one plain device copy of this many MiB (a known-size reference "
+                         "for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
 
 
@@ -113,6 +116,14 @@ def main():
             del src
     torch.cuda.synchronize()
     t_setup = time.time() - t_setup
+
+    if args.calib_copy_mib:
+        src_c = torch.ones((args.calib_copy_mib << 20,), dtype=torch.uint8, device=dev)
+        dst_c = torch.empty_like(src_c)
+        torch.cuda.synchronize()
+        dst_c.copy_(src_c)
+        torch.cuda.synchronize()
+        del src_c, dst_c
 
     stream = torch.cuda.Stream()  # default priority; all timed work runs on it
 
@@ -234,7 +245,7 @@ def main():
             oracle.hsa_decode(qh, Kh, Vh, lens, ps, k1, T)
             reps += 1
             el = time.perf_counter() - t_cpu0
-            if el >= args.cpu_seconds or reps >= 2000:
+            if el >= args.cpu_seconds:
                 break
         per_call = el / reps
         cpu_us_layer = per_call * (B / nb) * 1e6

@@ -19,8 +19,10 @@
  *    Work is enqueued on it and the call returns without synchronising.  No
  *    entry point allocates or frees device memory; scratch comes from the
  *    caller's `workspace` (size from rocketkv_workspace_bytes, 256-byte
- *    aligned).  The workspace needs no initialisation, and two calls that
- *    overlap in time must not share one.
+ *    aligned).  A workspace must be passed once through
+ *    rocketkv_workspace_init after it is allocated, and again whenever it is
+ *    reused for a cache of a different shape; every call leaves it ready for
+ *    the next.  Two calls that overlap in time must not share one.
  *  - Return value: ROCKETKV_OK (0) or a negative rocketkv_status_t.  Argument
  *    validation runs on the host before anything is launched; on error
  *    nothing has been enqueued and rocketkv_last_error() describes the
@@ -95,10 +97,20 @@ typedef struct rocketkv_cache {
   void* v_pool;               /* device bf16 */
 } rocketkv_cache_t;
 
+#define ROCKETKV_WS_HEADER_BYTES 65536 /* leading part of a workspace that workspace_init clears */
+
 /* Scratch bytes needed by an operation on `cache` (host struct; device
  * pointers inside it are not dereferenced).  Returns 0 for an invalid
  * request (see rocketkv_last_error). */
 size_t rocketkv_workspace_bytes(int32_t op, const rocketkv_cache_t* cache, int32_t a, int32_t b);
+
+/*
+ * Prepares a freshly allocated workspace: clears its first
+ * min(workspace_bytes, ROCKETKV_WS_HEADER_BYTES) bytes (the arrival counters of the
+ * split attention merge) on `stream`.  The attention entry points restore that
+ * state themselves at the end of every call.
+ */
+int32_t rocketkv_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * HSA Step 1 (Section 3.4): element-wise max and min of the keys of each page,

@@ -48,6 +48,8 @@ int check_cache(const rocketkv_cache_t* c, bool need_pools, const char* who) {
   if (c->pages_cap < 1 || c->pages_cap % 8 != 0)
     return fail(ROCKETKV_INVALID_ARG, "%s: pages_cap (%d) must be a positive multiple of 8", who,
                 c->pages_cap);
+  if ((int64_t)c->batch * c->n_kv_heads * 4 > ROCKETKV_WS_HEADER_BYTES)
+    return fail(ROCKETKV_UNSUPPORTED, "%s: batch * n_kv_heads exceeds %d", who, ROCKETKV_WS_HEADER_BYTES / 4);
   if ((int64_t)c->pages_cap * c->page_size > (int64_t)1 << 30)
     return fail(ROCKETKV_INVALID_ARG, "%s: pages_cap * page_size overflows", who);
   if (need_pools) {
@@ -127,10 +129,10 @@ DecodePlan plan_decode(const rocketkv_cache_t* c, int T) {
   d.row_len = list_len_for_budget(c, T);
   d.attend = plan_attend(v, d.row_len);
   size_t off = 0;
+  d.attend_off = off;  // first, so that the counters sit in the header workspace_init clears
+  off += d.attend.total_bytes;
   d.list_off = off;
   off += ((size_t)c->batch * c->n_kv_heads * d.row_len * sizeof(int32_t) + 255) / 256 * 256;
-  d.attend_off = off;
-  off += d.attend.total_bytes;
   d.total = off;
   return d;
 }
@@ -169,6 +171,16 @@ size_t rocketkv_workspace_bytes(int32_t op, const rocketkv_cache_t* cache, int32
       fail(ROCKETKV_INVALID_ARG, "rocketkv_workspace_bytes: unknown op %d", op);
       return 0;
   }
+}
+
+int32_t rocketkv_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
+  g_err[0] = 0;
+  if (!workspace) return fail(ROCKETKV_INVALID_ARG, "rocketkv_workspace_init: workspace is NULL");
+  if ((uintptr_t)workspace & 255)
+    return fail(ROCKETKV_INVALID_ARG, "rocketkv_workspace_init: workspace must be 256-byte aligned");
+  const size_t n = workspace_bytes < ROCKETKV_WS_HEADER_BYTES ? workspace_bytes : (size_t)ROCKETKV_WS_HEADER_BYTES;
+  const hipError_t e = launch_zero(workspace, n / 4 * 4, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? ROCKETKV_OK : hip_fail(e, "rocketkv_workspace_init");
 }
 
 int32_t rocketkv_build_page_summaries(const rocketkv_cache_t* cache, void* kmax, void* kmin,
@@ -233,7 +245,7 @@ int32_t rocketkv_attend(const rocketkv_cache_t* cache, const void* q, const int3
                 workspace ? workspace_bytes : (size_t)0, plan.total_bytes);
   if ((uintptr_t)workspace & 255) return fail(ROCKETKV_INVALID_ARG, "%s: workspace must be 256-byte aligned", who);
   const hipError_t e = launch_attend(v, static_cast<const bf16_t*>(q), pages, row_len,
-                                     static_cast<bf16_t*>(out), out_lse, workspace, plan, false,
+                                     static_cast<bf16_t*>(out), out_lse, workspace, plan,
                                      static_cast<hipStream_t>(stream));
   return e == hipSuccess ? ROCKETKV_OK : hip_fail(e, who);
 }
@@ -280,7 +292,7 @@ int32_t rocketkv_hsa_decode(const rocketkv_cache_t* cache, const void* q, const 
   hipError_t e = launch_hsa_select(v, a, st);
   if (e != hipSuccess) return hip_fail(e, who);
   e = launch_attend(v, a.q, a.out_pages, d.row_len, static_cast<bf16_t*>(out), out_lse,
-                    ws + d.attend_off, d.attend, true, st);
+                    ws + d.attend_off, d.attend, st);
   return e == hipSuccess ? ROCKETKV_OK : hip_fail(e, who);
 }
 

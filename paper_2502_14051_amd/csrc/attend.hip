@@ -354,7 +354,7 @@ __global__ void zero_u32_kernel(uint32_t* p, int n) {
 }
 
 // ---- launch geometry ---------------------------------------------------------------------------------
-static int g_waves = 4;            // wavefronts per workgroup (4 or 8)
+static int g_waves = 8;            // wavefronts per workgroup (4 or 8)
 static int g_pairs_per_wave = 2;   // page pairs a wavefront aims to own
 static int g_max_wgs = 2048;       // cap on units x splits (keeps the dense case from over-splitting)
 
@@ -385,8 +385,8 @@ AttendPlan plan_attend(const CacheView& c, int row_len) {
   p.n_split = (row_len + chunk - 1) / chunk;
   if (p.n_split < 1) p.n_split = 1;
   size_t off = 0;
-  p.counter_off = off;
-  off += ((size_t)units * sizeof(uint32_t) + 255) / 256 * 256;
+  p.counter_off = off;  // always first: the part rocketkv_workspace_init clears
+  off += ROCKETKV_WS_HEADER_BYTES;
   p.partial_off = off;
   off += ((size_t)units * p.n_split * c.group * kPartialStride * sizeof(float) + 255) / 256 * 256;
   p.total_bytes = off;
@@ -397,9 +397,15 @@ uint32_t* attend_counters(void* ws, const AttendPlan& plan) {
   return reinterpret_cast<uint32_t*>(static_cast<char*>(ws) + plan.counter_off);
 }
 
+hipError_t launch_zero(void* p, size_t bytes, hipStream_t st) {
+  const int n = (int)(bytes / sizeof(uint32_t));
+  if (n > 0) hipLaunchKernelGGL(zero_u32_kernel, dim3((n + 255) / 256), dim3(256), 0, st, static_cast<uint32_t*>(p), n);
+  return hipGetLastError();
+}
+
 hipError_t launch_attend(const CacheView& c, const bf16_t* q, const int32_t* pages, int row_len,
                          bf16_t* out, float* out_lse, void* ws, const AttendPlan& plan,
-                         bool counters_are_zero, hipStream_t st) {
+                         hipStream_t st) {
   const int units = c.batch * c.n_kv_heads;
   AttendArgs a;
   a.q = q;
@@ -412,9 +418,7 @@ hipError_t launch_attend(const CacheView& c, const bf16_t* q, const int32_t* pag
   a.n_split = plan.n_split;
   a.chunk = plan.chunk;
   a.per_wave = plan.per_wave;
-  if (plan.n_split > 1 && !counters_are_zero) {
-    hipLaunchKernelGGL(zero_u32_kernel, dim3((units + 255) / 256), dim3(256), 0, st, a.counters, units);
-  }
+  (void)units;
   const size_t smem = (size_t)plan.waves * c.group * (kHeadDim + 2) * sizeof(float);
   const dim3 grid(plan.n_split, units);
   if (plan.waves == 8)

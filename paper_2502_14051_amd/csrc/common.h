@@ -29,6 +29,18 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
   return (bf16_t)(u >> 16);
 }
 
+// Inclusive prefix sum over the 64 lanes of a wavefront with data-parallel-primitive moves (four
+// shifts inside each row of 16 lanes, then two row broadcasts): six adds and no LDS round trips.
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t x) {
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x111, 0xf, 0xf, false);  // row_shr:1
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x112, 0xf, 0xf, false);  // row_shr:2
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x114, 0xf, 0xf, false);  // row_shr:4
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x118, 0xf, 0xf, false);  // row_shr:8
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x142, 0xa, 0xf, false);  // row_bcast:15 -> rows 1,3
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x143, 0xc, 0xf, false);  // row_bcast:31 -> rows 2,3
+  return x;
+}
+
 // Device view of a cache (copied by value into kernel arguments).
 struct CacheView {
   int32_t batch, n_q_heads, n_kv_heads, group;
@@ -87,7 +99,8 @@ struct AttendPlan {
 AttendPlan plan_attend(const CacheView& c, int row_len);
 hipError_t launch_attend(const CacheView& c, const bf16_t* q, const int32_t* pages, int row_len,
                          bf16_t* out, float* out_lse, void* ws, const AttendPlan& plan,
-                         bool counters_are_zero, hipStream_t st);
+                         hipStream_t st);
+hipError_t launch_zero(void* p, size_t bytes, hipStream_t st);
 uint32_t* attend_counters(void* ws, const AttendPlan& plan);
 
 hipError_t launch_append(const CacheView& c, const bf16_t* k_new, const bf16_t* v_new, bf16_t* kmax,

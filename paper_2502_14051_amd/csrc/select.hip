@@ -20,12 +20,7 @@ __device__ __forceinline__ uint32_t f32_order_key(float f) {
 // exclusive prefix sum of one uint32 per thread over the 256-thread workgroup
 __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* wsum /*[4]*/) {
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
-  uint32_t inc = v;
-#pragma unroll
-  for (int off = 1; off < kWave; off <<= 1) {
-    const uint32_t y = __shfl_up(inc, off);
-    if (lane >= off) inc += y;
-  }
+  const uint32_t inc = wave_incl_scan(v);
   if (lane == kWave - 1) wsum[wave] = inc;
   __syncthreads();
   uint32_t base = 0;
@@ -223,17 +218,11 @@ __global__ __launch_bounds__(kSelThreads) void hsa_select_kernel(CacheView c, Se
       }
       __syncthreads();
       // every wavefront finds the bucket holding the k-th largest on its own (no broadcast needed):
-      // lane L owns bins 4L..4L+3; suffix sums inside the lane, then across lanes
-      const uint4 h = *reinterpret_cast<const uint4*>(&hist[pass][4 * lane]);
-      const uint32_t s3 = h.w, s2 = h.z + s3, s1 = h.y + s2, s0 = h.x + s1;
-      uint32_t inc = s0;
-#pragma unroll
-      for (int off = 1; off < kWave; off <<= 1) {
-        const uint32_t y = __shfl_down(inc, off);
-        if (lane + off < kWave) inc += y;
-      }
-      const uint32_t above = inc - s0;  // keys in bins of higher lanes
-      // bin j of this lane: inclusive suffix = above + s_j, exclusive = that minus its own count
+      // lane L owns bins 4(63-L)..4(63-L)+3, so a prefix sum over lanes counts the keys in higher bins
+      const int b0 = 4 * (kWave - 1 - lane);
+      const uint4 h = *reinterpret_cast<const uint4*>(&hist[pass][b0]);
+      const uint32_t s3 = h.w, s2 = h.z + s3, s1 = h.y + s2, s0 = h.x + s1;  // suffix sums inside the lane
+      const uint32_t above = wave_incl_scan(s0) - s0;                          // keys in bins of lower lanes
       const uint32_t in[4] = {above + s0, above + s1, above + s2, above + s3};
       const uint32_t hc[4] = {h.x, h.y, h.z, h.w};
       int found = -1;
@@ -242,14 +231,14 @@ __global__ __launch_bounds__(kSelThreads) void hsa_select_kernel(CacheView c, Se
       for (int j = 0; j < 4; ++j) {
         const uint32_t exc = in[j] - hc[j];
         if (exc < k && k <= in[j]) {
-          found = 4 * lane + j;
+          found = b0 + j;
           newk = k - exc;
         }
       }
       const unsigned long long who = __ballot(found >= 0);
       const int src = __ffsll((long long)who) - 1;
-      const uint32_t bucket = (uint32_t)__shfl(found, src);
-      k = (uint32_t)__shfl((int)newk, src);
+      const uint32_t bucket = (uint32_t)__builtin_amdgcn_readlane(found, src);
+      k = (uint32_t)__builtin_amdgcn_readlane((int)newk, src);
       prefix |= bucket << shift;
       mask |= 0xffu << shift;
     }

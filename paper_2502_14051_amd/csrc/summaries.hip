@@ -89,12 +89,14 @@ hipError_t launch_page_summaries(const CacheView& c, bf16_t* kmax, bf16_t* kmin,
 }
 
 // One generated token per sequence: write its key row and value column into the tail page, fold the
-// key into that page's summary, then bump the length.  One workgroup per sequence; every thread
-// reads the old length before the barrier that precedes the increment.
-__global__ __launch_bounds__(256) void append_kv_kernel(CacheView c, const bf16_t* __restrict__ k_new,
-                                                        const bf16_t* __restrict__ v_new,
-                                                        bf16_t* __restrict__ kmax,
-                                                        bf16_t* __restrict__ kmin) {
+// key into that page's summary, then bump the length.  One workgroup per sequence, one thread per
+// (KV head, channel) where that fits, so that every load of the step is in flight at once; every
+// thread reads the old length before the barrier that precedes the increment.
+constexpr int kAppendThreads = 1024;
+__global__ __launch_bounds__(kAppendThreads) void append_kv_kernel(CacheView c, const bf16_t* __restrict__ k_new,
+                                                                   const bf16_t* __restrict__ v_new,
+                                                                   bf16_t* __restrict__ kmax,
+                                                                   bf16_t* __restrict__ kmin) {
   const int b = blockIdx.x;
   const int n = c.seq_lens[b];
   const int ps = c.page_size;
@@ -102,24 +104,20 @@ __global__ __launch_bounds__(256) void append_kv_kernel(CacheView c, const bf16_
   if (room) {
     const int p = n / ps, slot = n % ps;
     const int64_t pp = phys_page(c, b, p);
-    for (int idx = threadIdx.x; idx < c.n_kv_heads * kHeadDim; idx += 256) {
+    for (int idx = threadIdx.x; idx < c.n_kv_heads * kHeadDim; idx += blockDim.x) {
       const int g = idx / kHeadDim, ch = idx % kHeadDim;
-      const bf16_t kb = k_new[((int64_t)b * c.n_kv_heads + g) * kHeadDim + ch];
-      const bf16_t vb = v_new[((int64_t)b * c.n_kv_heads + g) * kHeadDim + ch];
+      const int64_t src = ((int64_t)b * c.n_kv_heads + g) * kHeadDim + ch;
+      const int64_t o = (((int64_t)b * c.n_kv_heads + g) * kHeadDim + ch) * c.pages_cap + p;
+      const bf16_t kb = k_new[src], vb = v_new[src];
+      const bf16_t old_max = kmax[o], old_min = kmin[o];
       if (pp >= 0) {
         const int64_t base = pp * c.stride_page + (int64_t)g * c.stride_head;
         c.k_pool[base + slot * kHeadDim + ch] = kb;
         c.v_pool[base + ch * ps + slot] = vb;
       }
-      const int64_t o = (((int64_t)b * c.n_kv_heads + g) * kHeadDim + ch) * c.pages_cap + p;
-      if (slot == 0) {
-        kmax[o] = kb;
-        kmin[o] = kb;
-      } else {
-        const float x = bf16_to_f32(kb);
-        if (x > bf16_to_f32(kmax[o])) kmax[o] = kb;
-        if (x < bf16_to_f32(kmin[o])) kmin[o] = kb;
-      }
+      const float x = bf16_to_f32(kb);
+      if (slot == 0 || x > bf16_to_f32(old_max)) kmax[o] = kb;
+      if (slot == 0 || x < bf16_to_f32(old_min)) kmin[o] = kb;
     }
   }
   __syncthreads();
@@ -128,7 +126,9 @@ __global__ __launch_bounds__(256) void append_kv_kernel(CacheView c, const bf16_
 
 hipError_t launch_append(const CacheView& c, const bf16_t* k_new, const bf16_t* v_new, bf16_t* kmax,
                          bf16_t* kmin, hipStream_t st) {
-  hipLaunchKernelGGL(append_kv_kernel, dim3(c.batch), dim3(256), 0, st, c, k_new, v_new, kmax, kmin);
+  int threads = c.n_kv_heads * kHeadDim;
+  if (threads > kAppendThreads) threads = kAppendThreads;
+  hipLaunchKernelGGL(append_kv_kernel, dim3(c.batch), dim3(threads), 0, st, c, k_new, v_new, kmax, kmin);
   return hipGetLastError();
 }
 

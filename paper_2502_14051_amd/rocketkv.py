@@ -21,7 +21,7 @@ OP_HSA_DECODE, OP_DENSE_DECODE, OP_SNAPKV, OP_ATTEND = 0, 1, 2, 3
 MAX_PAGES = 8192
 
 EXPORTS = [
-    "rocketkv_workspace_bytes", "rocketkv_build_page_summaries", "rocketkv_hsa_select",
+    "rocketkv_workspace_bytes", "rocketkv_workspace_init", "rocketkv_build_page_summaries", "rocketkv_hsa_select",
     "rocketkv_attend", "rocketkv_hsa_decode", "rocketkv_dense_decode", "rocketkv_append_kv",
     "rocketkv_snapkv_compress", "rocketkv_last_error", "rocketkv_version",
 ]
@@ -62,6 +62,8 @@ def lib():
         vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
         L.rocketkv_workspace_bytes.restype = sz
         L.rocketkv_workspace_bytes.argtypes = [i32, cp, i32, i32]
+        L.rocketkv_workspace_init.restype = i32
+        L.rocketkv_workspace_init.argtypes = [vp, sz, vp]
         L.rocketkv_build_page_summaries.restype = i32
         L.rocketkv_build_page_summaries.argtypes = [cp, vp, vp, i32, i32, vp]
         L.rocketkv_hsa_select.restype = i32
@@ -208,10 +210,17 @@ def workspace_bytes(op: int, cache: Cache, a: int = 0, b: int = 0) -> int:
     return int(n)
 
 
-def alloc_workspace(op: int, cache: Cache, a: int = 0, b: int = 0):
+def workspace_init(workspace, stream=None):
+    _check(lib().rocketkv_workspace_init(_ptr(workspace), workspace.numel(), _stream(stream)))
+
+
+def alloc_workspace(op: int, cache: Cache, a: int = 0, b: int = 0, stream=None):
+    """Allocate (torch) and initialise a workspace for `op` on `cache`."""
     import torch
     n = workspace_bytes(op, cache, a, b)
-    return torch.empty((max(n, 256),), dtype=torch.uint8, device=cache.k_pool.device)
+    ws = torch.empty((max(n, 256),), dtype=torch.uint8, device=cache.k_pool.device)
+    workspace_init(ws, stream)
+    return ws
 
 
 def build_page_summaries(cache: Cache, kmax, kmin, first_page: int = 0, n_pages: int = -1,

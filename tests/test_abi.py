@@ -108,6 +108,8 @@ def test_null_and_range_arguments(L):
     assert L.rocketkv_hsa_select(C.byref(st), q, kx, kn, 32, 1024, 0, 0x6000, 8, None, None,
                                  None) == rk.INVALID_ARG and "pages_row_len" in rk.last_error()
     assert L.rocketkv_append_kv(C.byref(st), None, q, kx, kn, None) == rk.INVALID_ARG
+    assert L.rocketkv_workspace_init(None, 1024, None) == rk.INVALID_ARG
+    assert L.rocketkv_workspace_init(0x5010, 1024, None) == rk.INVALID_ARG
 
 
 def test_snapkv_argument_checks(L):

@@ -205,7 +205,8 @@ def test_dense_decode(env, oracle, name, over, lens, shuffle):
     out = torch.full((w.batch, w.n_q_heads, 128), 7.0, dtype=torch.bfloat16, device=dev)
     lse = torch.zeros((w.batch, w.n_q_heads), dtype=torch.float32, device=dev)
     ws = rk.alloc_workspace(rk.OP_DENSE_DECODE, cache)
-    ws.fill_(0xAB)  # the workspace needs no initialisation
+    ws.fill_(0xAB)  # whatever the allocation held; initialised once below
+    rk.workspace_init(ws)
     rk.dense_decode(cache, q, out, lse, ws)
     torch.cuda.synchronize()
     want_y, want_lse = oracle.dense_decode(d["q"], d["K"], d["V"], d["seq_lens"])
@@ -299,6 +300,7 @@ def test_hsa_decode(env, oracle, name, over, lens, n_recent, shuffle):
     chans = torch.empty((w.batch, w.n_kv_heads, w.channel_budget), dtype=torch.int32, device=dev)
     ws = rk.alloc_workspace(rk.OP_HSA_DECODE, cache, w.token_budget)
     ws.fill_(0xCD)
+    rk.workspace_init(ws)
     rk.hsa_decode(cache, q, kmax, kmin, w.channel_budget, w.token_budget, n_recent, out, lse, pages,
                   chans, ws)
     torch.cuda.synchronize()
@@ -418,6 +420,7 @@ def test_snapkv_compress(env, oracle, name, over, lens, ks, shuffle):
     kept = torch.full((w.batch, w.n_kv_heads, N), -9, dtype=torch.int32, device=dev)
     ws = rk.alloc_workspace(rk.OP_SNAPKV, src, W, N)
     ws.fill_(0xEE)
+    rk.workspace_init(ws)
     rk.snapkv_compress(wl.from_bits(d["qobs"], dev), src, W, ks, N, dst, kept, ws)
     torch.cuda.synchronize()
     ref = oracle.snapkv(d["qobs"], d["K"], d["seq_lens"], ks, N, want_votes=True)
