@@ -6,9 +6,10 @@ Llama3.1-8B-shaped decode step, 32 layers x (32 query / 8 KV heads, head_dim 128
 32768-token bf16 context per sequence, SnapKV-compressed to 4096 tokens per (sequence, KV head),
 then hybrid sparse attention with token budget 1024, page size 16, channel budget 32.
 
-One "step" = one decode step of the attention path of every layer: append the new token's K/V
-(which also folds the key into the tail page's min/max summary), then rocketkv_hsa_decode (channel
-pick, page scores, page top-k, exact attention over the picked pages).  Projections, MLPs and
+One "step" = one decode step of the attention path of every layer: rocketkv_hsa_decode_append, which
+takes in the new token's K/V (folding the key into the tail page's min/max summary) and runs
+Algorithm 1 (channel pick, page scores, page top-k, exact attention over the picked pages) in one
+launch per layer.  Projections, MLPs and
 weights are outside the path and not run.  Inputs are seeded synthetic data resident in HBM; the
 one-time SnapKV stage and the summary build run untimed in set-up, through the same library.
 
@@ -28,6 +29,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published peak
+# HBM bytes per launch of the fused kernel on this workload from rocprofv3 FETCH_SIZE / WRITE_SIZE
+# (profiles/hsa_decode_kernel_llama8b_step_b16_pmc.txt); None until measured for the current kernel.
+TRAFFIC_BYTES_PER_LAUNCH = None
 
 
 def parse():
@@ -131,9 +135,8 @@ def main():
     # values do not change the work done), so a captured step can be replayed as is.
     def one_step():
         for L in layers:
-            rk.append_kv(L["cache"], L["new_k"], L["new_v"], L["kmax"], L["kmin"], stream)
-            rk.hsa_decode(L["cache"], L["q"], L["kmax"], L["kmin"], k1, T, 0, L["out"], None, None,
-                          None, L["ws"], stream)
+            rk.hsa_decode_append(L["cache"], L["q"], L["new_k"], L["new_v"], L["kmax"], L["kmin"], k1, T, 0,
+                                 L["out"], None, None, None, L["ws"], stream)
 
     graph = None
     with torch.cuda.stream(stream):
@@ -207,8 +210,22 @@ def main():
         for L, pg in zip(layers, lists):
             rk.hsa_select(L["cache"], L["q"], L["kmax"], L["kmin"], k1, T, 0, pg, None, None, stream)
 
+    def decode_all():
+        for L in layers:
+            rk.hsa_decode(L["cache"], L["q"], L["kmax"], L["kmin"], k1, T, 0, L["out"], None, None, None,
+                          L["ws"], stream)
+
+    def append_all():
+        for L in layers:
+            rk.append_kv(L["cache"], L["new_k"], L["new_v"], L["kmax"], L["kmin"], stream)
+
     attend_us = timed_graph(attend_all, args.kernel_reps) * 1e3 / w.n_layers
     select_us = timed_graph(select_all, args.kernel_reps) * 1e3 / w.n_layers
+    decode_us = timed_graph(decode_all, args.kernel_reps) * 1e3 / w.n_layers
+    n_before = int(layers[0]["cache"].seq_lens[0].item())
+    append_us = timed_graph(append_all, 2) * 1e3 / w.n_layers
+    for L in layers:  # undo the appends of that probe
+        L["cache"].seq_lens.fill_(n_before)
 
     def dense_all():
         for Ld in dense_layers:
@@ -276,17 +293,21 @@ def main():
         "hsa_achieved_GBs": round(hsa_gbs, 1),
         "hsa_frac_of_hbm_peak": round(hsa_gbs / HBM_PEAK_GBS, 4),
         "hsa_bytes_per_layer_step": hsa_bytes,
-        "select_us_per_layer": round(select_us, 3),
         "dense_full_kv_us_per_layer_step": round(dense_us, 2),
         "dense_achieved_GBs": round(dense_gbs, 1),
         "speedup_vs_dense_full_kv": round(dense_us / us_layer, 2),
         "snapkv_ms_per_layer": round(float(np.median(snap_ms)), 3),
         "host_wall_ms_per_step": round(wall_ms / args.steps, 4),
         "setup_s": round(t_setup, 1),
-        "roofline": {"bound": "hbm", "kernel": "attend_mfma_kernel", "achieved": round(att_gbs, 1),
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(att_gbs / HBM_PEAK_GBS, 4),
-                     "traffic": None, "us_per_launch": round(attend_us, 3),
-                     "bytes_per_launch": attend_bytes},
+        "stage_us_per_layer": {"attend_only": round(attend_us, 3), "select_only": round(select_us, 3),
+                               "decode_no_append": round(decode_us, 3), "append_only": round(append_us, 3),
+                               "attend_only_GBs": round(att_gbs, 1)},
+        # the step is one launch of the fused kernel per layer, so its average launch time is the
+        # timed region divided by the number of launches
+        "roofline": {"bound": "hbm", "kernel": "hsa_decode_kernel<8, true>", "achieved": round(hsa_gbs, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(hsa_gbs / HBM_PEAK_GBS, 4),
+                     "traffic": TRAFFIC_BYTES_PER_LAUNCH, "us_per_launch": round(us_layer, 3),
+                     "bytes_per_launch": hsa_bytes},
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

@@ -173,6 +173,20 @@ int32_t rocketkv_hsa_decode(const rocketkv_cache_t* cache, const void* q, const 
                             size_t workspace_bytes, void* stream);
 
 /*
+ * One decode step including the token generated at it (Section 3.4 Step 1, last
+ * sentence, then Algorithm 1): the result, the caches, the summaries and
+ * seq_lens end up exactly as after rocketkv_append_kv(k_new, v_new) followed by
+ * rocketkv_hsa_decode, in one launch where the shapes allow.  kmax / kmin are
+ * read and written.  k_new, v_new: bf16 [batch][n_kv_heads][head_dim].
+ * workspace: as for rocketkv_hsa_decode (same size, same initialisation).
+ */
+int32_t rocketkv_hsa_decode_append(const rocketkv_cache_t* cache, const void* q, const void* k_new,
+                                   const void* v_new, void* kmax, void* kmin, int32_t channel_budget,
+                                   int32_t token_budget, int32_t n_recent_pages, void* out,
+                                   float* out_lse, int32_t* out_pages, int32_t* out_channels,
+                                   void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Full-KV decode attention (Table 1, first row; the baseline every figure of
  * Section 4.3 is normalised to): rocketkv_attend with every page.
  * workspace: rocketkv_workspace_bytes(ROCKETKV_OP_DENSE_DECODE, cache, 0, 0).

@@ -48,8 +48,8 @@ int check_cache(const rocketkv_cache_t* c, bool need_pools, const char* who) {
   if (c->pages_cap < 1 || c->pages_cap % 8 != 0)
     return fail(ROCKETKV_INVALID_ARG, "%s: pages_cap (%d) must be a positive multiple of 8", who,
                 c->pages_cap);
-  if ((int64_t)c->batch * c->n_kv_heads * 4 > ROCKETKV_WS_HEADER_BYTES)
-    return fail(ROCKETKV_UNSUPPORTED, "%s: batch * n_kv_heads exceeds %d", who, ROCKETKV_WS_HEADER_BYTES / 4);
+  if ((int64_t)c->batch * c->n_kv_heads * 4 > ROCKETKV_WS_HEADER_BYTES / 2)
+    return fail(ROCKETKV_UNSUPPORTED, "%s: batch * n_kv_heads exceeds %d", who, ROCKETKV_WS_HEADER_BYTES / 8);
   if ((int64_t)c->pages_cap * c->page_size > (int64_t)1 << 30)
     return fail(ROCKETKV_INVALID_ARG, "%s: pages_cap * page_size overflows", who);
   if (need_pools) {
@@ -256,13 +256,13 @@ int32_t rocketkv_dense_decode(const rocketkv_cache_t* cache, const void* q, void
   return rocketkv_attend(cache, q, nullptr, 0, out, out_lse, workspace, workspace_bytes, stream);
 }
 
-int32_t rocketkv_hsa_decode(const rocketkv_cache_t* cache, const void* q, const void* kmax,
-                            const void* kmin, int32_t channel_budget, int32_t token_budget,
-                            int32_t n_recent_pages, void* out, float* out_lse,
-                            int32_t* out_pages, int32_t* out_channels, void* workspace,
-                            size_t workspace_bytes, void* stream) {
-  g_err[0] = 0;
-  const char* who = "rocketkv_hsa_decode";
+namespace {
+
+// Shared body of rocketkv_hsa_decode and rocketkv_hsa_decode_append (k_new == NULL: no append).
+int decode_impl(const char* who, const rocketkv_cache_t* cache, const void* q, const void* k_new,
+                const void* v_new, void* kmax, void* kmin, int32_t channel_budget, int32_t token_budget,
+                int32_t n_recent_pages, void* out, float* out_lse, int32_t* out_pages,
+                int32_t* out_channels, void* workspace, size_t workspace_bytes, void* stream) {
   if (int r = check_cache(cache, true, who)) return r;
   if (int r = check_attend_shape(cache, who)) return r;
   if (int r = check_select_args(cache, q, kmax, kmin, channel_budget, token_budget, n_recent_pages, who)) return r;
@@ -282,18 +282,60 @@ int32_t rocketkv_hsa_decode(const rocketkv_cache_t* cache, const void* q, const 
   a.k1 = channel_budget;
   a.T = token_budget;
   a.n_recent = n_recent_pages;
-  a.out_pages = reinterpret_cast<int32_t*>(ws + d.list_off);
   a.row_len = d.row_len;
-  a.out_pages2 = out_pages;
-  a.row_len2 = d.row_len;
   a.out_channels = out_channels;
   a.out_scores = nullptr;
+  AppendArgs ap = {static_cast<const bf16_t*>(k_new), static_cast<const bf16_t*>(v_new),
+                   static_cast<bf16_t*>(kmax), static_cast<bf16_t*>(kmin)};
+  hipError_t e;
+  if (fused_decode_lds_bytes(v, d.row_len, d.attend) + 64 <= kMaxLdsBytes) {
+    // one launch: every workgroup selects for itself and keeps the list in LDS
+    a.out_pages = out_pages;
+    a.out_pages2 = nullptr;
+    a.row_len2 = 0;
+    a.zero_counters = nullptr;
+    e = launch_hsa_decode_fused(v, a, ap, static_cast<bf16_t*>(out), out_lse, ws + d.attend_off, d.attend, st);
+    return e == hipSuccess ? ROCKETKV_OK : hip_fail(e, who);
+  }
+  if (k_new) {
+    e = launch_append(v, ap.k_new, ap.v_new, ap.kmax, ap.kmin, st);
+    if (e != hipSuccess) return hip_fail(e, who);
+  }
+  a.out_pages = reinterpret_cast<int32_t*>(ws + d.list_off);
+  a.out_pages2 = out_pages;
+  a.row_len2 = d.row_len;
   a.zero_counters = d.attend.n_split > 1 ? attend_counters(ws + d.attend_off, d.attend) : nullptr;
-  hipError_t e = launch_hsa_select(v, a, st);
+  e = launch_hsa_select(v, a, st);
   if (e != hipSuccess) return hip_fail(e, who);
   e = launch_attend(v, a.q, a.out_pages, d.row_len, static_cast<bf16_t*>(out), out_lse,
                     ws + d.attend_off, d.attend, st);
   return e == hipSuccess ? ROCKETKV_OK : hip_fail(e, who);
+}
+
+}  // namespace
+
+int32_t rocketkv_hsa_decode(const rocketkv_cache_t* cache, const void* q, const void* kmax,
+                            const void* kmin, int32_t channel_budget, int32_t token_budget,
+                            int32_t n_recent_pages, void* out, float* out_lse,
+                            int32_t* out_pages, int32_t* out_channels, void* workspace,
+                            size_t workspace_bytes, void* stream) {
+  g_err[0] = 0;
+  return decode_impl("rocketkv_hsa_decode", cache, q, nullptr, nullptr, const_cast<void*>(kmax),
+                     const_cast<void*>(kmin), channel_budget, token_budget, n_recent_pages, out, out_lse,
+                     out_pages, out_channels, workspace, workspace_bytes, stream);
+}
+
+int32_t rocketkv_hsa_decode_append(const rocketkv_cache_t* cache, const void* q, const void* k_new,
+                                   const void* v_new, void* kmax, void* kmin, int32_t channel_budget,
+                                   int32_t token_budget, int32_t n_recent_pages, void* out,
+                                   float* out_lse, int32_t* out_pages, int32_t* out_channels,
+                                   void* workspace, size_t workspace_bytes, void* stream) {
+  g_err[0] = 0;
+  const char* who = "rocketkv_hsa_decode_append";
+  if (!k_new || !v_new) return fail(ROCKETKV_INVALID_ARG, "%s: k_new / v_new must not be NULL", who);
+  return decode_impl(who, cache, q, k_new, v_new, kmax, kmin, channel_budget, token_budget,
+                     n_recent_pages, out, out_lse, out_pages, out_channels, workspace, workspace_bytes,
+                     stream);
 }
 
 int32_t rocketkv_append_kv(const rocketkv_cache_t* cache, const void* k_new, const void* v_new,

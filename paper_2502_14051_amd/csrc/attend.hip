@@ -1,351 +1,21 @@
-// HSA Step 3 (Algorithm 1 of arXiv 2502.14051, y = attn(q, K[i2], V[i2])) and the Full-KV baseline of
-// Table 1: exact GQA decode attention over a list of 16-token pages, split over workgroups along the
-// list, with online softmax and a last-arriver merge of the split partials.
-//
-// The work is a stream of 4 KiB K tiles and 4 KiB V tiles per page and is HBM-bound; the arithmetic
-// (G flop per byte plus the softmax) would not fit the vector ALUs beside the stream, so both
-// contractions run on the matrix cores with the query heads of the group padded to one 16-wide tile:
-//
-//   S[token][head]   = K[token][:] . Q[head][:]            A = K tile (rows: 16 tokens), B = Q^T
-//   O^T[chan][head] += V^T[chan][token] . P[token][head]   A = V tile (rows: 16 channels), B = P
-//
-// Both products have the head index as the MFMA column, so a lane owns one head throughout: its
-// S values, running max / sum and O accumulators never move between lanes.  The V pool is
-// channel-major inside a page precisely so that the contraction index (tokens) is contiguous per lane.
-// A 16x16x32 MFMA contracts 32 tokens: two pages per step, lane group kg contributing tokens
-// 4kg..4kg+3 of each, which is exactly how the S tiles come out of the first product.
-//
-// Latency matters as much as bandwidth here (a layer moves only tens of MB): a wavefront reads the
-// page ids of its whole share with one load, keeps the next page pair's 16 KiB in flight while it
-// works on the current one, and the split partials are handed over with write-through stores and a
-// relaxed device-scope counter instead of cache-flushing fences.
-#include "common.h"
+// Stand-alone HSA Step 3 kernel and the Full-KV baseline (Algorithm 1 of arXiv 2502.14051,
+// y = attn(q, K[i2], V[i2]); Table 1, first row): the workgroup-level attention routine driven by a
+// page list in global memory (or the identity list), plus the launch geometry shared with the
+// fused decode kernel.
+#include "attend_core.h"
 
 namespace rkv {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-
-constexpr int kPartialStride = kHeadDim + 2;  // O[128], running max (log2 domain), running sum
-constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kLn2 = 0.6931471805599453f;
-constexpr float kNegBig = -1.0e30f;
-
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-
-// Fragments are plain ext-vector values (no unions or structs of arrays): anything the compiler
-// cannot split into scalars ends up in scratch memory, which costs far more than the arithmetic.
-__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
-
-struct AttendArgs {
-  const bf16_t* q;
-  const int32_t* pages;  // NULL = identity list
-  int row_len;           // entries per unit in `pages` (or pages_cap for identity)
-  bf16_t* out;
-  float* out_lse;
-  float* partial;        // [units][n_split][G][kPartialStride]
-  uint32_t* counters;    // [units]
-  int n_split, chunk, per_wave;
-};
-
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-
-// two fp32 -> packed bf16, round to nearest even (one v_cvt_pk_bf16_f32)
-__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  const f32x2 v = {lo, hi};
-  const bf16x2 r = __builtin_convertvector(v, bf16x2);
-  return *reinterpret_cast<const uint32_t*>(&r);
-}
-
-__device__ __forceinline__ void st_agent(float* p, float v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ float ld_agent(const float* p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-// Online-softmax step over the NP page pairs of one round.  The vector ALUs issue one wave64
-// instruction per four cycles and share the SIMD with the next wave, so instruction count is what
-// this step is built around: one max / rescale per round instead of per page, the logit scale folded
-// into the exponent's FMA, hardware bf16 packing, and the per-token masks compiled only into the
-// MASK variant, which a round takes when it holds an absent page or the sequence's partial tail page.
-template <int NP, bool MASK>
-__device__ __forceinline__ void softmax_round(const u32x4 (&kf)[NP][2][4], u32x2 (&vf)[NP][2][8],
-                                              const int (&ids)[NP][2], const u32x4 (&qf)[4],
-                                              f32x4 (&O)[8], float& m, float& l, bool have_acc, int n,
-                                              int kg, float sc) {
-  f32x4 acc[NP][2];
-#pragma unroll
-  for (int u = 0; u < NP; ++u)
-#pragma unroll
-    for (int x = 0; x < 2; ++x) {
-      acc[u][x] = (f32x4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        acc[u][x] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kf[u][x][j]), as_bf16x8(qf[j]),
-                                                            acc[u][x], 0, 0, 0);
-    }
-  if (MASK) {
-#pragma unroll
-    for (int u = 0; u < NP; ++u)
-#pragma unroll
-      for (int x = 0; x < 2; ++x) {
-        const int tok0 = ids[u][x] * kAttnPage + kg * 4;
-        const bool gone = ids[u][x] < 0;
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-          if (gone || tok0 + r >= n) acc[u][x][r] = -INFINITY;
-        // what lies in an absent page, or beyond the sequence end in the tail page, may be anything:
-        // its probability is zero, but 0 x NaN is not, so it is cleared out of the V operand too
-#pragma unroll
-        for (int cb = 0; cb < 8; ++cb) {
-          uint32_t w0 = vf[u][x][cb].x, w1 = vf[u][x][cb].y;
-          if (gone || tok0 + 0 >= n) w0 &= 0xffff0000u;
-          if (gone || tok0 + 1 >= n) w0 &= 0x0000ffffu;
-          if (gone || tok0 + 2 >= n) w1 &= 0xffff0000u;
-          if (gone || tok0 + 3 >= n) w1 &= 0x0000ffffu;
-          vf[u][x][cb] = (u32x2){w0, w1};
-        }
-      }
-  }
-  float mx = -INFINITY;
-#pragma unroll
-  for (int u = 0; u < NP; ++u)
-#pragma unroll
-    for (int x = 0; x < 2; ++x)
-      mx = fmaxf(fmaxf(mx, fmaxf(acc[u][x][0], acc[u][x][1])), fmaxf(acc[u][x][2], acc[u][x][3]));
-  mx = fmaxf(mx, __shfl_xor(mx, 16));
-  mx = fmaxf(mx, __shfl_xor(mx, 32));
-  const float m_new = fmaxf(m, mx * sc);  // running max in the scaled log2 domain
-  if (have_acc) {
-    const float alpha = fast_exp2(m - m_new);
-    l *= alpha;
-    if (__any(alpha != 1.f)) {
-#pragma unroll
-      for (int cb = 0; cb < 8; ++cb) O[cb] *= alpha;
-    }
-  }
-  m = m_new;
-  float psum = 0.f;
-  u32x4 pf[NP];
-#pragma unroll
-  for (int u = 0; u < NP; ++u) {
-    float p[2][4];
-#pragma unroll
-    for (int x = 0; x < 2; ++x)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        p[x][r] = fast_exp2(fmaf(acc[u][x][r], sc, -m_new));
-        psum += p[x][r];
-      }
-    pf[u] = (u32x4){pack_bf16x2(p[0][0], p[0][1]), pack_bf16x2(p[0][2], p[0][3]),
-                    pack_bf16x2(p[1][0], p[1][1]), pack_bf16x2(p[1][2], p[1][3])};
-  }
-  l += psum;
-#pragma unroll
-  for (int u = 0; u < NP; ++u)
-#pragma unroll
-    for (int cb = 0; cb < 8; ++cb) {
-      const u32x4 vv = {vf[u][0][cb].x, vf[u][0][cb].y, vf[u][1][cb].x, vf[u][1][cb].y};
-      O[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vv), as_bf16x8(pf[u]), O[cb], 0, 0, 0);
-    }
-}
 
 template <int WAVES, int NP>
 __global__ __launch_bounds__(WAVES* kWave) __attribute__((amdgpu_waves_per_eu(2)))
 void attend_mfma_kernel(CacheView c, AttendArgs a) {
   extern __shared__ float smem[];  // sO[WAVES][G][128], sM[WAVES][G], sL[WAVES][G]
   __shared__ int s_last;
-  constexpr int kThreads = WAVES * kWave;
-
-  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
-  const int hn = lane % 16, kg = lane / 16;
   const int unit = blockIdx.y, split = blockIdx.x;
-  const int b = unit / c.n_kv_heads, g = unit % c.n_kv_heads;
-  const int G = c.group;
-  float* sO = smem;
-  float* sM = smem + WAVES * G * kHeadDim;
-  float* sL = sM + WAVES * G;
-  const int n = c.seq_lens[b];
-  int P = (n + kAttnPage - 1) / kAttnPage;
-  if (P > c.pages_cap) P = c.pages_cap;
-
-  // this wave's share of the list
-  const int e_begin = split * a.chunk;
-  const int e_end = min(e_begin + a.chunk, a.row_len);
-  const int wb = e_begin + wave * a.per_wave;
-  const int we = min(wb + a.per_wave, e_end);
+  const int n = c.seq_lens[unit / c.n_kv_heads];
   const int32_t* list = a.pages ? a.pages + (int64_t)unit * a.row_len : nullptr;
-
-  // first batch of page ids: issued before anything else
-  int my_id = -1;
-  if (wb + lane < we) my_id = list ? list[wb + lane] : wb + lane;
-
-  // Q as the B operand of the first product: lane (head hn, group kg) holds channels j*32+kg*8..+7
-  u32x4 qf[4];
-  {
-    const bf16_t* qp = a.q + ((int64_t)b * c.n_q_heads + (int64_t)g * G + (hn < G ? hn : 0)) * kHeadDim + kg * 8;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      qf[j] = *reinterpret_cast<const u32x4*>(qp + j * 32);
-      if (hn >= G) qf[j] = (u32x4){0u, 0u, 0u, 0u};
-    }
-  }
-
-  f32x4 O[8];
-#pragma unroll
-  for (int cb = 0; cb < 8; ++cb) O[cb] = (f32x4){0.f, 0.f, 0.f, 0.f};
-  float m = kNegBig, l = 0.f;
-  bool have_acc = false;
-  const float sc = kLog2e * 0.08838834764831845f;  // log2(e) / sqrt(128)
-  // lane-dependent part of every tile address
-  const bf16_t* k_lane = c.k_pool + (int64_t)g * c.stride_head + hn * kHeadDim + kg * 8;
-  const bf16_t* v_lane = c.v_pool + (int64_t)g * c.stride_head + hn * kAttnPage + kg * 4;
-
-  for (int base = wb; base < we; base += kWave) {
-    if (base != wb) {
-      my_id = -1;
-      if (base + lane < we) my_id = list ? list[base + lane] : base + lane;
-    }
-    if (my_id >= P) my_id = -1;
-    int64_t my_pp = my_id >= 0 ? phys_page(c, b, my_id) : -1;
-    if (my_pp < 0) my_id = -1;
-    // element offset of this lane's page (an absent page reads page 0 and is masked out)
-    const int64_t my_off = (my_id >= 0 ? my_pp : 0) * c.stride_page;
-    const unsigned long long special = __ballot(my_id < 0 || my_id * kAttnPage + kAttnPage > n);
-    const int cnt = min(kWave, we - base);
-    const int npairs = (cnt + 1) / 2;
-
-    // NP pairs per round: all their loads go out back to back (K tiles first, the first product
-    // needs them first), then one softmax step consumes them.  Nothing is carried between rounds in
-    // registers; the other wavefronts of the SIMD cover the gap.
-    for (int i = 0; i < npairs; i += NP) {
-      u32x4 kf[NP][2][4];
-      u32x2 vf[NP][2][8];
-      int ids[NP][2];
-      const bf16_t* vt[NP][2];
-      const int e0 = __builtin_amdgcn_readfirstlane(2 * i);
-#pragma unroll
-      for (int u = 0; u < NP; ++u)
-#pragma unroll
-        for (int x = 0; x < 2; ++x) {
-          const int e = (e0 + 2 * u + x) & (kWave - 1);
-          ids[u][x] = 2 * (i + u) + x < kWave ? __builtin_amdgcn_readlane(my_id, e) : -1;
-          const int64_t off = ((int64_t)__builtin_amdgcn_readlane((int)(my_off >> 32), e) << 32) |
-                              (uint32_t)__builtin_amdgcn_readlane((int)(my_off & 0xffffffff), e);
-          const bf16_t* kt = k_lane + off;
-          vt[u][x] = v_lane + off;
-#pragma unroll
-          for (int j = 0; j < 4; ++j) kf[u][x][j] = *reinterpret_cast<const u32x4*>(kt + j * 32);
-        }
-#pragma unroll
-      for (int u = 0; u < NP; ++u)
-#pragma unroll
-        for (int x = 0; x < 2; ++x)
-#pragma unroll
-          for (int cb = 0; cb < 8; ++cb)
-            vf[u][x][cb] = *reinterpret_cast<const u32x2*>(vt[u][x] + cb * 16 * kAttnPage);
-      const bool masked = ((special >> e0) & ((1ull << (2 * NP)) - 1ull)) != 0ull || e0 + 2 * NP > kWave;
-      if (!masked)
-        softmax_round<NP, false>(kf, vf, ids, qf, O, m, l, have_acc, n, kg, sc);
-      else
-        softmax_round<NP, true>(kf, vf, ids, qf, O, m, l, have_acc, n, kg, sc);
-      have_acc = true;
-    }
-  }
-  l += __shfl_xor(l, 16);
-  l += __shfl_xor(l, 32);
-
-  // ---- merge the waves through LDS ---------------------------------------------------------------
-  if (hn < G) {
-#pragma unroll
-    for (int cb = 0; cb < 8; ++cb)
-      *reinterpret_cast<float4*>(&sO[(wave * G + hn) * kHeadDim + cb * 16 + kg * 4]) =
-          make_float4(O[cb][0], O[cb][1], O[cb][2], O[cb][3]);
-    if (kg == 0) {
-      sM[wave * G + hn] = m;
-      sL[wave * G + hn] = l;
-    }
-  }
-  __syncthreads();
-  const int64_t out_base = ((int64_t)b * c.n_q_heads + (int64_t)g * G) * kHeadDim;
-  for (int idx = tid; idx < G * kHeadDim; idx += kThreads) {
-    const int h = idx / kHeadDim, ch = idx % kHeadDim;
-    float M = sM[h];
-#pragma unroll
-    for (int w = 1; w < WAVES; ++w) M = fmaxf(M, sM[w * G + h]);
-    float num = 0.f, den = 0.f;
-#pragma unroll
-    for (int w = 0; w < WAVES; ++w) {
-      const float f = fast_exp2(sM[w * G + h] - M);
-      num += f * sO[(w * G + h) * kHeadDim + ch];
-      den += f * sL[w * G + h];
-    }
-    if (a.n_split == 1) {
-      a.out[out_base + idx] = f32_to_bf16(den > 0.f ? num / den : 0.f);
-      if (ch == 0 && a.out_lse)
-        a.out_lse[(int64_t)b * c.n_q_heads + g * G + h] = den > 0.f ? (M + log2f(den)) * kLn2 : -INFINITY;
-    } else {
-      // write-through stores: visible device-wide once acknowledged, no cache flush needed
-      float* pr = a.partial + (((int64_t)unit * a.n_split + split) * G + h) * kPartialStride;
-      st_agent(pr + ch, num);
-      if (ch == 0) {
-        st_agent(pr + kHeadDim, M);
-        st_agent(pr + kHeadDim + 1, den);
-      }
-    }
-  }
-  if (a.n_split == 1) return;
-
-  // ---- last workgroup of the unit merges the split partials --------------------------------------
-  __syncthreads();  // every store of this workgroup has been acknowledged
-  if (tid == 0) {
-    const uint32_t old = __hip_atomic_fetch_add(&a.counters[unit], 1u, __ATOMIC_RELAXED,
-                                                __HIP_MEMORY_SCOPE_AGENT);
-    s_last = (old == (uint32_t)a.n_split - 1u);
-  }
-  __syncthreads();
-  if (!s_last) return;
-  for (int idx = tid; idx < G * kHeadDim; idx += kThreads) {
-    const int h = idx / kHeadDim, ch = idx % kHeadDim;
-    const float* pr = a.partial + ((int64_t)unit * a.n_split * G + h) * kPartialStride;
-    const int64_t sstride = (int64_t)G * kPartialStride;
-    float M = kNegBig, num = 0.f, den = 0.f;
-    // eight splits per batch, every load of a batch in flight before the first use
-    for (int s0 = 0; s0 < a.n_split; s0 += 8) {
-      float ms[8], ls[8], os[8];
-#pragma unroll
-      for (int t = 0; t < 8; ++t) {
-        const bool ok = s0 + t < a.n_split;
-        const float* ps = pr + (ok ? s0 + t : s0) * sstride;
-        ms[t] = ld_agent(ps + kHeadDim);
-        ls[t] = ld_agent(ps + kHeadDim + 1);
-        os[t] = ld_agent(ps + ch);
-        if (!ok) { ms[t] = kNegBig; ls[t] = 0.f; os[t] = 0.f; }
-      }
-      float Mb = M;
-#pragma unroll
-      for (int t = 0; t < 8; ++t) Mb = fmaxf(Mb, ms[t]);
-      const float fo = fast_exp2(M - Mb);
-      num *= fo;
-      den *= fo;
-#pragma unroll
-      for (int t = 0; t < 8; ++t) {
-        const float f = fast_exp2(ms[t] - Mb);
-        num += f * os[t];
-        den += f * ls[t];
-      }
-      M = Mb;
-    }
-    a.out[out_base + idx] = f32_to_bf16(den > 0.f ? num / den : 0.f);
-    if (ch == 0 && a.out_lse)
-      a.out_lse[(int64_t)b * c.n_q_heads + g * G + h] = den > 0.f ? (M + log2f(den)) * kLn2 : -INFINITY;
-  }
-  if (tid == 0) __hip_atomic_store(&a.counters[unit], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  const TailPatch none = {-1, 0, nullptr, nullptr};
+  attend_block<WAVES, NP>(c, a, unit, split, n, list, smem, &s_last, none);
 }
 
 __global__ void zero_u32_kernel(uint32_t* p, int n) {

@@ -68,6 +68,17 @@ __host__ __device__ __forceinline__ int pages_to_pick(int n, int ps, int T) {
   return kp < P ? kp : P;
 }
 
+// A token that is being appended in the same launch that attends to it (Section 3.4 Step 1: the
+// summaries follow every new key).  Its key / value are not read back from the pools: every consumer
+// patches them in from these LDS copies, so it does not matter whether the workgroup that writes them
+// to memory has got there yet.  page < 0: nothing is being appended.
+struct TailPatch {
+  int page;            // logical page that receives the token
+  int slot;            // position inside that page
+  const bf16_t* knew;  // LDS, [128]
+  const bf16_t* vnew;  // LDS, [128]
+};
+
 // ---- launchers (defined next to their kernels); all return hipError_t ----
 hipError_t launch_page_summaries(const CacheView& c, bf16_t* kmax, bf16_t* kmin, int first_page,
                                  int n_pages, hipStream_t st);
@@ -101,6 +112,18 @@ hipError_t launch_attend(const CacheView& c, const bf16_t* q, const int32_t* pag
                          bf16_t* out, float* out_lse, void* ws, const AttendPlan& plan,
                          hipStream_t st);
 hipError_t launch_zero(void* p, size_t bytes, hipStream_t st);
+// Step 2 + Step 3 in one launch; usable when fused_decode_lds_bytes() fits kMaxLdsBytes
+constexpr size_t kMaxLdsBytes = 64 * 1024;
+size_t fused_decode_lds_bytes(const CacheView& c, int row_len, const AttendPlan& plan);
+struct AppendArgs {      // all null: plain decode
+  const bf16_t* k_new;   // [B][Hkv][128]
+  const bf16_t* v_new;
+  bf16_t* kmax;          // writable views of the summaries
+  bf16_t* kmin;
+};
+hipError_t launch_hsa_decode_fused(const CacheView& c, const SelectArgs& sa, const AppendArgs& ap,
+                                   bf16_t* out, float* out_lse, void* ws, const AttendPlan& plan,
+                                   hipStream_t st);
 uint32_t* attend_counters(void* ws, const AttendPlan& plan);
 
 hipError_t launch_append(const CacheView& c, const bf16_t* k_new, const bf16_t* v_new, bf16_t* kmax,

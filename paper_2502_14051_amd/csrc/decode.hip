@@ -1,0 +1,152 @@
+// One HSA decode step in one launch (Algorithm 1 of arXiv 2502.14051 end to end): every workgroup
+// of a (sequence, KV head) unit first runs Step 2 on its own (the selection is cheap and
+// deterministic, so the splits of a unit arrive at the same page list without talking to each other),
+// keeps the list in LDS, and goes straight on to Step 3 over its share of the list.  This removes a
+// dependent launch (about 2.7 us on MI355X) and the round trip of the list through memory from a step
+// whose whole budget is a few tens of microseconds.  The unit index is the fast grid dimension, so the
+// splits of a unit land on the same XCD and the second reader of the summary rows hits in L2.
+//
+// The APPEND variant also takes in the token generated at this step (Section 3.4 Step 1: the
+// summaries are updated each time a new key is generated): split 0 of each unit writes the key row,
+// the value column and the updated summary column for later steps, while every workgroup patches the
+// new key / value into what it reads from LDS copies, so nobody depends on those writes having
+// landed.  The sequence length is bumped by whichever workgroup of the sequence is last to have read
+// the old one (a per-sequence arrival counter in the workspace header).
+#include "attend_core.h"
+#include "select_core.h"
+
+namespace rkv {
+
+__host__ __device__ constexpr size_t round16(size_t x) { return (x + 15) / 16 * 16; }
+constexpr size_t kStageBytes = 2 * kHeadDim * sizeof(bf16_t);  // staged new key and value
+constexpr size_t kSeqCounterOff = ROCKETKV_WS_HEADER_BYTES / 2;  // per-sequence arrival counters
+
+template <int WAVES, bool APPEND>
+__global__ __launch_bounds__(WAVES* kWave) __attribute__((amdgpu_waves_per_eu(2)))
+void hsa_decode_kernel(CacheView c, SelectArgs sa, AttendArgs aa, AppendArgs ap, uint32_t* seq_counters) {
+  constexpr int NT = WAVES * kWave;
+  extern __shared__ __align__(16) unsigned char dsm[];  // [staged k,v][list][selection scratch | merge buffer]
+  __shared__ int s_last;
+  __shared__ int s_n0;
+  const int tid = threadIdx.x;
+  const int unit = blockIdx.x, split = blockIdx.y;
+  const int b = unit / c.n_kv_heads, g = unit % c.n_kv_heads;
+  bf16_t* s_knew = reinterpret_cast<bf16_t*>(dsm);
+  bf16_t* s_vnew = s_knew + kHeadDim;
+  int32_t* list = reinterpret_cast<int32_t*>(dsm + kStageBytes);
+  unsigned char* region = dsm + kStageBytes + round16((size_t)sa.row_len * sizeof(int32_t));
+  SelectShared<NT>& sh = *reinterpret_cast<SelectShared<NT>*>(region);
+  uint32_t* keys = reinterpret_cast<uint32_t*>(region + round16(sizeof(SelectShared<NT>)));
+
+  TailPatch tp = {-1, 0, s_knew, s_vnew};
+  for (int i = tid; i < sa.row_len; i += NT) list[i] = -1;
+  int n = 0;
+  uint32_t arrivals = 0;
+  bf16_t kb = 0, vb = 0;
+  if (!APPEND) {
+    n = c.seq_lens[b];  // in flight during the channel pick, which does not need it
+  } else {
+    // One thread reads the old length for the whole workgroup; later the workgroup reports that read
+    // to the per-sequence counter, and the one that finds every other workgroup of the sequence has
+    // reported stores the new length at the very end: no thread anywhere sees the length change
+    // under it.
+    if (tid == 0) s_n0 = c.seq_lens[b];
+    if (tid < kHeadDim) {
+      const int64_t src = ((int64_t)b * c.n_kv_heads + g) * kHeadDim + tid;
+      kb = ap.k_new[src];
+      vb = ap.v_new[src];
+      s_knew[tid] = kb;
+      s_vnew[tid] = vb;
+    }
+  }
+  select_channels<NT>(c, sa, unit, sh, split == 0);  // ends with a barrier: s_n0 and the staging are visible
+  bool room = false;
+  if (APPEND) {
+    const int n0 = s_n0;
+    n = n0;
+    room = n0 < c.pages_cap * kAttnPage;
+    if (room) {
+      tp.page = n0 / kAttnPage;
+      tp.slot = n0 % kAttnPage;
+      n = n0 + 1;
+    }
+  }
+  // the summary column the new key goes into, fetched now (beside the row loads) and stored at the end
+  bf16_t old_max = 0, old_min = 0;
+  const int64_t sum_off = ((int64_t)unit * kHeadDim + (tid & (kHeadDim - 1))) * c.pages_cap + (room ? tp.page : 0);
+  if (APPEND && room && split == 0 && tid < kHeadDim && tp.slot != 0) {
+    old_max = ap.kmax[sum_off];
+    old_min = ap.kmin[sum_off];
+  }
+  select_pages<NT>(c, sa, unit, n, sh, keys, list, split == 0, tp);
+  __syncthreads();  // list complete; the selection scratch is dead and becomes the merge buffer
+  // Runs after this thread's last K/V tile, so that the stores and the counter round trip drain under
+  // the merges: split 0 of the unit stores the key row, the value column and the updated summary
+  // column for later steps, and thread 0 reports this workgroup's read of the old length.
+  auto write_back = [&]() {
+    if (!APPEND) return;
+    if (tid == 0)
+      arrivals = __hip_atomic_fetch_add(&seq_counters[b], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (room && split == 0 && tid < kHeadDim) {
+      const int64_t pp = phys_page(c, b, tp.page);
+      if (pp >= 0) {
+        const int64_t base = pp * c.stride_page + (int64_t)g * c.stride_head;
+        c.k_pool[base + tp.slot * kHeadDim + tid] = kb;
+        c.v_pool[base + tid * kAttnPage + tp.slot] = vb;
+      }
+      const float x = bf16_to_f32(kb);
+      if (tp.slot == 0 || x > bf16_to_f32(old_max)) ap.kmax[sum_off] = kb;
+      if (tp.slot == 0 || x < bf16_to_f32(old_min)) ap.kmin[sum_off] = kb;
+    }
+  };
+  attend_block<WAVES, 1>(c, aa, unit, split, n, list, reinterpret_cast<float*>(region), &s_last, tp, write_back);
+
+  if (APPEND) {
+    // the last workgroup of the sequence to have read the old length stores the new one
+    if (tid == 0 && arrivals == (uint32_t)c.n_kv_heads * gridDim.y - 1u) {
+      if (room) c.seq_lens[b] = n;
+      __hip_atomic_store(&seq_counters[b], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
+}
+
+size_t fused_decode_lds_bytes(const CacheView& c, int row_len, const AttendPlan& plan) {
+  const size_t sel = round16(plan.waves == 8 ? sizeof(SelectShared<512>) : sizeof(SelectShared<256>)) +
+                     (size_t)((c.pages_cap + 7) / 8 * 8) * sizeof(uint32_t);
+  const size_t mrg = (size_t)plan.waves * c.group * (kHeadDim + 2) * sizeof(float);
+  return kStageBytes + round16((size_t)row_len * sizeof(int32_t)) + (sel > mrg ? sel : mrg);
+}
+
+hipError_t launch_hsa_decode_fused(const CacheView& c, const SelectArgs& sa, const AppendArgs& ap,
+                                   bf16_t* out, float* out_lse, void* ws, const AttendPlan& plan,
+                                   hipStream_t st) {
+  AttendArgs a;
+  a.q = sa.q;
+  a.pages = nullptr;
+  a.row_len = sa.row_len;
+  a.out = out;
+  a.out_lse = out_lse;
+  a.partial = reinterpret_cast<float*>(static_cast<char*>(ws) + plan.partial_off);
+  a.counters = attend_counters(ws, plan);
+  a.n_split = plan.n_split;
+  a.chunk = plan.chunk;
+  a.per_wave = plan.per_wave;
+  uint32_t* seq_counters = reinterpret_cast<uint32_t*>(static_cast<char*>(ws) + plan.counter_off + kSeqCounterOff);
+  const size_t smem = fused_decode_lds_bytes(c, sa.row_len, plan);
+  const dim3 grid(c.batch * c.n_kv_heads, plan.n_split);
+  const bool append = ap.k_new != nullptr;
+  if (plan.waves == 8) {
+    if (append)
+      hipLaunchKernelGGL((hsa_decode_kernel<8, true>), grid, dim3(8 * kWave), smem, st, c, sa, a, ap, seq_counters);
+    else
+      hipLaunchKernelGGL((hsa_decode_kernel<8, false>), grid, dim3(8 * kWave), smem, st, c, sa, a, ap, seq_counters);
+  } else {
+    if (append)
+      hipLaunchKernelGGL((hsa_decode_kernel<4, true>), grid, dim3(4 * kWave), smem, st, c, sa, a, ap, seq_counters);
+    else
+      hipLaunchKernelGGL((hsa_decode_kernel<4, false>), grid, dim3(4 * kWave), smem, st, c, sa, a, ap, seq_counters);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace rkv

@@ -1,0 +1,327 @@
+// HSA Step 2 (Algorithm 1 of arXiv 2502.14051, assignments i1, g, P, s1, i2) as a workgroup-level
+// routine: one workgroup of NT threads handles one (sequence, KV head).  It picks the top-k1
+// channels of the group-summed |q|, streams only those rows of the channel-major page summaries
+// (K_max where the group-summed q is >= 0, K_min otherwise), forms one fp32 score per page in LDS
+// and keeps the top-kp pages with an exact 4-pass radix select.  Ties go to the lower index in both
+// picks; the page list comes out ascending.
+//
+// Traffic: k1 rows of P bf16 values, read as 16-byte runs of eight pages; everything else lives in
+// LDS.  Summation order is fixed, so results are bit-reproducible run to run.  The routine is
+// latency-bound (a chain of a few dependent memory and LDS round trips), hence the batched loads,
+// the one-barrier radix passes and the lane-shift scans.
+#pragma once
+
+#include "common.h"
+
+namespace rkv {
+
+__device__ __forceinline__ uint32_t f32_order_key(float f) {
+  const uint32_t u = __float_as_uint(f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);  // larger float <=> larger unsigned key
+}
+
+template <int NT>
+struct SelectShared {
+  __align__(16) float s_abs[kHeadDim];
+  float s_sum[kHeadDim];
+  int s_chan[kHeadDim];
+  float s_wgt[kHeadDim];
+  int s_rank[NT];
+  float partial[NT * 8];
+  __align__(16) uint32_t hist[4][256];  // one histogram per radix pass
+  uint32_t wsum[NT / kWave];
+  uint32_t cnt0;
+};
+
+// exclusive prefix sum of one uint32 per thread over the NT-thread workgroup
+template <int NT>
+__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* wsum) {
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const uint32_t inc = wave_incl_scan(v);
+  if (lane == kWave - 1) wsum[wave] = inc;
+  __syncthreads();
+  uint32_t base = 0;
+  for (int w = 0; w < wave; ++w) base += wsum[w];
+  __syncthreads();
+  return base + inc - v;
+}
+
+// accumulate eight rows' worth of eight-page runs; every load of the batch is issued before use
+__device__ __forceinline__ void score_rows8(const SelectArgs& a, const int* s_chan, const float* s_wgt,
+                                            int64_t rows, int pages_cap, int o, int j0, int jstep,
+                                            const TailPatch& tp, float (&acc)[8]) {
+  uint4 v[8];
+  float w[8];
+#pragma unroll
+  for (int t = 0; t < 8; ++t) {
+    const int j = j0 + t * jstep;
+    w[t] = 0.f;
+    v[t] = make_uint4(0, 0, 0, 0);
+    if (j < a.k1) {
+      w[t] = s_wgt[j];
+      const bf16_t* row = (w[t] >= 0.f ? a.kmax : a.kmin) + (rows + s_chan[j]) * pages_cap + o * 8;
+      v[t] = *reinterpret_cast<const uint4*>(row);
+    }
+  }
+  if (tp.page >= 0 && o == (tp.page >> 3)) {
+    // this run of eight pages holds the page that is receiving a token: fold the new key into its
+    // bound (or start the bound from it when the token opens the page); idempotent if memory
+    // already holds the updated value
+    const int e = tp.page & 7;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      const int j = j0 + t * jstep;
+      if (j < a.k1) {
+        const uint32_t kn = tp.knew[s_chan[j]];
+        uint32_t x[4] = {v[t].x, v[t].y, v[t].z, v[t].w};
+#pragma unroll
+        for (int wd = 0; wd < 4; ++wd) {
+          if (wd == (e >> 1)) {
+            const uint32_t old = (e & 1) ? (x[wd] >> 16) : (x[wd] & 0xffffu);
+            const float fo = bf16_to_f32((bf16_t)old), fn = bf16_to_f32((bf16_t)kn);
+            const bool take_new = tp.slot == 0 || (w[t] >= 0.f ? fn > fo : fn < fo);
+            const uint32_t val = take_new ? kn : old;
+            x[wd] = (e & 1) ? ((x[wd] & 0xffffu) | (val << 16)) : ((x[wd] & 0xffff0000u) | val);
+          }
+        }
+        v[t] = make_uint4(x[0], x[1], x[2], x[3]);
+      }
+    }
+  }
+#pragma unroll
+  for (int t = 0; t < 8; ++t) {
+    const uint32_t x[4] = {v[t].x, v[t].y, v[t].z, v[t].w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      acc[2 * i] = fmaf(w[t], bf16lo_to_f32(x[i]), acc[2 * i]);
+      acc[2 * i + 1] = fmaf(w[t], bf16hi_to_f32(x[i]), acc[2 * i + 1]);
+    }
+  }
+}
+
+// Step 2, first half (needs only q): a = sum_h |q|, s = sum_h q, i1 = top-k1 channels of a, left in
+// sh.s_chan / sh.s_wgt.  All NT threads of the workgroup take part; ends with a barrier.
+template <int NT>
+__device__ __forceinline__ void select_channels(const CacheView& c, const SelectArgs& a, int unit,
+                                                SelectShared<NT>& sh, bool write_global) {
+  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+  const int b = unit / c.n_kv_heads, g = unit % c.n_kv_heads;
+  const int G = c.group;
+
+#pragma unroll
+  for (int i = 0; i < 4 * 256 / NT; ++i) (&sh.hist[0][0])[tid + i * NT] = 0;
+  if (write_global && a.zero_counters && tid == 0) a.zero_counters[unit] = 0;
+
+  // ---- a[c] = sum_h |q|, s[c] = sum_h q (fp32, head order) -----------------------------------
+  if (tid < kHeadDim) {
+    float sa = 0.f, ss = 0.f;
+    const bf16_t* qp = a.q + ((int64_t)b * c.n_q_heads + (int64_t)g * G) * kHeadDim + tid;
+    bf16_t qv[kMaxGroup];
+#pragma unroll
+    for (int h = 0; h < kMaxGroup; ++h) qv[h] = h < G ? qp[h * kHeadDim] : (bf16_t)0;
+#pragma unroll
+    for (int h = 0; h < kMaxGroup; ++h) {
+      if (h < G) {
+        const float x = bf16_to_f32(qv[h]);
+        sa += fabsf(x);
+        ss += x;
+      }
+    }
+    sh.s_abs[tid] = sa;
+    sh.s_sum[tid] = ss;
+  }
+  __syncthreads();
+  // ---- i1: rank by counting, compact ascending --------------------------------------------------
+  // every thread ranks channel (tid mod 128) against one slice of the channels, 4 at a time
+  {
+    constexpr int kParts = NT / kHeadDim, kSlice = kHeadDim / kParts;
+    const int ch = tid & (kHeadDim - 1), part = tid / kHeadDim;
+    const float mine = sh.s_abs[ch];
+    const float4* v4 = reinterpret_cast<const float4*>(sh.s_abs + part * kSlice);
+    int rank = 0;
+#pragma unroll
+    for (int i = 0; i < kSlice / 4; ++i) {
+      const float4 v = v4[i];
+      const int o = part * kSlice + 4 * i;
+      rank += (v.x > mine) || (v.x == mine && o + 0 < ch);
+      rank += (v.y > mine) || (v.y == mine && o + 1 < ch);
+      rank += (v.z > mine) || (v.z == mine && o + 2 < ch);
+      rank += (v.w > mine) || (v.w == mine && o + 3 < ch);
+    }
+    sh.s_rank[tid] = rank;
+  }
+  __syncthreads();
+  bool sel = false;
+  if (tid < kHeadDim) {
+    int rank = 0;
+#pragma unroll
+    for (int part = 0; part < NT / kHeadDim; ++part) rank += sh.s_rank[tid + part * kHeadDim];
+    sel = rank < a.k1;
+  }
+  const unsigned long long bal = __ballot(sel);
+  if (tid == 0) sh.cnt0 = (uint32_t)__popcll(bal);
+  __syncthreads();
+  if (sel) {
+    const int pos = __popcll(bal & ((1ull << lane) - 1ull)) + (wave == 1 ? (int)sh.cnt0 : 0);
+    sh.s_chan[pos] = tid;
+    sh.s_wgt[pos] = sh.s_sum[tid];
+    if (write_global && a.out_channels) a.out_channels[(int64_t)unit * a.k1 + pos] = tid;
+  }
+  __syncthreads();
+}
+
+// Step 2, second half for a sequence of n tokens: page scores from the picked summary rows, exact
+// top-kp pages.  `keys` is LDS scratch of ceil8(pages_cap) words.  The ascending list goes to
+// `list_lds` (if not null, kp entries) and, when `write_global`, to a.out_pages / a.out_pages2 (-1
+// padded) and the optional score output.  Returns kp.  Ends WITHOUT a final barrier: the caller
+// synchronises before reading `list_lds`.
+template <int NT>
+__device__ __forceinline__ int select_pages(const CacheView& c, const SelectArgs& a, int unit, int n,
+                                            SelectShared<NT>& sh, uint32_t* keys, int32_t* list_lds,
+                                            bool write_global, const TailPatch& tp) {
+  const int tid = threadIdx.x, lane = tid % kWave;
+  const int ps = c.page_size;
+  int P = (n + ps - 1) / ps;
+  if (P > c.pages_cap) P = c.pages_cap;
+  int kp = pages_to_pick(n, ps, a.T);
+  if (kp > P) kp = P;
+  if (kp > a.row_len) kp = a.row_len;
+  if (write_global) {
+    // -1 padding of the list rows beyond kp
+    if (a.out_pages)
+      for (int i = kp + tid; i < a.row_len; i += NT) a.out_pages[(int64_t)unit * a.row_len + i] = -1;
+    if (a.out_pages2)
+      for (int i = kp + tid; i < a.row_len2; i += NT) a.out_pages2[(int64_t)unit * a.row_len2 + i] = -1;
+  }
+  if (P == 0) return 0;
+
+  // ---- s1: page scores ---------------------------------------------------------------------------
+  const int n_oct = (P + 7) / 8;
+  const int64_t rows = (int64_t)unit * kHeadDim;
+  float* out_scores = write_global ? a.out_scores : nullptr;
+  if (n_oct < NT) {
+    int npow = 1;
+    while (npow < n_oct) npow <<= 1;
+    const int R = NT / npow;  // row groups summed separately, then in order
+    const int r = tid / npow, o = tid % npow;
+    float acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+    if (o < n_oct)
+      for (int j0 = r; j0 < a.k1; j0 += 8 * R) score_rows8(a, sh.s_chan, sh.s_wgt, rows, c.pages_cap, o, j0, R, tp, acc);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) sh.partial[(r * npow + o) * 8 + i] = acc[i];
+    __syncthreads();
+    for (int p = tid; p < npow * 8; p += NT) {
+      float s = 0.f;
+      for (int rr = 0; rr < R; ++rr) s += sh.partial[rr * npow * 8 + p];
+      if (p < n_oct * 8) {
+        if (p < P && out_scores) out_scores[(int64_t)unit * c.pages_cap + p] = s;
+        if (p >= P) s = -INFINITY;
+        else if (p >= P - a.n_recent) s = INFINITY;
+        keys[p] = f32_order_key(s);
+      }
+    }
+  } else {
+    for (int o = tid; o < n_oct; o += NT) {
+      float acc[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+      for (int j0 = 0; j0 < a.k1; j0 += 8) score_rows8(a, sh.s_chan, sh.s_wgt, rows, c.pages_cap, o, j0, 1, tp, acc);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int p = o * 8 + i;
+        float s = acc[i];
+        if (p < P && out_scores) out_scores[(int64_t)unit * c.pages_cap + p] = s;
+        if (p >= P) s = -INFINITY;
+        else if (p >= P - a.n_recent) s = INFINITY;
+        keys[p] = f32_order_key(s);
+      }
+    }
+  }
+  __syncthreads();
+
+  // ---- i2: exact kp-th largest key by 4 x 8-bit radix passes -------------------------------------
+  uint32_t tau = 0, need_eq = (uint32_t)P;  // defaults select everything (kp == P)
+  if (kp < P) {
+    uint32_t prefix = 0, mask = 0, k = (uint32_t)kp;
+    for (int pass = 0; pass < 4; ++pass) {
+      const int shift = 24 - 8 * pass;
+      for (int p = tid; p < P; p += NT) {
+        const uint32_t key = keys[p];
+        if ((key & mask) == prefix) atomicAdd(&sh.hist[pass][(key >> shift) & 255u], 1u);
+      }
+      __syncthreads();
+      // every wavefront finds the bucket holding the k-th largest on its own (no broadcast needed):
+      // lane L owns bins 4(63-L)..4(63-L)+3, so a prefix sum over lanes counts the keys in higher bins
+      const int b0 = 4 * (kWave - 1 - lane);
+      const uint4 h = *reinterpret_cast<const uint4*>(&sh.hist[pass][b0]);
+      const uint32_t s3 = h.w, s2 = h.z + s3, s1 = h.y + s2, s0 = h.x + s1;  // suffix sums inside the lane
+      const uint32_t above = wave_incl_scan(s0) - s0;                          // keys in bins of lower lanes
+      const uint32_t in[4] = {above + s0, above + s1, above + s2, above + s3};
+      const uint32_t hc[4] = {h.x, h.y, h.z, h.w};
+      int found = -1;
+      uint32_t newk = 0;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const uint32_t exc = in[j] - hc[j];
+        if (exc < k && k <= in[j]) {
+          found = b0 + j;
+          newk = k - exc;
+        }
+      }
+      const unsigned long long who = __ballot(found >= 0);
+      const int src = __ffsll((long long)who) - 1;
+      const uint32_t bucket = (uint32_t)__builtin_amdgcn_readlane(found, src);
+      k = (uint32_t)__builtin_amdgcn_readlane((int)newk, src);
+      prefix |= bucket << shift;
+      mask |= 0xffu << shift;
+    }
+    tau = prefix;
+    need_eq = k;
+  }
+
+  // ---- emit ascending: every key > tau, plus the first need_eq keys == tau -----------------------
+  const int ipt = (P + NT - 1) / NT;
+  const int lo = min(P, tid * ipt), hi = min(P, lo + ipt);
+  uint32_t cnt = 0;  // low 16 bits: keys > tau, high 16 bits: keys == tau
+  for (int p = lo; p < hi; ++p) {
+    const uint32_t key = keys[p];
+    cnt += (key > tau) ? 1u : 0u;
+    cnt += (key == tau) ? 0x10000u : 0u;
+  }
+  const uint32_t before = block_excl_scan<NT>(cnt, sh.wsum);
+  uint32_t gt = before & 0xffffu, eq = before >> 16;
+  for (int p = lo; p < hi; ++p) {
+    const uint32_t key = keys[p];
+    bool take = key > tau;
+    if (key == tau) {
+      take = eq < need_eq;
+      ++eq;
+    }
+    if (take) {
+      const uint32_t eq_taken = (key == tau) ? eq - 1 : min(eq, need_eq);
+      const uint32_t pos = gt + eq_taken;
+      if ((int)pos < kp) {
+        if (list_lds) list_lds[pos] = p;
+        if (write_global) {
+          if (a.out_pages) a.out_pages[(int64_t)unit * a.row_len + pos] = p;
+          if (a.out_pages2 && (int)pos < a.row_len2) a.out_pages2[(int64_t)unit * a.row_len2 + pos] = p;
+        }
+      }
+    }
+    if (key > tau) ++gt;
+  }
+  return kp;
+}
+
+// Both halves back to back.
+template <int NT>
+__device__ __forceinline__ int select_block(const CacheView& c, const SelectArgs& a, int unit, int n,
+                                            SelectShared<NT>& sh, uint32_t* keys, int32_t* list_lds,
+                                            bool write_global, const TailPatch& tp) {
+  select_channels<NT>(c, a, unit, sh, write_global);
+  return select_pages<NT>(c, a, unit, n, sh, keys, list_lds, write_global, tp);
+}
+
+}  // namespace rkv

@@ -22,7 +22,7 @@ MAX_PAGES = 8192
 
 EXPORTS = [
     "rocketkv_workspace_bytes", "rocketkv_workspace_init", "rocketkv_build_page_summaries", "rocketkv_hsa_select",
-    "rocketkv_attend", "rocketkv_hsa_decode", "rocketkv_dense_decode", "rocketkv_append_kv",
+    "rocketkv_attend", "rocketkv_hsa_decode", "rocketkv_hsa_decode_append", "rocketkv_dense_decode", "rocketkv_append_kv",
     "rocketkv_snapkv_compress", "rocketkv_last_error", "rocketkv_version",
 ]
 
@@ -72,6 +72,8 @@ def lib():
         L.rocketkv_attend.argtypes = [cp, vp, vp, i32, vp, vp, vp, sz, vp]
         L.rocketkv_hsa_decode.restype = i32
         L.rocketkv_hsa_decode.argtypes = [cp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+        L.rocketkv_hsa_decode_append.restype = i32
+        L.rocketkv_hsa_decode_append.argtypes = [cp, vp, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
         L.rocketkv_dense_decode.restype = i32
         L.rocketkv_dense_decode.argtypes = [cp, vp, vp, vp, vp, sz, vp]
         L.rocketkv_append_kv.restype = i32
@@ -254,6 +256,15 @@ def hsa_decode(cache: Cache, q, kmax, kmin, channel_budget: int, token_budget: i
                                      token_budget, n_recent_pages, _ptr(out), _ptr(out_lse),
                                      _ptr(out_pages), _ptr(out_channels), _ptr(workspace),
                                      workspace.numel(), _stream(stream)))
+
+
+def hsa_decode_append(cache: Cache, q, k_new, v_new, kmax, kmin, channel_budget: int, token_budget: int,
+                      n_recent_pages: int, out, out_lse, out_pages, out_channels, workspace, stream=None):
+    st = cache.struct()
+    _check(lib().rocketkv_hsa_decode_append(C.byref(st), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(kmax),
+                                            _ptr(kmin), channel_budget, token_budget, n_recent_pages,
+                                            _ptr(out), _ptr(out_lse), _ptr(out_pages), _ptr(out_channels),
+                                            _ptr(workspace), workspace.numel(), _stream(stream)))
 
 
 def dense_decode(cache: Cache, q, out, out_lse, workspace, stream=None):

@@ -477,3 +477,84 @@ def test_snapkv_then_decode_pipeline(env, oracle):
     # planted tokens survive both stages: HSA over the compacted cache matches dense over the prompt
     yd, _ = oracle.dense_decode(d["q"], d["K"], d["V"], d["seq_lens"])
     assert np.median(np.abs(wl.bf16_bits_to_f64(wl.to_bits(out)) - yd)) < 2e-2
+
+
+# ------------------------------------------------------------------ decode step with the new token folded in
+@pytest.mark.parametrize("name,over,lens0,shuffle", [
+    ("tiny", dict(batch=3, context=300, token_budget=96, heavy_nats=2.0), (250, 239, 0), True),
+    ("llama8b_step_b16", dict(batch=2, context=4200, n_layers=1, token_budget=1024), (4090, 4096), False),
+    ("llama70b_step_b16", dict(batch=1, context=600, n_layers=1, token_budget=128, n_heavy=4), (555,), False),
+])
+def test_decode_append_equals_append_then_decode(env, oracle, name, over, lens0, shuffle):
+    """rocketkv_hsa_decode_append must leave everything exactly as rocketkv_append_kv followed by
+    rocketkv_hsa_decode does, step after step, across page boundaries; and both must match the oracle
+    on the grown cache."""
+    torch, rk, dev = env
+    w = small(name, **over)
+    steps = 20
+    say("decode+append", name, over, lens0, shuffle)
+    full = wl.generate(w)
+    lens0 = np.asarray(lens0, dtype=np.int32)
+    B, Hkv = w.batch, w.n_kv_heads
+    cap = int(lens0.max()) + steps + 5
+    base = dict(full)
+    base["seq_lens"] = lens0
+
+    def fresh():
+        c, q = to_device_cache(rk, torch, base, w.n_q_heads, 16, dev, pages_cap=(cap + 15) // 16,
+                               shuffle_rng=np.random.default_rng(8) if shuffle else None)
+        kx, kn = rk.alloc_summaries(c)
+        rk.build_page_summaries(c, kx, kn)
+        return c, q, kx, kn
+
+    A, q, Akx, Akn = fresh()
+    Bc, _, Bkx, Bkn = fresh()
+    row = rk.pages_row_len(A, w.token_budget)
+    wsA = rk.alloc_workspace(rk.OP_HSA_DECODE, A, w.token_budget)
+    wsB = rk.alloc_workspace(rk.OP_HSA_DECODE, Bc, w.token_budget)
+    outA = torch.empty((B, w.n_q_heads, 128), dtype=torch.bfloat16, device=dev)
+    outB = torch.empty_like(outA)
+    pgA = torch.empty((B, Hkv, row), dtype=torch.int32, device=dev)
+    pgB = torch.empty_like(pgA)
+    rng = np.random.default_rng(9)
+    Kref = full["K"].copy()
+    Vref = full["V"].copy()
+    Kref = np.concatenate([Kref, np.zeros((B, Hkv, cap, 128), dtype=np.uint16)], axis=2)
+    Vref = np.concatenate([Vref, np.zeros((B, Hkv, cap, 128), dtype=np.uint16)], axis=2)
+    lens = lens0.copy()
+    for s in range(steps):
+        kn_new = wl.f32_to_bf16_bits(rng.standard_normal((B, Hkv, 128)).astype(np.float32) * 1.5)
+        vn_new = wl.f32_to_bf16_bits(rng.standard_normal((B, Hkv, 128)).astype(np.float32))
+        for b in range(B):
+            Kref[b, :, lens[b]] = kn_new[b]
+            Vref[b, :, lens[b]] = vn_new[b]
+        lens += 1
+        kt, vt = wl.from_bits(kn_new, dev), wl.from_bits(vn_new, dev)
+        rk.hsa_decode_append(A, q, kt, vt, Akx, Akn, w.channel_budget, w.token_budget, 1, outA, None, pgA,
+                             None, wsA)
+        rk.append_kv(Bc, kt, vt, Bkx, Bkn)
+        rk.hsa_decode(Bc, q, Bkx, Bkn, w.channel_budget, w.token_budget, 1, outB, None, pgB, None, wsB)
+        torch.cuda.synchronize()
+        assert A.seq_lens.cpu().numpy().tolist() == lens.tolist(), f"step {s}"
+        assert torch.equal(pgA, pgB), f"step {s}: page lists differ"
+        assert torch.equal(outA, outB), f"step {s}: outputs differ"
+    assert torch.equal(Akx, Bkx) and torch.equal(Akn, Bkn)
+    KA, VA = rk.unpack_cache(A)
+    KB, VB = rk.unpack_cache(Bc)
+    KA, VA, KB, VB = (wl.to_bits(t) for t in (KA, VA, KB, VB))
+    for b in range(B):
+        assert np.array_equal(KA[b, :, :lens[b]], Kref[b, :, :lens[b]])
+        assert np.array_equal(VA[b, :, :lens[b]], Vref[b, :, :lens[b]])
+        assert np.array_equal(KB[b, :, :lens[b]], Kref[b, :, :lens[b]])
+    # oracle on the grown cache
+    nmax = int(lens.max())
+    d = dict(q=full["q"], K=np.ascontiguousarray(Kref[:, :, :nmax]), V=np.ascontiguousarray(Vref[:, :, :nmax]),
+             seq_lens=lens)
+    gp = pgA.cpu().numpy()
+    check_selection(oracle, d, w, A.pages_cap, gp, None, None, n_recent=1)
+    want_y, _ = oracle.attend_given(d["q"], d["K"], d["V"], lens, 16, gp)
+    assert_attention_close(wl.to_bits(outA), want_y, "decode+append y")
+    want_max, want_min = oracle.build_summaries(d["K"], lens, 16, A.pages_cap)
+    valid = ~np.isnan(want_max)
+    assert np.array_equal(wl.bf16_bits_to_f64(wl.to_bits(Akx))[valid], want_max[valid])
+    assert np.array_equal(wl.bf16_bits_to_f64(wl.to_bits(Akn))[valid], want_min[valid])
