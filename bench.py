@@ -30,8 +30,8 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published peak
 # HBM bytes per launch of the fused kernel on this workload from rocprofv3 FETCH_SIZE / WRITE_SIZE
-# (profiles/hsa_decode_kernel_llama8b_step_b16_pmc.txt); None until measured for the current kernel.
-TRAFFIC_BYTES_PER_LAUNCH = None
+# (profiles/hsa_decode_kernel_llama8b_step_b16_pmc.txt): (FETCH_SIZE x 2.0 + WRITE_SIZE) KiB.
+TRAFFIC_BYTES_PER_LAUNCH = 75136819
 
 
 def parse():
@@ -47,6 +47,7 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--kernel-reps", type=int, default=20)
+    ap.add_argument("--tune", type=str, default="", help="waves,pairs_per_wave override of the attention split")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (a known-size reference "
                          "for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
@@ -67,6 +68,9 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
     rk.lib()
+    if args.tune:
+        wv, ppw = (int(x) for x in args.tune.split(","))
+        rk.tune_attend(wv, ppw, 0)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
