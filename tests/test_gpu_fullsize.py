@@ -1,0 +1,195 @@
+"""GPU parity at the benchmark's full shapes, in the launch configuration bench.py times.
+
+The whole tensors are too large for the oracle, so a sample of (sequence, KV head) units is
+downloaded and checked one by one: SnapKV kept sets, the compacted cache, page selection and the
+attention output of the fused decode-with-append step.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+from paper_2502_14051_amd import workloads as wl
+from helpers import assert_attention_close, assert_topk_within_band
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    from paper_2502_14051_amd import rocketkv as rk
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    rk.lib()
+    return torch, rk, torch.device("cuda:0")
+
+
+def say(*a):
+    print("[case]", *a, flush=True)
+    sys.stdout.flush()
+
+
+def unit_rows(t, units, Hkv):
+    """Download rows (b, g) of a [B][Hkv]... device tensor as uint16 bits."""
+    return [wl.to_bits(t[b, g]) for (b, g) in units]
+
+
+FULL_CASES = [
+    # workload, batch override, sampled units
+    ("llama8b_step_b16", None, [(0, 0), (3, 5), (9, 2), (15, 7)]),
+    ("llama70b_step_b16", 4, [(0, 1), (3, 6)]),          # G = 8; batch cut to keep the test short
+    ("mistral_snap_128k", None, [(0, 0), (0, 5)]),         # 131072-token prompt, keep 8192, budget 2048
+]
+
+
+@pytest.mark.parametrize("name,batch,units", FULL_CASES)
+def test_full_shape_pipeline_sampled(env, oracle, name, batch, units):
+    torch, rk, dev = env
+    w = wl.CONFIGS[name]
+    if batch:
+        w = wl.scaled(w, batch=batch)
+    say("full-size", name, "batch", w.batch, "context", w.context, "keep", w.snap_keep, "T", w.token_budget)
+    B, Hq, Hkv, G = w.batch, w.n_q_heads, w.n_kv_heads, w.group
+    N, W, T, k1 = w.snap_keep, w.window, w.token_budget, w.channel_budget
+    d = wl.generate_device(w, 0, dev, with_obs=True)
+    src = rk.pack_cache(d["K"], d["V"], d["seq_lens"].cpu().numpy(), Hq, 16)
+    steps = 3
+    dst = rk.alloc_cache(B, Hq, Hkv, 128, 16, N // 16 + 8, dev, zero=True)
+    kept = torch.empty((B, Hkv, N), dtype=torch.int32, device=dev)
+    ws = rk.alloc_workspace(rk.OP_SNAPKV, src, W, N)
+    rk.snapkv_compress(d["qobs"], src, W, w.pool_kernel, N, dst, kept, ws)
+    kmax, kmin = rk.alloc_summaries(dst)
+    rk.build_page_summaries(dst, kmax, kmin)
+    torch.cuda.synchronize()
+    assert dst.seq_lens.cpu().numpy().tolist() == [N] * B
+
+    # ---- stage 1 on the sampled units
+    S = w.context
+    L = S - W
+    Kc, Vc = rk.unpack_cache(dst)
+    kept_h = kept.cpu().numpy()
+    for (b, g) in units:
+        Ku = wl.to_bits(d["K"][b, g])[None, None]
+        qo = wl.to_bits(d["qobs"][b, g * G:(g + 1) * G])[None]
+        ref = oracle.snapkv(qo, Ku, [S], w.pool_kernel, N, want_votes=True)
+        row = kept_h[b, g]
+        assert row[N - W:].tolist() == list(range(L, S))
+        assert_topk_within_band(ref["pooled"][0, 0, :L], row[:N - W], N - W, f"kept b{b} g{g}")
+        assert np.array_equal(wl.to_bits(Kc[b, g, :N]), Ku[0, 0][row])
+        assert np.array_equal(wl.to_bits(Vc[b, g, :N]), wl.to_bits(d["V"][b, g])[row])
+
+    # ---- a few fused decode-with-append steps, exactly as the benchmark issues them
+    q = d["q"].contiguous()
+    out = torch.empty((B, Hq, 128), dtype=torch.bfloat16, device=dev)
+    row_len = rk.pages_row_len(dst, T)
+    pages = torch.empty((B, Hkv, row_len), dtype=torch.int32, device=dev)
+    wsd = rk.alloc_workspace(rk.OP_HSA_DECODE, dst, T)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(5)
+    new_k, new_v = [], []
+    for s in range(steps):
+        nk = torch.randn((B, Hkv, 128), generator=gen, device=dev).bfloat16()
+        nv = torch.randn((B, Hkv, 128), generator=gen, device=dev).bfloat16()
+        new_k.append(nk)
+        new_v.append(nv)
+        rk.hsa_decode_append(dst, q, nk, nv, kmax, kmin, k1, T, 0, out, None, pages, None, wsd)
+    torch.cuda.synchronize()
+    n = N + steps
+    assert dst.seq_lens.cpu().numpy().tolist() == [n] * B
+    gp = pages.cpu().numpy()
+    out_bits = wl.to_bits(out)
+    Kc, Vc = rk.unpack_cache(dst)
+    for (b, g) in units:
+        Ku = np.concatenate([wl.to_bits(Kc[b, g, :N])] + [wl.to_bits(t[b, g])[None] for t in new_k])
+        Vu = np.concatenate([wl.to_bits(Vc[b, g, :N])] + [wl.to_bits(t[b, g])[None] for t in new_v])
+        assert np.array_equal(wl.to_bits(Kc[b, g, :n]), Ku)  # the appended rows landed
+        assert np.array_equal(wl.to_bits(Vc[b, g, :n]), Vu)
+        qu = wl.to_bits(q[b, g * G:(g + 1) * G])
+        ref = oracle.hsa_decode(qu[None], Ku[None, None], Vu[None, None], [n], 16, k1, T, want_scores=True)
+        P = (n + 15) // 16
+        kp = oracle.pages_to_pick(n, 16, T)
+        assert_topk_within_band(ref["scores"][0, 0, :P], gp[b, g], kp, f"pages b{b} g{g}")
+        y, _ = oracle.attend_pages(qu, Ku, Vu, 16, gp[b, g][gp[b, g] >= 0])
+        assert_attention_close(out_bits[b, g * G:(g + 1) * G], y, f"y b{b} g{g}")
+        want_max, want_min = oracle.page_summaries(Ku, 16)
+        got_max = wl.bf16_bits_to_f64(wl.to_bits(kmax[b, g, :, :P]))
+        got_min = wl.bf16_bits_to_f64(wl.to_bits(kmin[b, g, :, :P]))
+        assert np.array_equal(got_max, want_max) and np.array_equal(got_min, want_min)
+
+
+def test_dense_full_context_sampled(env, oracle):
+    """The full-KV comparison kernel at the benchmark's dense shape (batch 16 x 32768 tokens)."""
+    torch, rk, dev = env
+    w = wl.CONFIGS["llama8b_step_b16"]
+    say("dense full-size", w.name)
+    d = wl.generate_device(wl.scaled(w, heavy_nats=1.0), 1, dev)
+    cache = rk.pack_cache(d["K"], d["V"], d["seq_lens"].cpu().numpy(), w.n_q_heads, 16)
+    out = torch.empty((w.batch, w.n_q_heads, 128), dtype=torch.bfloat16, device=dev)
+    lse = torch.empty((w.batch, w.n_q_heads), dtype=torch.float32, device=dev)
+    ws = rk.alloc_workspace(rk.OP_DENSE_DECODE, cache)
+    rk.dense_decode(cache, d["q"].contiguous(), out, lse, ws)
+    torch.cuda.synchronize()
+    G = w.group
+    for (b, g) in [(0, 0), (7, 3), (15, 7)]:
+        qu = wl.to_bits(d["q"][b, g * G:(g + 1) * G])[None]
+        y, l = oracle.dense_decode(qu, wl.to_bits(d["K"][b, g])[None, None], wl.to_bits(d["V"][b, g])[None, None],
+                                   [w.context])
+        assert_attention_close(wl.to_bits(out[b, g * G:(g + 1) * G]), y[0], f"dense y b{b} g{g}")
+        np.testing.assert_allclose(lse[b, g * G:(g + 1) * G].cpu().numpy(), l[0], rtol=1e-3, atol=1e-3)
+
+
+def test_long_decode_after_snapkv(env, oracle):
+    """SnapKV stage, then 256 decode steps that each append a token (the long-decode configuration):
+    checked against the oracle at several steps along the way and at the end."""
+    torch, rk, dev = env
+    w = wl.scaled(wl.CONFIGS["mistral_snap_128k"], context=16384, snap_keep=2048, token_budget=512)
+    say("long decode", w.name, "prompt", w.context, "keep", w.snap_keep, "steps 256")
+    B, Hq, Hkv, G = w.batch, w.n_q_heads, w.n_kv_heads, w.group
+    N, T, k1 = w.snap_keep, w.token_budget, w.channel_budget
+    d = wl.generate(w, with_obs=True)
+    src = rk.pack_cache(wl.from_bits(d["K"], dev), wl.from_bits(d["V"], dev), d["seq_lens"], Hq, 16)
+    dst = rk.alloc_cache(B, Hq, Hkv, 128, 16, (N + 256) // 16 + 1, dev, zero=True)
+    kept = torch.empty((B, Hkv, N), dtype=torch.int32, device=dev)
+    ws = rk.alloc_workspace(rk.OP_SNAPKV, src, w.window, N)
+    rk.snapkv_compress(wl.from_bits(d["qobs"], dev), src, w.window, w.pool_kernel, N, dst, kept, ws)
+    kmax, kmin = rk.alloc_summaries(dst)
+    rk.build_page_summaries(dst, kmax, kmin)
+    torch.cuda.synchronize()
+    gk = kept.cpu().numpy()
+    K = np.stack([d["K"][0, g, gk[0, g]] for g in range(Hkv)])[None]
+    V = np.stack([d["V"][0, g, gk[0, g]] for g in range(Hkv)])[None]
+    rng = np.random.default_rng(11)
+    out = torch.empty((B, Hq, 128), dtype=torch.bfloat16, device=dev)
+    row_len = rk.pages_row_len(dst, T)
+    pages = torch.empty((B, Hkv, row_len), dtype=torch.int32, device=dev)
+    wsd = rk.alloc_workspace(rk.OP_HSA_DECODE, dst, T)
+    check_at = {0, 1, 15, 16, 100, 255}
+    for s in range(256):
+        qs = wl.f32_to_bf16_bits(rng.standard_normal((B, Hq, 128)).astype(np.float32) * 1.3)
+        kn = wl.f32_to_bf16_bits(rng.standard_normal((B, Hkv, 128)).astype(np.float32) * 1.3)
+        vn = wl.f32_to_bf16_bits(rng.standard_normal((B, Hkv, 128)).astype(np.float32))
+        K = np.concatenate([K, kn[:, :, None]], axis=2)
+        V = np.concatenate([V, vn[:, :, None]], axis=2)
+        rk.hsa_decode_append(dst, wl.from_bits(qs, dev), wl.from_bits(kn, dev), wl.from_bits(vn, dev), kmax,
+                             kmin, k1, T, 1, out, None, pages, None, wsd)
+        if s in check_at:
+            torch.cuda.synchronize()
+            n = N + s + 1
+            assert dst.seq_lens.cpu().numpy().tolist() == [n]
+            ref = oracle.hsa_decode(qs, K, V, [n], 16, k1, T, n_recent=1, want_scores=True)
+            gp = pages.cpu().numpy()
+            P, kp = (n + 15) // 16, oracle.pages_to_pick(n, 16, T)
+            for g in range(Hkv):
+                sc = ref["scores"][0, g, :P].copy()
+                sc[P - 1] = np.inf
+                assert_topk_within_band(sc, gp[0, g], kp, f"step {s} g{g}")
+            want_y, _ = oracle.attend_given(qs, K, V, [n], 16, gp)
+            assert_attention_close(wl.to_bits(out), want_y, f"step {s} y")
+    torch.cuda.synchronize()
+    Kc, Vc = rk.unpack_cache(dst)
+    n = N + 256
+    assert np.array_equal(wl.to_bits(Kc[:, :, :n]), K) and np.array_equal(wl.to_bits(Vc[:, :, :n]), V)
+    want_max, want_min = oracle.build_summaries(K, [n], 16, dst.pages_cap)
+    valid = ~np.isnan(want_max)
+    assert np.array_equal(wl.bf16_bits_to_f64(wl.to_bits(kmax))[valid], want_max[valid])
+    assert np.array_equal(wl.bf16_bits_to_f64(wl.to_bits(kmin))[valid], want_min[valid])
