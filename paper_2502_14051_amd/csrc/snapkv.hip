@@ -11,6 +11,8 @@
 // The two score passes are the one dense contraction of the method (G*W query rows against every
 // key): they run on the matrix cores with the (head, window-row) index as the MFMA column, so a lane
 // owns a fixed set of softmax rows and their statistics stay in registers.
+#include <type_traits>
+
 #include "common.h"
 
 namespace rkv {
@@ -19,7 +21,6 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kSnapColBlocks = 8;    // 16-column blocks per wavefront (128 softmax rows)
-constexpr int kSnapChunkPages = 64;  // pages per workgroup in the score passes
 constexpr float kLog2eS = 1.4426950408889634f;
 constexpr float kNegBigS = -1.0e30f;
 
@@ -30,7 +31,7 @@ union FragS {
 
 struct SnapArgs {
   const bf16_t* qobs;
-  int W, NC, CG, n_chunks, keep, s_cap, pool_r;
+  int W, NC, CG, n_chunks, chunk_pages, keep, s_cap, pool_r;
   float* stats_part;  // [units][n_chunks][NC][2]
   float* stats;       // [units][NC][2]   (max in log2 domain, 1/sum)
   float* votes;       // [units][s_cap]
@@ -41,7 +42,8 @@ struct SnapArgs {
 __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
 
 template <bool PASS2>
-__global__ __launch_bounds__(256) void snap_score_kernel(CacheView c, SnapArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2)))
+void snap_score_kernel(CacheView c, SnapArgs a) {
   __shared__ float sM[4][kSnapColBlocks * 16], sZ[4][kSnapColBlocks * 16];
   __shared__ float sV[4][16];
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
@@ -52,9 +54,11 @@ __global__ __launch_bounds__(256) void snap_score_kernel(CacheView c, SnapArgs a
   if (S <= a.keep || S > c.pages_cap * kAttnPage) return;
   const int L = S - a.W;
   const int cgi = wave % a.CG, pw = wave / a.CG, npw = 4 / a.CG;
-  const int p_begin = chunk * kSnapChunkPages;
+  // 16-column blocks this wavefront owns that hold real softmax rows (same for all its lanes)
+  const int n_cb = __builtin_amdgcn_readfirstlane(min(kSnapColBlocks, (a.NC + 15) / 16 - cgi * kSnapColBlocks));
+  const int p_begin = chunk * a.chunk_pages;
   const int p_limit = PASS2 ? (L + kAttnPage - 1) / kAttnPage : (S + kAttnPage - 1) / kAttnPage;
-  const int p_end = min(p_begin + kSnapChunkPages, p_limit);
+  const int p_end = min(p_begin + a.chunk_pages, p_limit);
 
   FragS qf[kSnapColBlocks][4];
   int limit[kSnapColBlocks];
@@ -87,45 +91,71 @@ __global__ __launch_bounds__(256) void snap_score_kernel(CacheView c, SnapArgs a
   const float sc = kLog2eS * 0.08838834764831845f;
   const int64_t head_off = (int64_t)g * c.stride_head;
 
+  // Key tiles are requested two pages ahead of the one being scored (two register buffers used in
+  // rotation), so the memory latency is hidden behind the matrix and exponent work of the pages
+  // in between.  An absent or out-of-range page reads tile 0 of the pool and is masked below: the
+  // loads stay unconditional and the loop body straight-line.
+  const int64_t lane_off = head_off + hn * kHeadDim + kg * 8;
+  const auto fetch = [&](int p, uint4* kf) -> bool {
+    const int64_t pp = p < p_end ? phys_page(c, b, p) : -1;
+    const bf16_t* kt = c.k_pool + (pp >= 0 ? pp : 0) * c.stride_page + lane_off;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) kf[j] = *reinterpret_cast<const uint4*>(kt + j * 32);
+    return pp >= 0;
+  };
   const int n_it = p_end > p_begin ? (p_end - p_begin + npw - 1) / npw : 0;
-  for (int it = 0; it < n_it; ++it) {
+  // one page: consume buffer kn (its tile arrived by now), refill it with the page two steps on
+  const auto step = [&](int it, uint4* kn, bool& present_buf) {
     const int p = p_begin + it * npw + pw;
     const bool live = p < p_end;
-    const int64_t pp = live ? phys_page(c, b, p) : -1;
-    FragS kf[4];
-    if (pp >= 0) {
-      const bf16_t* kt = c.k_pool + pp * c.stride_page + head_off + hn * kHeadDim + kg * 8;
+    const bool present = present_buf;
+    bf16x8 kf[4];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) kf[j].u = *reinterpret_cast<const uint4*>(kt + j * 32);
-    } else {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) kf[j].u = make_uint4(0, 0, 0, 0);
-    }
+    for (int j = 0; j < 4; ++j) kf[j] = __builtin_bit_cast(bf16x8, kn[j]);
+    present_buf = fetch(p + 2 * npw, kn);
     const int tok0 = p * kAttnPage + kg * 4;
     float v[4] = {0.f, 0.f, 0.f, 0.f};
+    // A page that lies wholly inside the prefix is visible to every window row: no causal mask.
+    // Column blocks go four at a time: four independent accumulator chains keep the matrix pipe
+    // busy, and the softmax update is branch-free so the whole group schedules as one block.
+    const auto score_page = [&](auto masked_tag) {
+      constexpr bool MASKED = decltype(masked_tag)::value;
 #pragma unroll
-    for (int cb = 0; cb < kSnapColBlocks; ++cb) {
-      if ((cgi * kSnapColBlocks + cb) * 16 >= a.NC) continue;  // uniform: whole block unused
-      f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+      for (int qd = 0; qd < kSnapColBlocks / 4; ++qd) {
+        if (qd * 4 >= n_cb) break;  // wave-uniform: the rest of this wavefront's blocks are unused
+        f32x4 acc[4];
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[j].v, qf[cb][j].v, acc, 0, 0, 0);
-      float s[4];
+        for (int i = 0; i < 4; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int r = 0; r < 4; ++r) s[r] = (pp >= 0 && tok0 + r <= limit[cb]) ? acc[r] * sc : -INFINITY;
-      if (!PASS2) {
-        const float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
-        if (mx > m[cb]) {
-          z[cb] *= exp2_fast(m[cb] - mx);
-          m[cb] = mx;
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[j], qf[qd * 4 + i][j].v, acc[i], 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int cb = qd * 4 + i;
+          float s[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            s[r] = acc[i][r] * sc;
+            if (MASKED) s[r] = (present && tok0 + r <= limit[cb]) ? s[r] : -INFINITY;
+          }
+          if (!PASS2) {
+            const float mn = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), m[cb]);
+            z[cb] = z[cb] * exp2_fast(m[cb] - mn) + exp2_fast(s[0] - mn) + exp2_fast(s[1] - mn) +
+                    exp2_fast(s[2] - mn) + exp2_fast(s[3] - mn);
+            m[cb] = mn;
+          } else {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) v[r] += exp2_fast(s[r] - M2[cb]) * invZ[cb];
+          }
         }
-        z[cb] += exp2_fast(s[0] - m[cb]) + exp2_fast(s[1] - m[cb]) + exp2_fast(s[2] - m[cb]) +
-                 exp2_fast(s[3] - m[cb]);
-      } else {
-#pragma unroll
-        for (int r = 0; r < 4; ++r) v[r] += exp2_fast(s[r] - M2[cb]) * invZ[cb];
       }
-    }
+    };
+    if (present && p * kAttnPage + kAttnPage - 1 <= L)
+      score_page(std::false_type{});
+    else
+      score_page(std::true_type{});
     if (PASS2) {
       // sum the 16 columns held by the lanes of one token group, then the column groups
 #pragma unroll
@@ -153,6 +183,16 @@ __global__ __launch_bounds__(256) void snap_score_kernel(CacheView c, SnapArgs a
           if (tok0 + r < L) a.votes[(int64_t)unit * a.s_cap + tok0 + r] = v[r];
       }
     }
+  };
+  uint4 k0[4], k1[4];
+  bool pr0 = false, pr1 = false;
+  if (n_it > 0) {
+    pr0 = fetch(p_begin + pw, k0);
+    pr1 = fetch(p_begin + npw + pw, k1);
+  }
+  for (int it = 0; it < n_it; it += 2) {  // n_it is the same for every wavefront of the workgroup
+    step(it, k0, pr0);
+    if (it + 1 < n_it) step(it + 1, k1, pr1);
   }
   if (PASS2) return;
 
@@ -195,7 +235,7 @@ __global__ __launch_bounds__(256) void snap_stats_kernel(CacheView c, SnapArgs a
   const int b = unit / c.n_kv_heads;
   const int S = c.seq_lens[b];
   if (S <= a.keep || S > c.pages_cap * kAttnPage) return;
-  const int chunks = ((S + kAttnPage - 1) / kAttnPage + kSnapChunkPages - 1) / kSnapChunkPages;
+  const int chunks = ((S + kAttnPage - 1) / kAttnPage + a.chunk_pages - 1) / a.chunk_pages;
   for (int col = threadIdx.x; col < a.NC; col += 256) {
     float mm = kNegBigS, zz = 0.f;
     for (int ch = 0; ch < chunks; ++ch) {
@@ -427,8 +467,13 @@ SnapPlan plan_snapkv(const CacheView& src, int window, int keep) {
   SnapPlan p;
   const size_t units = (size_t)src.batch * src.n_kv_heads;
   const int NC = src.group * window;
-  p.chunk_pages = kSnapChunkPages;
-  p.n_chunks = (src.pages_cap + kSnapChunkPages - 1) / kSnapChunkPages;
+  // Pages per workgroup in the score passes.  Every wavefront loads the whole observation-window
+  // query block before its first page, so long chunks amortise that; short ones keep the chip full
+  // when there are few (sequence, KV head) units.  Aim for about 2048 workgroups.
+  int chunk_pages = 32;
+  while (chunk_pages < 256 && units * ((src.pages_cap + chunk_pages - 1) / chunk_pages) > 2048) chunk_pages *= 2;
+  p.chunk_pages = chunk_pages;
+  p.n_chunks = (src.pages_cap + chunk_pages - 1) / chunk_pages;
   const size_t s_cap = (size_t)src.pages_cap * kAttnPage;
   auto up = [](size_t x) { return (x + 255) / 256 * 256; };
   size_t off = 0;
@@ -456,6 +501,7 @@ hipError_t launch_snapkv(const bf16_t* q_obs, const CacheView& src, int window, 
   a.NC = src.group * window;
   a.CG = a.NC > kSnapColBlocks * 16 ? 2 : 1;
   a.n_chunks = plan.n_chunks;
+  a.chunk_pages = plan.chunk_pages;
   a.keep = keep;
   a.s_cap = src.pages_cap * kAttnPage;
   a.pool_r = (pool_kernel - 1) / 2;
