@@ -36,7 +36,13 @@
  *        pp * stride_page + g * stride_head
  * of the pool and holds `page_size * head_dim` contiguous bf16 values:
  *        K tile: [page_size][head_dim]   (token-major, channels contiguous)
- *        V tile: [head_dim][page_size]   (channel-major, tokens contiguous)
+ *        V tile: [head_dim][page_size]   (channel-major, tokens contiguous) when
+ *                v_layout == ROCKETKV_V_CHANNEL_MAJOR, else [page_size][head_dim]
+ * The channel-major V tile with page_size 16 is the layout the fused decode
+ * kernel is built for (the token index is the contraction index of its second
+ * matrix product).  The token-major V tile keeps every token's value row
+ * contiguous, which is what page sizes other than 16 (Section 3.6 derives 2-4
+ * for the usual budgets) and token-granular gathers need.
  * Sequence b's logical page p (tokens p*page_size ...) is physical page
  * `block_table[b*pages_cap + p]`, or `b*pages_cap + p` when block_table is
  * NULL.  `seq_lens[b]` is the number of valid tokens of sequence b (all KV
@@ -50,9 +56,9 @@
  * are never read.
  *
  * Limits of this build: head_dim == 128; n_q_heads a multiple of n_kv_heads
- * with group size <= 16; page_size == 16 for the attention entry points
- * (summaries and selection accept 1..64); pages_cap a multiple of 8 and at
- * most ROCKETKV_MAX_PAGES for selection.
+ * with group size <= 16; page_size 1..64, and 16 where V is channel-major and
+ * attention or SnapKV is involved; pages_cap a multiple of 8 and at most
+ * ROCKETKV_MAX_PAGES for selection.
  */
 #ifndef ROCKETKV_H
 #define ROCKETKV_H
@@ -81,6 +87,11 @@ typedef enum {
   ROCKETKV_OP_ATTEND = 3        /* a = pages_row_len (0 = every page)     */
 } rocketkv_op_t;
 
+typedef enum {
+  ROCKETKV_V_CHANNEL_MAJOR = 0, /* V tile [head_dim][page_size] */
+  ROCKETKV_V_TOKEN_MAJOR = 1    /* V tile [page_size][head_dim] */
+} rocketkv_v_layout_t;
+
 typedef struct rocketkv_cache {
   int32_t batch;
   int32_t n_q_heads;
@@ -95,6 +106,7 @@ typedef struct rocketkv_cache {
   const int32_t* block_table; /* device [batch][pages_cap] or NULL (identity) */
   void* k_pool;               /* device bf16 */
   void* v_pool;               /* device bf16 */
+  int32_t v_layout;           /* rocketkv_v_layout_t */
 } rocketkv_cache_t;
 
 #define ROCKETKV_WS_HEADER_BYTES 65536 /* leading part of a workspace that workspace_init clears */
@@ -214,11 +226,11 @@ int32_t rocketkv_append_kv(const rocketkv_cache_t* cache, const void* k_new, con
  *   pooled  = stride-1 max-pool of vote with odd kernel pool_kernel, clipped at the ends
  *   kept    = top-(keep_budget - window) of pooled (ties: lower position) plus the window
  * and K/V of the kept tokens are copied, in ascending position, into `dst`
- * (same head counts, head_dim and page_size; dst->pages_cap*page_size >=
- * keep_budget), dst->seq_lens[b] = min(S, keep_budget).
+ * (same head counts and head_dim; dst->pages_cap*page_size >= keep_budget),
+ * dst->seq_lens[b] = min(S, keep_budget).
  * q_obs: bf16 [batch][n_q_heads][window][head_dim], queries of the last
- *        `window` prompt positions.  A sequence with keep_budget < S < window
- *        is rejected on the device side by keeping its first keep_budget tokens.
+ *        `window` prompt positions.
+ * src needs page_size 16; dst may have any page size when its V is token-major.
  * kept_idx: optional int32 [batch][n_kv_heads][keep_budget], -1 padded.
  * workspace: rocketkv_workspace_bytes(ROCKETKV_OP_SNAPKV, src, window, keep_budget).
  */
@@ -226,6 +238,26 @@ int32_t rocketkv_snapkv_compress(const void* q_obs, const rocketkv_cache_t* src,
                                  int32_t pool_kernel, int32_t keep_budget,
                                  const rocketkv_cache_t* dst, int32_t* kept_idx, void* workspace,
                                  size_t workspace_bytes, void* stream);
+
+/*
+ * Adaptive compression decomposition (Section 3.6): for a sequence of seq_len
+ * tokens and a total token budget t (memory traffic of one attention call in
+ * key/value pairs, Step 2 and Step 3 together), c = seq_len / t (at least 1),
+ *   r = min(0.2 + 0.06 log2 c, 0.8),  stage1 = c^r,  stage2 = c^(1-r),
+ *   page_size = ceil(c^((1-r)/2)),  head_ratio = stage2 / page_size,
+ * and, with the budget split evenly between Step 2 and Step 3 (Appendix A.3),
+ *   keep_budget    = round(seq_len / stage1)          tokens Stage 1 keeps,
+ *   channel_budget = round(head_dim / head_ratio)     in [1, head_dim],
+ *   attend_tokens  = max(1, t / 2)                    the token_budget argument
+ *                                                     of the decode entry points.
+ * Host arithmetic only (double precision); `out` is a host struct.
+ */
+typedef struct rocketkv_split {
+  double c, r, stage1, stage2, head_ratio;
+  int32_t page_size, keep_budget, channel_budget, attend_tokens;
+} rocketkv_split_t;
+int32_t rocketkv_decompose(int64_t seq_len, int32_t token_budget, int32_t head_dim,
+                           rocketkv_split_t* out);
 
 /* Thread-local description of the last error returned on this thread ("" if none). */
 const char* rocketkv_last_error(void);

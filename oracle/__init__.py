@@ -229,3 +229,10 @@ def decompose(c):
     out = np.zeros(5, dtype=np.float64)
     _load().okv_decompose(C.c_double(float(c)), _p(out, C.c_double))
     return dict(r=out[0], stage1=out[1], stage2=out[2], page=int(out[3]), head_ratio=out[4])
+
+
+def decompose_budget(S, t, D):
+    """Section 3.6 + Appendix A.3: integer operating point dict(page, keep, channels, attend_tokens)."""
+    out = np.zeros(4, dtype=np.int32)
+    _load().okv_decompose_budget(C.c_longlong(int(S)), C.c_int(int(t)), C.c_int(int(D)), _p(out, C.c_int))
+    return dict(page=int(out[0]), keep=int(out[1]), channels=int(out[2]), attend_tokens=int(out[3]))

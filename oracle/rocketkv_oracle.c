@@ -421,3 +421,26 @@ void okv_decompose(double c, double* out) {
   double page = ceil(pow(c, (1.0 - r) / 2.0));
   out[0] = r; out[1] = c1; out[2] = c2; out[3] = page; out[4] = c2 / page;
 }
+
+/* Integer operating point that follows from the split when the budget t is   */
+/* shared evenly by Step 2 and Step 3 (Appendix A.3): Stage 1 keeps S / c^r   */
+/* tokens, Step 2 reads D / head_ratio channels of one summary row per page,  */
+/* Step 3 attends to t / 2 tokens.  c below 1 (budget above the sequence) is  */
+/* taken as 1: nothing is compressed.  Rounding to nearest is this build's    */
+/* reading; the paper prints only the real-valued ratios.                     */
+/* out: page, keep, channels, attend_tokens.                                  */
+void okv_decompose_budget(long long S, int t, int D, int* out) {
+  double c = (double)S / (double)t;
+  if (c < 1.0) c = 1.0;
+  double sp[5];
+  okv_decompose(c, sp);
+  long long keep = (long long)floor((double)S / sp[1] + 0.5);
+  if (keep < 1) keep = 1;
+  if (keep > S) keep = S;
+  int k1 = (int)floor((double)D / sp[4] + 0.5);
+  if (k1 < 1) k1 = 1;
+  if (k1 > D) k1 = D;
+  int T = t / 2;
+  if (T < 1) T = 1;
+  out[0] = (int)sp[3]; out[1] = (int)keep; out[2] = k1; out[3] = T;
+}

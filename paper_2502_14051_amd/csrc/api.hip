@@ -1,5 +1,6 @@
 // C-ABI front end: argument validation on the host, workspace carving, kernel launches.
 // Every exported function validates before it enqueues anything and never synchronises.
+#include <math.h>
 #include <stdarg.h>
 #include <stdio.h>
 #include <string.h>
@@ -43,6 +44,8 @@ int check_cache(const rocketkv_cache_t* c, bool need_pools, const char* who) {
   if (c->n_q_heads / c->n_kv_heads > kMaxGroup)
     return fail(ROCKETKV_UNSUPPORTED, "%s: group size %d exceeds %d", who,
                 c->n_q_heads / c->n_kv_heads, kMaxGroup);
+  if (c->v_layout != ROCKETKV_V_CHANNEL_MAJOR && c->v_layout != ROCKETKV_V_TOKEN_MAJOR)
+    return fail(ROCKETKV_INVALID_ARG, "%s: unknown v_layout %d", who, c->v_layout);
   if (c->page_size < 1) return fail(ROCKETKV_INVALID_ARG, "%s: page_size must be >= 1", who);
   if (c->page_size > 64) return fail(ROCKETKV_UNSUPPORTED, "%s: page_size %d > 64", who, c->page_size);
   if (c->pages_cap < 1 || c->pages_cap % 8 != 0)
@@ -86,6 +89,7 @@ CacheView view_of(const rocketkv_cache_t* c) {
   v.block_table = c->block_table;
   v.k_pool = static_cast<bf16_t*>(c->k_pool);
   v.v_pool = static_cast<bf16_t*>(c->v_pool);
+  v.v_token_major = c->v_layout == ROCKETKV_V_TOKEN_MAJOR;
   return v;
 }
 
@@ -111,10 +115,25 @@ int check_select_args(const rocketkv_cache_t* c, const void* q, const void* kmax
 }
 
 int check_attend_shape(const rocketkv_cache_t* c, const char* who) {
-  if (c->page_size != kAttnPage)
-    return fail(ROCKETKV_UNSUPPORTED, "%s: attention needs page_size %d (got %d)", who, kAttnPage,
-                c->page_size);
+  if (c->v_layout == ROCKETKV_V_CHANNEL_MAJOR && c->page_size != kAttnPage)
+    return fail(ROCKETKV_UNSUPPORTED, "%s: attention over channel-major V needs page_size %d (got %d)", who,
+                kAttnPage, c->page_size);
   return ROCKETKV_OK;
+}
+
+// Launch geometry of Step 3 over `row_len` list entries.  The plan counts 16-token entries; a
+// token-major cache of another page size is planned on the token slots its entries add up to.
+AttendPlan attend_plan_for(const CacheView& v, int row_len) {
+  if (!v.v_token_major) return plan_attend(v, row_len);
+  const int64_t slots = (int64_t)row_len * v.page_size;
+  return plan_attend(v, (int)((slots + kAttnPage - 1) / kAttnPage));
+}
+
+hipError_t launch_attend_any(const CacheView& v, const bf16_t* q, const int32_t* pages, int row_len,
+                             bf16_t* out, float* out_lse, void* ws, const AttendPlan& plan,
+                             hipStream_t st) {
+  return v.v_token_major ? launch_attend_tokens(v, q, pages, row_len, out, out_lse, ws, plan, st)
+                         : launch_attend(v, q, pages, row_len, out, out_lse, ws, plan, st);
 }
 
 struct DecodePlan {
@@ -127,7 +146,7 @@ DecodePlan plan_decode(const rocketkv_cache_t* c, int T) {
   DecodePlan d;
   const CacheView v = view_of(c);
   d.row_len = list_len_for_budget(c, T);
-  d.attend = plan_attend(v, d.row_len);
+  d.attend = attend_plan_for(v, d.row_len);
   size_t off = 0;
   d.attend_off = off;  // first, so that the counters sit in the header workspace_init clears
   off += d.attend.total_bytes;
@@ -160,10 +179,10 @@ size_t rocketkv_workspace_bytes(int32_t op, const rocketkv_cache_t* cache, int32
       if (a < 1) { fail(ROCKETKV_INVALID_ARG, "rocketkv_workspace_bytes: token_budget must be >= 1"); return 0; }
       return plan_decode(cache, a).total;
     case ROCKETKV_OP_DENSE_DECODE:
-      return plan_attend(v, cache->pages_cap).total_bytes;
+      return attend_plan_for(v, cache->pages_cap).total_bytes;
     case ROCKETKV_OP_ATTEND:
       if (a < 0) { fail(ROCKETKV_INVALID_ARG, "rocketkv_workspace_bytes: pages_row_len must be >= 0"); return 0; }
-      return plan_attend(v, a > 0 ? a : cache->pages_cap).total_bytes;
+      return attend_plan_for(v, a > 0 ? a : cache->pages_cap).total_bytes;
     case ROCKETKV_OP_SNAPKV:
       if (a < 1 || b <= a) { fail(ROCKETKV_INVALID_ARG, "rocketkv_workspace_bytes: need 1 <= window < keep_budget"); return 0; }
       return plan_snapkv(v, a, b).total_bytes;
@@ -239,14 +258,14 @@ int32_t rocketkv_attend(const rocketkv_cache_t* cache, const void* q, const int3
   if (pages && pages_row_len < 1) return fail(ROCKETKV_INVALID_ARG, "%s: pages_row_len must be >= 1", who);
   const int row_len = pages ? pages_row_len : cache->pages_cap;
   const CacheView v = view_of(cache);
-  const AttendPlan plan = plan_attend(v, row_len);
+  const AttendPlan plan = attend_plan_for(v, row_len);
   if (plan.total_bytes && (!workspace || workspace_bytes < plan.total_bytes))
     return fail(ROCKETKV_WORKSPACE_TOO_SMALL, "%s: workspace %zu bytes < %zu needed", who,
                 workspace ? workspace_bytes : (size_t)0, plan.total_bytes);
   if ((uintptr_t)workspace & 255) return fail(ROCKETKV_INVALID_ARG, "%s: workspace must be 256-byte aligned", who);
-  const hipError_t e = launch_attend(v, static_cast<const bf16_t*>(q), pages, row_len,
-                                     static_cast<bf16_t*>(out), out_lse, workspace, plan,
-                                     static_cast<hipStream_t>(stream));
+  const hipError_t e = launch_attend_any(v, static_cast<const bf16_t*>(q), pages, row_len,
+                                         static_cast<bf16_t*>(out), out_lse, workspace, plan,
+                                         static_cast<hipStream_t>(stream));
   return e == hipSuccess ? ROCKETKV_OK : hip_fail(e, who);
 }
 
@@ -288,7 +307,7 @@ int decode_impl(const char* who, const rocketkv_cache_t* cache, const void* q, c
   AppendArgs ap = {static_cast<const bf16_t*>(k_new), static_cast<const bf16_t*>(v_new),
                    static_cast<bf16_t*>(kmax), static_cast<bf16_t*>(kmin)};
   hipError_t e;
-  if (fused_decode_lds_bytes(v, d.row_len, d.attend) + 64 <= kMaxLdsBytes) {
+  if (!v.v_token_major && fused_decode_lds_bytes(v, d.row_len, d.attend) + 64 <= kMaxLdsBytes) {
     // one launch: every workgroup selects for itself and keeps the list in LDS
     a.out_pages = out_pages;
     a.out_pages2 = nullptr;
@@ -307,8 +326,8 @@ int decode_impl(const char* who, const rocketkv_cache_t* cache, const void* q, c
   a.zero_counters = d.attend.n_split > 1 ? attend_counters(ws + d.attend_off, d.attend) : nullptr;
   e = launch_hsa_select(v, a, st);
   if (e != hipSuccess) return hip_fail(e, who);
-  e = launch_attend(v, a.q, a.out_pages, d.row_len, static_cast<bf16_t*>(out), out_lse,
-                    ws + d.attend_off, d.attend, st);
+  e = launch_attend_any(v, a.q, a.out_pages, d.row_len, static_cast<bf16_t*>(out), out_lse,
+                        ws + d.attend_off, d.attend, st);
   return e == hipSuccess ? ROCKETKV_OK : hip_fail(e, who);
 }
 
@@ -361,11 +380,13 @@ int32_t rocketkv_snapkv_compress(const void* q_obs, const rocketkv_cache_t* src,
   if (int r = check_cache(dst, true, who)) return r;
   if (!q_obs) return fail(ROCKETKV_INVALID_ARG, "%s: q_obs must not be NULL", who);
   if (((uintptr_t)q_obs) & 15) return fail(ROCKETKV_INVALID_ARG, "%s: q_obs must be 16-byte aligned", who);
-  if (src->batch != dst->batch || src->n_q_heads != dst->n_q_heads || src->n_kv_heads != dst->n_kv_heads ||
-      src->page_size != dst->page_size)
-    return fail(ROCKETKV_INVALID_ARG, "%s: src and dst must agree on batch, heads and page_size", who);
+  if (src->batch != dst->batch || src->n_q_heads != dst->n_q_heads || src->n_kv_heads != dst->n_kv_heads)
+    return fail(ROCKETKV_INVALID_ARG, "%s: src and dst must agree on batch and head counts", who);
   if (src->page_size != kAttnPage)
-    return fail(ROCKETKV_UNSUPPORTED, "%s: needs page_size %d (got %d)", who, kAttnPage, src->page_size);
+    return fail(ROCKETKV_UNSUPPORTED, "%s: src needs page_size %d (got %d)", who, kAttnPage, src->page_size);
+  if (dst->v_layout == ROCKETKV_V_CHANNEL_MAJOR && dst->page_size != kAttnPage)
+    return fail(ROCKETKV_UNSUPPORTED, "%s: a dst with channel-major V needs page_size %d (got %d)", who,
+                kAttnPage, dst->page_size);
   if (window < 1 || window > 128 || window % 16 != 0)
     return fail(window < 1 ? ROCKETKV_INVALID_ARG : ROCKETKV_UNSUPPORTED,
                 "%s: window %d must be a multiple of 16 in [16, 128]", who, window);
@@ -392,6 +413,31 @@ int32_t rocketkv_snapkv_compress(const void* q_obs, const rocketkv_cache_t* src,
                                      keep_budget, dv, kept_idx, workspace, plan,
                                      static_cast<hipStream_t>(stream));
   return e == hipSuccess ? ROCKETKV_OK : hip_fail(e, who);
+}
+
+int32_t rocketkv_decompose(int64_t seq_len, int32_t token_budget, int32_t head_dim,
+                           rocketkv_split_t* out) {
+  g_err[0] = 0;
+  const char* who = "rocketkv_decompose";
+  if (!out) return fail(ROCKETKV_INVALID_ARG, "%s: out is NULL", who);
+  if (seq_len < 1 || token_budget < 1 || head_dim < 1)
+    return fail(ROCKETKV_INVALID_ARG, "%s: seq_len, token_budget and head_dim must be positive", who);
+  if (seq_len > ((int64_t)1 << 40)) return fail(ROCKETKV_INVALID_ARG, "%s: seq_len too large", who);
+  rocketkv_split_t s;
+  s.c = fmax(1.0, (double)seq_len / (double)token_budget);
+  s.r = fmin(0.2 + 0.06 * log2(s.c), 0.8);
+  s.stage1 = pow(s.c, s.r);
+  s.stage2 = pow(s.c, 1.0 - s.r);
+  const double seq_ratio = ceil(pow(s.c, 0.5 * (1.0 - s.r)));  // sequence-dimension share, a whole page size
+  s.head_ratio = s.stage2 / seq_ratio;
+  s.page_size = (int32_t)seq_ratio;
+  const double keep = floor((double)seq_len / s.stage1 + 0.5);
+  s.keep_budget = (int32_t)fmin(fmax(keep, 1.0), fmin((double)seq_len, 2147483647.0));
+  const double ch = floor((double)head_dim / s.head_ratio + 0.5);
+  s.channel_budget = (int32_t)fmin(fmax(ch, 1.0), (double)head_dim);
+  s.attend_tokens = token_budget / 2 > 1 ? token_budget / 2 : 1;
+  *out = s;
+  return ROCKETKV_OK;
 }
 
 }  // extern "C"

@@ -70,6 +70,56 @@ __device__ __forceinline__ float ld_agent(const float* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Online-softmax update and second product for the NP page pairs of one round: `acc` holds the raw
+// logits S[token][head] (masked entries -inf), `vf` the V operand (lane: channel cb*16+hn, tokens
+// 4kg..4kg+3 of each page).  One max / rescale per round, the logit scale folded into the exponent's
+// FMA, hardware bf16 packing.
+template <int NP>
+__device__ __forceinline__ void softmax_pv(f32x4 (&acc)[NP][2], u32x2 (&vf)[NP][2][8],
+                                           f32x4 (&O)[8], float& m, float& l, bool have_acc, float sc) {
+  float mx = -INFINITY;
+#pragma unroll
+  for (int u = 0; u < NP; ++u)
+#pragma unroll
+    for (int x = 0; x < 2; ++x)
+      mx = fmaxf(fmaxf(mx, fmaxf(acc[u][x][0], acc[u][x][1])), fmaxf(acc[u][x][2], acc[u][x][3]));
+  mx = fmaxf(mx, __shfl_xor(mx, 16));
+  mx = fmaxf(mx, __shfl_xor(mx, 32));
+  const float m_new = fmaxf(m, mx * sc);  // running max in the scaled log2 domain
+  if (have_acc) {
+    const float alpha = fast_exp2(m - m_new);
+    l *= alpha;
+    if (__any(alpha != 1.f)) {
+#pragma unroll
+      for (int cb = 0; cb < 8; ++cb) O[cb] *= alpha;
+    }
+  }
+  m = m_new;
+  float psum = 0.f;
+  u32x4 pf[NP];
+#pragma unroll
+  for (int u = 0; u < NP; ++u) {
+    float p[2][4];
+#pragma unroll
+    for (int x = 0; x < 2; ++x)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        p[x][r] = fast_exp2(fmaf(acc[u][x][r], sc, -m_new));
+        psum += p[x][r];
+      }
+    pf[u] = (u32x4){pack_bf16x2(p[0][0], p[0][1]), pack_bf16x2(p[0][2], p[0][3]),
+                    pack_bf16x2(p[1][0], p[1][1]), pack_bf16x2(p[1][2], p[1][3])};
+  }
+  l += psum;
+#pragma unroll
+  for (int u = 0; u < NP; ++u)
+#pragma unroll
+    for (int cb = 0; cb < 8; ++cb) {
+      const u32x4 vv = {vf[u][0][cb].x, vf[u][0][cb].y, vf[u][1][cb].x, vf[u][1][cb].y};
+      O[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vv), as_bf16x8(pf[u]), O[cb], 0, 0, 0);
+    }
+}
+
 // Online-softmax step over the NP page pairs of one round.  The vector ALUs issue one wave64
 // instruction per four cycles and share the SIMD with the next wave, so instruction count is what
 // this step is built around: one max / rescale per round instead of per page, the logit scale folded
@@ -142,47 +192,111 @@ __device__ __forceinline__ void softmax_round(u32x4 (&kf)[NP][2][4], u32x2 (&vf)
         }
       }
   }
-  float mx = -INFINITY;
+  softmax_pv<NP>(acc, vf, O, m, l, have_acc, sc);
+}
+
+// Merges of one workgroup's result: the wavefronts' (O, max, sum) through LDS, then, when the unit is
+// split over several workgroups, the hand-over of the partial and the last arriver's merge of all of
+// them.  `O`, `m`, `l` are the lane's online-softmax state with `l` already summed over the four
+// token groups; `smem` holds WAVES*G*130 floats, `s_last` one int.
+template <int WAVES>
+__device__ __forceinline__ void attend_merge(const CacheView& c, const AttendArgs& a, int unit, int split,
+                                             const f32x4 (&O)[8], float m, float l, float* smem,
+                                             int* s_last, int b, int g) {
+  constexpr int kThreads = WAVES * kWave;
+  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+  const int hn = lane % 16, kg = lane / 16;
+  const int G = c.group;
+  float* sO = smem;
+  float* sM = smem + WAVES * G * kHeadDim;
+  float* sL = sM + WAVES * G;
+
+  // ---- merge the waves through LDS ---------------------------------------------------------------
+  if (hn < G) {
 #pragma unroll
-  for (int u = 0; u < NP; ++u)
-#pragma unroll
-    for (int x = 0; x < 2; ++x)
-      mx = fmaxf(fmaxf(mx, fmaxf(acc[u][x][0], acc[u][x][1])), fmaxf(acc[u][x][2], acc[u][x][3]));
-  mx = fmaxf(mx, __shfl_xor(mx, 16));
-  mx = fmaxf(mx, __shfl_xor(mx, 32));
-  const float m_new = fmaxf(m, mx * sc);  // running max in the scaled log2 domain
-  if (have_acc) {
-    const float alpha = fast_exp2(m - m_new);
-    l *= alpha;
-    if (__any(alpha != 1.f)) {
-#pragma unroll
-      for (int cb = 0; cb < 8; ++cb) O[cb] *= alpha;
+    for (int cb = 0; cb < 8; ++cb)
+      *reinterpret_cast<float4*>(&sO[(wave * G + hn) * kHeadDim + cb * 16 + kg * 4]) =
+          make_float4(O[cb][0], O[cb][1], O[cb][2], O[cb][3]);
+    if (kg == 0) {
+      sM[wave * G + hn] = m;
+      sL[wave * G + hn] = l;
     }
   }
-  m = m_new;
-  float psum = 0.f;
-  u32x4 pf[NP];
+  __syncthreads();
+  const int64_t out_base = ((int64_t)b * c.n_q_heads + (int64_t)g * G) * kHeadDim;
+  for (int idx = tid; idx < G * kHeadDim; idx += kThreads) {
+    const int h = idx / kHeadDim, ch = idx % kHeadDim;
+    float M = sM[h];
 #pragma unroll
-  for (int u = 0; u < NP; ++u) {
-    float p[2][4];
+    for (int w = 1; w < WAVES; ++w) M = fmaxf(M, sM[w * G + h]);
+    float num = 0.f, den = 0.f;
 #pragma unroll
-    for (int x = 0; x < 2; ++x)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        p[x][r] = fast_exp2(fmaf(acc[u][x][r], sc, -m_new));
-        psum += p[x][r];
+    for (int w = 0; w < WAVES; ++w) {
+      const float f = fast_exp2(sM[w * G + h] - M);
+      num += f * sO[(w * G + h) * kHeadDim + ch];
+      den += f * sL[w * G + h];
+    }
+    if (a.n_split == 1) {
+      a.out[out_base + idx] = f32_to_bf16(den > 0.f ? num / den : 0.f);
+      if (ch == 0 && a.out_lse)
+        a.out_lse[(int64_t)b * c.n_q_heads + g * G + h] = den > 0.f ? (M + log2f(den)) * kLn2 : -INFINITY;
+    } else {
+      // write-through stores: visible device-wide once acknowledged, no cache flush needed
+      float* pr = a.partial + (((int64_t)unit * a.n_split + split) * G + h) * kPartialStride;
+      st_agent(pr + ch, num);
+      if (ch == 0) {
+        st_agent(pr + kHeadDim, M);
+        st_agent(pr + kHeadDim + 1, den);
       }
-    pf[u] = (u32x4){pack_bf16x2(p[0][0], p[0][1]), pack_bf16x2(p[0][2], p[0][3]),
-                    pack_bf16x2(p[1][0], p[1][1]), pack_bf16x2(p[1][2], p[1][3])};
-  }
-  l += psum;
-#pragma unroll
-  for (int u = 0; u < NP; ++u)
-#pragma unroll
-    for (int cb = 0; cb < 8; ++cb) {
-      const u32x4 vv = {vf[u][0][cb].x, vf[u][0][cb].y, vf[u][1][cb].x, vf[u][1][cb].y};
-      O[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vv), as_bf16x8(pf[u]), O[cb], 0, 0, 0);
     }
+  }
+  if (a.n_split == 1) return;
+
+  // ---- last workgroup of the unit merges the split partials --------------------------------------
+  __syncthreads();  // every store of this workgroup has been acknowledged
+  if (tid == 0) {
+    const uint32_t old = __hip_atomic_fetch_add(&a.counters[unit], 1u, __ATOMIC_RELAXED,
+                                                __HIP_MEMORY_SCOPE_AGENT);
+    *s_last = (old == (uint32_t)a.n_split - 1u);
+  }
+  __syncthreads();
+  if (!*s_last) return;
+  for (int idx = tid; idx < G * kHeadDim; idx += kThreads) {
+    const int h = idx / kHeadDim, ch = idx % kHeadDim;
+    const float* pr = a.partial + ((int64_t)unit * a.n_split * G + h) * kPartialStride;
+    const int64_t sstride = (int64_t)G * kPartialStride;
+    float M = kNegBig, num = 0.f, den = 0.f;
+    // eight splits per batch, every load of a batch in flight before the first use
+    for (int s0 = 0; s0 < a.n_split; s0 += 8) {
+      float ms[8], ls[8], os[8];
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        const bool ok = s0 + t < a.n_split;
+        const float* ps = pr + (ok ? s0 + t : s0) * sstride;
+        ms[t] = ld_agent(ps + kHeadDim);
+        ls[t] = ld_agent(ps + kHeadDim + 1);
+        os[t] = ld_agent(ps + ch);
+        if (!ok) { ms[t] = kNegBig; ls[t] = 0.f; os[t] = 0.f; }
+      }
+      float Mb = M;
+#pragma unroll
+      for (int t = 0; t < 8; ++t) Mb = fmaxf(Mb, ms[t]);
+      const float fo = fast_exp2(M - Mb);
+      num *= fo;
+      den *= fo;
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        const float f = fast_exp2(ms[t] - Mb);
+        num += f * os[t];
+        den += f * ls[t];
+      }
+      M = Mb;
+    }
+    a.out[out_base + idx] = f32_to_bf16(den > 0.f ? num / den : 0.f);
+    if (ch == 0 && a.out_lse)
+      a.out_lse[(int64_t)b * c.n_q_heads + g * G + h] = den > 0.f ? (M + log2f(den)) * kLn2 : -INFINITY;
+  }
+  if (tid == 0) __hip_atomic_store(&a.counters[unit], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // The attention of one workgroup: its share (`split`) of the page list of `unit`, then the merges.
@@ -198,16 +312,10 @@ template <int WAVES, int NP, typename Hook = NoHook>
 __device__ __forceinline__ void attend_block(const CacheView& c, const AttendArgs& a, int unit, int split,
                                              int n, const int32_t* list, float* smem, int* s_last,
                                              const TailPatch& tp, const Hook& after_stream = Hook()) {
-
-  constexpr int kThreads = WAVES * kWave;
-
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
   const int hn = lane % 16, kg = lane / 16;
   const int b = unit / c.n_kv_heads, g = unit % c.n_kv_heads;
   const int G = c.group;
-  float* sO = smem;
-  float* sM = smem + WAVES * G * kHeadDim;
-  float* sL = sM + WAVES * G;
   int P = (n + kAttnPage - 1) / kAttnPage;
   if (P > c.pages_cap) P = c.pages_cap;
 
@@ -297,93 +405,7 @@ __device__ __forceinline__ void attend_block(const CacheView& c, const AttendArg
   l += __shfl_xor(l, 16);
   l += __shfl_xor(l, 32);
   after_stream();
-
-  // ---- merge the waves through LDS ---------------------------------------------------------------
-  if (hn < G) {
-#pragma unroll
-    for (int cb = 0; cb < 8; ++cb)
-      *reinterpret_cast<float4*>(&sO[(wave * G + hn) * kHeadDim + cb * 16 + kg * 4]) =
-          make_float4(O[cb][0], O[cb][1], O[cb][2], O[cb][3]);
-    if (kg == 0) {
-      sM[wave * G + hn] = m;
-      sL[wave * G + hn] = l;
-    }
-  }
-  __syncthreads();
-  const int64_t out_base = ((int64_t)b * c.n_q_heads + (int64_t)g * G) * kHeadDim;
-  for (int idx = tid; idx < G * kHeadDim; idx += kThreads) {
-    const int h = idx / kHeadDim, ch = idx % kHeadDim;
-    float M = sM[h];
-#pragma unroll
-    for (int w = 1; w < WAVES; ++w) M = fmaxf(M, sM[w * G + h]);
-    float num = 0.f, den = 0.f;
-#pragma unroll
-    for (int w = 0; w < WAVES; ++w) {
-      const float f = fast_exp2(sM[w * G + h] - M);
-      num += f * sO[(w * G + h) * kHeadDim + ch];
-      den += f * sL[w * G + h];
-    }
-    if (a.n_split == 1) {
-      a.out[out_base + idx] = f32_to_bf16(den > 0.f ? num / den : 0.f);
-      if (ch == 0 && a.out_lse)
-        a.out_lse[(int64_t)b * c.n_q_heads + g * G + h] = den > 0.f ? (M + log2f(den)) * kLn2 : -INFINITY;
-    } else {
-      // write-through stores: visible device-wide once acknowledged, no cache flush needed
-      float* pr = a.partial + (((int64_t)unit * a.n_split + split) * G + h) * kPartialStride;
-      st_agent(pr + ch, num);
-      if (ch == 0) {
-        st_agent(pr + kHeadDim, M);
-        st_agent(pr + kHeadDim + 1, den);
-      }
-    }
-  }
-  if (a.n_split == 1) return;
-
-  // ---- last workgroup of the unit merges the split partials --------------------------------------
-  __syncthreads();  // every store of this workgroup has been acknowledged
-  if (tid == 0) {
-    const uint32_t old = __hip_atomic_fetch_add(&a.counters[unit], 1u, __ATOMIC_RELAXED,
-                                                __HIP_MEMORY_SCOPE_AGENT);
-    *s_last = (old == (uint32_t)a.n_split - 1u);
-  }
-  __syncthreads();
-  if (!*s_last) return;
-  for (int idx = tid; idx < G * kHeadDim; idx += kThreads) {
-    const int h = idx / kHeadDim, ch = idx % kHeadDim;
-    const float* pr = a.partial + ((int64_t)unit * a.n_split * G + h) * kPartialStride;
-    const int64_t sstride = (int64_t)G * kPartialStride;
-    float M = kNegBig, num = 0.f, den = 0.f;
-    // eight splits per batch, every load of a batch in flight before the first use
-    for (int s0 = 0; s0 < a.n_split; s0 += 8) {
-      float ms[8], ls[8], os[8];
-#pragma unroll
-      for (int t = 0; t < 8; ++t) {
-        const bool ok = s0 + t < a.n_split;
-        const float* ps = pr + (ok ? s0 + t : s0) * sstride;
-        ms[t] = ld_agent(ps + kHeadDim);
-        ls[t] = ld_agent(ps + kHeadDim + 1);
-        os[t] = ld_agent(ps + ch);
-        if (!ok) { ms[t] = kNegBig; ls[t] = 0.f; os[t] = 0.f; }
-      }
-      float Mb = M;
-#pragma unroll
-      for (int t = 0; t < 8; ++t) Mb = fmaxf(Mb, ms[t]);
-      const float fo = fast_exp2(M - Mb);
-      num *= fo;
-      den *= fo;
-#pragma unroll
-      for (int t = 0; t < 8; ++t) {
-        const float f = fast_exp2(ms[t] - Mb);
-        num += f * os[t];
-        den += f * ls[t];
-      }
-      M = Mb;
-    }
-    a.out[out_base + idx] = f32_to_bf16(den > 0.f ? num / den : 0.f);
-    if (ch == 0 && a.out_lse)
-      a.out_lse[(int64_t)b * c.n_q_heads + g * G + h] = den > 0.f ? (M + log2f(den)) * kLn2 : -INFINITY;
-  }
-  if (tid == 0) __hip_atomic_store(&a.counters[unit], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  attend_merge<WAVES>(c, a, unit, split, O, m, l, smem, s_last, b, g);
 }
 
 }  // namespace rkv

@@ -50,6 +50,7 @@ struct CacheView {
   const int32_t* block_table;
   bf16_t* k_pool;
   bf16_t* v_pool;
+  int32_t v_token_major;  // V tile [page_size][128] instead of [128][page_size]
 };
 
 // physical page of logical page p of sequence b, or -1 when absent
@@ -112,6 +113,11 @@ hipError_t launch_attend(const CacheView& c, const bf16_t* q, const int32_t* pag
                          bf16_t* out, float* out_lse, void* ws, const AttendPlan& plan,
                          hipStream_t st);
 hipError_t launch_zero(void* p, size_t bytes, hipStream_t st);
+// Step 3 over token-major caches of any page size; `row_len` counts list entries (pages), the plan
+// comes from plan_attend(c, ceil(row_len * page_size / 16)).
+hipError_t launch_attend_tokens(const CacheView& c, const bf16_t* q, const int32_t* pages, int row_len,
+                                bf16_t* out, float* out_lse, void* ws, const AttendPlan& plan,
+                                hipStream_t st);
 // Step 2 + Step 3 in one launch; usable when fused_decode_lds_bytes() fits kMaxLdsBytes
 constexpr size_t kMaxLdsBytes = 64 * 1024;
 size_t fused_decode_lds_bytes(const CacheView& c, int row_len, const AttendPlan& plan);

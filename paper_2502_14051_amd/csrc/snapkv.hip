@@ -410,56 +410,90 @@ __global__ __launch_bounds__(kSelT) void snap_select_kernel(CacheView c, SnapArg
   if (g == 0 && tid == 0) dst.seq_lens[b] = a.keep;
 }
 
-// copy the kept tokens into the destination cache; one workgroup per destination page
+// copy the kept tokens into the destination cache; one workgroup per 16 kept tokens.  K rows move
+// as 256-byte rows.  The V values of the 16 tokens are staged in LDS as [channel][token] whatever the
+// source layout, then leave as one contiguous channel-major tile (page size 16) or as token rows.
 __global__ __launch_bounds__(256) void snap_gather_kernel(CacheView src, CacheView dst, SnapArgs a) {
   __shared__ int s_tok[kAttnPage];
   __shared__ bf16_t s_v[kHeadDim * kAttnPage];
   const int tid = threadIdx.x;
-  const int unit = blockIdx.y, dp = blockIdx.x;
+  const int unit = blockIdx.y, blk = blockIdx.x;
   const int b = unit / src.n_kv_heads, g = unit % src.n_kv_heads;
   const int S = src.seq_lens[b];
   const int cnt = S > src.pages_cap * kAttnPage ? 0 : min(S, a.keep);
-  if (dp * kAttnPage >= cnt) return;
-  const int64_t dpp = phys_page(dst, b, dp);
-  if (dpp < 0) return;
+  if (blk * kAttnPage >= cnt) return;
   if (tid < kAttnPage) {
-    const int t = dp * kAttnPage + tid;
+    const int t = blk * kAttnPage + tid;
     s_tok[tid] = t < cnt ? a.kept[(int64_t)unit * a.keep + t] : -1;
   }
   __syncthreads();
-  bf16_t* dk = dst.k_pool + dpp * dst.stride_page + (int64_t)g * dst.stride_head;
-  bf16_t* dv = dst.v_pool + dpp * dst.stride_page + (int64_t)g * dst.stride_head;
+  const int dps = dst.page_size;
+  const int64_t dhead = (int64_t)g * dst.stride_head, shead = (int64_t)g * src.stride_head;
   // K: 16 rows of 256 B; thread -> (row = tid/16, 16-byte piece = tid%16)
+  const int row = tid / 16, piece = tid % 16;
+  const int tok = s_tok[row];
+  const int dt = blk * kAttnPage + row;  // destination position of this thread's row
+  const int64_t spp = tok >= 0 ? phys_page(src, b, tok / kAttnPage) : -1;
+  const int64_t dpp = dt / dps < dst.pages_cap ? phys_page(dst, b, dt / dps) : -1;
+  const bool row_live = tok >= 0 && spp >= 0;
   {
-    const int row = tid / 16, piece = tid % 16;
-    const int tok = s_tok[row];
     uint4 val = make_uint4(0, 0, 0, 0);
-    if (tok >= 0) {
-      const int64_t spp = phys_page(src, b, tok / kAttnPage);
-      if (spp >= 0)
-        val = *reinterpret_cast<const uint4*>(src.k_pool + spp * src.stride_page +
-                                              (int64_t)g * src.stride_head +
-                                              (tok % kAttnPage) * kHeadDim + piece * 8);
-    }
-    *reinterpret_cast<uint4*>(dk + row * kHeadDim + piece * 8) = val;
+    if (row_live)
+      val = *reinterpret_cast<const uint4*>(src.k_pool + spp * src.stride_page + shead +
+                                            (tok % kAttnPage) * kHeadDim + piece * 8);
+    // a channel-major destination gets whole tiles (zero rows past the end); a token-major one only
+    // the rows that exist, as later pages may belong to something else
+    if (dpp >= 0 && (tok >= 0 || !dst.v_token_major))
+      *reinterpret_cast<uint4*>(dst.k_pool + dpp * dst.stride_page + dhead + (dt % dps) * kHeadDim +
+                                piece * 8) = val;
   }
-  // V: element (channel, slot) comes from the source page's column; staged so the store is contiguous
-  for (int idx = tid; idx < kHeadDim * kAttnPage; idx += 256) {
-    const int slot = idx % kAttnPage, ch = idx / kAttnPage;
-    const int tok = s_tok[slot];
-    bf16_t val = 0;
-    if (tok >= 0) {
-      const int64_t spp = phys_page(src, b, tok / kAttnPage);
-      if (spp >= 0)
-        val = src.v_pool[spp * src.stride_page + (int64_t)g * src.stride_head + ch * kAttnPage +
-                         tok % kAttnPage];
+  if (src.v_token_major && dst.v_token_major) {
+    if (row_live && dpp >= 0)
+      *reinterpret_cast<uint4*>(dst.v_pool + dpp * dst.stride_page + dhead + (dt % dps) * kHeadDim +
+                                piece * 8) =
+          *reinterpret_cast<const uint4*>(src.v_pool + spp * src.stride_page + shead +
+                                          (tok % kAttnPage) * kHeadDim + piece * 8);
+    return;
+  }
+  // stage V as s_v[channel][token]
+  if (src.v_token_major) {
+    uint4 val = make_uint4(0, 0, 0, 0);
+    if (row_live)
+      val = *reinterpret_cast<const uint4*>(src.v_pool + spp * src.stride_page + shead +
+                                            (tok % kAttnPage) * kHeadDim + piece * 8);
+    const uint32_t w[4] = {val.x, val.y, val.z, val.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      s_v[(piece * 8 + 2 * i) * kAttnPage + row] = (bf16_t)(w[i] & 0xffffu);
+      s_v[(piece * 8 + 2 * i + 1) * kAttnPage + row] = (bf16_t)(w[i] >> 16);
     }
-    s_v[idx] = val;
+  } else {
+    for (int idx = tid; idx < kHeadDim * kAttnPage; idx += 256) {
+      const int slot = idx % kAttnPage, ch = idx / kAttnPage;
+      const int tk = s_tok[slot];
+      bf16_t val = 0;
+      if (tk >= 0) {
+        const int64_t sp2 = phys_page(src, b, tk / kAttnPage);
+        if (sp2 >= 0)
+          val = src.v_pool[sp2 * src.stride_page + shead + ch * kAttnPage + tk % kAttnPage];
+      }
+      s_v[idx] = val;
+    }
   }
   __syncthreads();
-  {
-    const uint4* sv4 = reinterpret_cast<const uint4*>(s_v);
-    reinterpret_cast<uint4*>(dv)[tid] = sv4[tid];
+  if (!dst.v_token_major) {
+    // page size 16: the staged block is the destination tile
+    if (dpp >= 0)
+      reinterpret_cast<uint4*>(dst.v_pool + dpp * dst.stride_page + dhead)[tid] =
+          reinterpret_cast<const uint4*>(s_v)[tid];
+  } else if (tok >= 0 && dpp >= 0) {
+    uint32_t w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      w[i] = (uint32_t)s_v[(piece * 8 + 2 * i) * kAttnPage + row] |
+             ((uint32_t)s_v[(piece * 8 + 2 * i + 1) * kAttnPage + row] << 16);
+    *reinterpret_cast<uint4*>(dst.v_pool + dpp * dst.stride_page + dhead + (dt % dps) * kHeadDim +
+                              piece * 8) = make_uint4(w[0], w[1], w[2], w[3]);
   }
 }
 

@@ -113,7 +113,7 @@ __global__ __launch_bounds__(kAppendThreads) void append_kv_kernel(CacheView c, 
       if (pp >= 0) {
         const int64_t base = pp * c.stride_page + (int64_t)g * c.stride_head;
         c.k_pool[base + slot * kHeadDim + ch] = kb;
-        c.v_pool[base + ch * ps + slot] = vb;
+        c.v_pool[base + (c.v_token_major ? slot * kHeadDim + ch : ch * ps + slot)] = vb;
       }
       const float x = bf16_to_f32(kb);
       if (slot == 0 || x > bf16_to_f32(old_max)) kmax[o] = kb;

@@ -19,11 +19,12 @@ LIB_PATH = os.path.join(_HERE, "librocketkv.so")
 OK, INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, HIP_ERROR = 0, -1, -2, -3, -4
 OP_HSA_DECODE, OP_DENSE_DECODE, OP_SNAPKV, OP_ATTEND = 0, 1, 2, 3
 MAX_PAGES = 8192
+V_CHANNEL_MAJOR, V_TOKEN_MAJOR = 0, 1
 
 EXPORTS = [
     "rocketkv_workspace_bytes", "rocketkv_workspace_init", "rocketkv_build_page_summaries", "rocketkv_hsa_select",
     "rocketkv_attend", "rocketkv_hsa_decode", "rocketkv_hsa_decode_append", "rocketkv_dense_decode", "rocketkv_append_kv",
-    "rocketkv_snapkv_compress", "rocketkv_last_error", "rocketkv_version",
+    "rocketkv_snapkv_compress", "rocketkv_decompose", "rocketkv_last_error", "rocketkv_version",
 ]
 
 
@@ -40,7 +41,16 @@ class CacheStruct(C.Structure):
         ("head_dim", C.c_int32), ("page_size", C.c_int32), ("pages_cap", C.c_int32),
         ("n_phys_pages", C.c_int64), ("stride_page", C.c_int64), ("stride_head", C.c_int64),
         ("seq_lens", C.c_void_p), ("block_table", C.c_void_p),
-        ("k_pool", C.c_void_p), ("v_pool", C.c_void_p),
+        ("k_pool", C.c_void_p), ("v_pool", C.c_void_p), ("v_layout", C.c_int32),
+    ]
+
+
+class SplitStruct(C.Structure):
+    """Mirror of ``rocketkv_split_t``."""
+    _fields_ = [
+        ("c", C.c_double), ("r", C.c_double), ("stage1", C.c_double), ("stage2", C.c_double),
+        ("head_ratio", C.c_double), ("page_size", C.c_int32), ("keep_budget", C.c_int32),
+        ("channel_budget", C.c_int32), ("attend_tokens", C.c_int32),
     ]
 
 
@@ -80,6 +90,8 @@ def lib():
         L.rocketkv_append_kv.argtypes = [cp, vp, vp, vp, vp, vp]
         L.rocketkv_snapkv_compress.restype = i32
         L.rocketkv_snapkv_compress.argtypes = [vp, cp, i32, i32, i32, cp, vp, vp, sz, vp]
+        L.rocketkv_decompose.restype = i32
+        L.rocketkv_decompose.argtypes = [C.c_int64, i32, i32, C.POINTER(SplitStruct)]
         L.rocketkv_last_error.restype = C.c_char_p
         L.rocketkv_last_error.argtypes = []
         L.rocketkv_version.restype = i32
@@ -117,7 +129,8 @@ class Cache:
     """A paged KV cache living in torch tensors, plus its C descriptor.
 
     k_pool: bf16 [n_phys_pages][n_kv_heads][page_size][head_dim]
-    v_pool: bf16 [n_phys_pages][n_kv_heads][head_dim][page_size]
+    v_pool: bf16 [n_phys_pages][n_kv_heads][head_dim][page_size], or
+            [n_phys_pages][n_kv_heads][page_size][head_dim] when v_layout is V_TOKEN_MAJOR
     seq_lens: int32 [batch]; block_table: int32 [batch][pages_cap] or None (identity).
     """
     batch: int
@@ -130,13 +143,14 @@ class Cache:
     v_pool: object
     seq_lens: object
     block_table: object = None
+    v_layout: int = V_CHANNEL_MAJOR
 
     def struct(self) -> CacheStruct:
         tile = self.page_size * self.head_dim
         return CacheStruct(self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim,
                            self.page_size, self.pages_cap, int(self.k_pool.shape[0]),
                            self.n_kv_heads * tile, tile, _ptr(self.seq_lens),
-                           _ptr(self.block_table), _ptr(self.k_pool), _ptr(self.v_pool))
+                           _ptr(self.block_table), _ptr(self.k_pool), _ptr(self.v_pool), self.v_layout)
 
     @property
     def units(self) -> int:
@@ -144,20 +158,21 @@ class Cache:
 
 
 def alloc_cache(batch, n_q_heads, n_kv_heads, head_dim, page_size, pages_cap, device,
-                block_table=None, n_phys_pages=None, zero=False) -> Cache:
+                block_table=None, n_phys_pages=None, zero=False, v_layout=V_CHANNEL_MAJOR) -> Cache:
     import torch
     pages_cap = (pages_cap + 7) // 8 * 8
     n_phys = n_phys_pages if n_phys_pages is not None else batch * pages_cap
     mk = torch.zeros if zero else torch.empty
     k_pool = mk((n_phys, n_kv_heads, page_size, head_dim), dtype=torch.bfloat16, device=device)
-    v_pool = mk((n_phys, n_kv_heads, head_dim, page_size), dtype=torch.bfloat16, device=device)
+    v_shape = (page_size, head_dim) if v_layout == V_TOKEN_MAJOR else (head_dim, page_size)
+    v_pool = mk((n_phys, n_kv_heads) + v_shape, dtype=torch.bfloat16, device=device)
     seq_lens = torch.zeros((batch,), dtype=torch.int32, device=device)
     return Cache(batch, n_q_heads, n_kv_heads, head_dim, page_size, pages_cap, k_pool, v_pool,
-                 seq_lens, block_table)
+                 seq_lens, block_table, v_layout)
 
 
 def pack_cache(K, V, seq_lens, n_q_heads, page_size, pages_cap=None, block_table=None,
-               n_phys_pages=None) -> Cache:
+               n_phys_pages=None, v_layout=V_CHANNEL_MAJOR) -> Cache:
     """Lay token-major bf16 K, V ([B][Hkv][n][D] torch tensors on the device) out as a paged cache.
 
     Pure data movement (pad, reshape, permute, scatter by the block table)."""
@@ -166,20 +181,23 @@ def pack_cache(K, V, seq_lens, n_q_heads, page_size, pages_cap=None, block_table
     need = (n + page_size - 1) // page_size
     pages_cap = max(need, pages_cap or 0, 1)
     cache = alloc_cache(B, n_q_heads, Hkv, D, page_size, pages_cap, K.device, block_table,
-                        n_phys_pages, zero=True)
+                        n_phys_pages, zero=True, v_layout=v_layout)
     pc = cache.pages_cap
     pad = pc * page_size - n
     Kp = torch.nn.functional.pad(K, (0, 0, 0, pad)) if pad else K
     Vp = torch.nn.functional.pad(V, (0, 0, 0, pad)) if pad else V
     Kt = Kp.reshape(B, Hkv, pc, page_size, D).permute(0, 2, 1, 3, 4)        # [B][pc][Hkv][ps][D]
-    Vt = Vp.reshape(B, Hkv, pc, page_size, D).permute(0, 2, 1, 4, 3)        # [B][pc][Hkv][D][ps]
+    Vt = Vp.reshape(B, Hkv, pc, page_size, D).permute(0, 2, 1, 3, 4)        # [B][pc][Hkv][ps][D]
+    if v_layout != V_TOKEN_MAJOR:
+        Vt = Vt.transpose(3, 4)                                              # [B][pc][Hkv][D][ps]
+    v_tile = tuple(cache.v_pool.shape[2:])
     if block_table is None:
         cache.k_pool[:B * pc].copy_(Kt.reshape(B * pc, Hkv, page_size, D))
-        cache.v_pool[:B * pc].copy_(Vt.reshape(B * pc, Hkv, D, page_size))
+        cache.v_pool[:B * pc].copy_(Vt.reshape((B * pc, Hkv) + v_tile))
     else:
         idx = block_table.reshape(-1).long()
         cache.k_pool.index_copy_(0, idx, Kt.reshape(B * pc, Hkv, page_size, D).contiguous())
-        cache.v_pool.index_copy_(0, idx, Vt.reshape(B * pc, Hkv, D, page_size).contiguous())
+        cache.v_pool.index_copy_(0, idx, Vt.reshape((B * pc, Hkv) + v_tile).contiguous())
     cache.seq_lens.copy_(torch.as_tensor(seq_lens, dtype=torch.int32))
     return cache
 
@@ -193,7 +211,10 @@ def unpack_cache(cache: Cache):
         idx = cache.block_table.reshape(-1).long()
         kp, vp = cache.k_pool[idx], cache.v_pool[idx]
     K = kp.reshape(B, pc, Hkv, ps, D).permute(0, 2, 1, 3, 4).reshape(B, Hkv, pc * ps, D)
-    V = vp.reshape(B, pc, Hkv, D, ps).permute(0, 2, 1, 4, 3).reshape(B, Hkv, pc * ps, D)
+    if cache.v_layout == V_TOKEN_MAJOR:
+        V = vp.reshape(B, pc, Hkv, ps, D).permute(0, 2, 1, 3, 4).reshape(B, Hkv, pc * ps, D)
+    else:
+        V = vp.reshape(B, pc, Hkv, D, ps).permute(0, 2, 1, 4, 3).reshape(B, Hkv, pc * ps, D)
     return K.contiguous(), V.contiguous()
 
 
@@ -285,6 +306,13 @@ def snapkv_compress(q_obs, src: Cache, window: int, pool_kernel: int, keep_budge
     _check(lib().rocketkv_snapkv_compress(_ptr(q_obs), C.byref(s), window, pool_kernel, keep_budget,
                                           C.byref(d), _ptr(kept_idx), _ptr(workspace),
                                           workspace.numel(), _stream(stream)))
+
+
+def decompose(seq_len: int, token_budget: int, head_dim: int = 128) -> dict:
+    """Adaptive compression decomposition (host arithmetic in the library); see rocketkv_decompose."""
+    out = SplitStruct()
+    _check(lib().rocketkv_decompose(int(seq_len), int(token_budget), int(head_dim), C.byref(out)))
+    return {name: getattr(out, name) for name, _ in SplitStruct._fields_}
 
 
 def pages_row_len(cache: Cache, token_budget: int) -> int:

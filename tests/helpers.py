@@ -46,7 +46,7 @@ def make_block_table(rng, batch, pages_cap, n_phys):
 
 
 def to_device_cache(rk, torch, d, n_q_heads, page_size, device, pages_cap=None, shuffle_rng=None,
-                    extra_pages=0):
+                    extra_pages=0, v_layout=0):
     """Upload a generated workload (uint16 arrays) as a paged cache. Returns (cache, q tensor)."""
     K = wl.from_bits(d["K"], device)
     V = wl.from_bits(d["V"], device)
@@ -59,6 +59,6 @@ def to_device_cache(rk, torch, d, n_q_heads, page_size, device, pages_cap=None, 
         n_phys = B * need + extra_pages
         bt = torch.from_numpy(make_block_table(shuffle_rng, B, need, n_phys)).to(device)
     cache = rk.pack_cache(K, V, d["seq_lens"], n_q_heads, page_size, pages_cap=need, block_table=bt,
-                          n_phys_pages=n_phys)
+                          n_phys_pages=n_phys, v_layout=v_layout)
     q = wl.from_bits(d["q"], device)
     return cache, q

@@ -128,3 +128,41 @@ def test_snapkv_argument_checks(L):
     assert call(dst=fake_cache(n_kv_heads=4, k_pool=0x30000, v_pool=0x40000)) == rk.INVALID_ARG
     assert call(dst=src) == rk.INVALID_ARG and "distinct" in rk.last_error()
     assert call(wsb=1024) == rk.WORKSPACE_TOO_SMALL
+
+
+def test_decompose_is_host_arithmetic_and_matches_oracle(L, oracle):
+    """rocketkv_decompose launches nothing, so it is checked here against the oracle's own
+    evaluation of Section 3.6 over a grid of sequence lengths and budgets."""
+    g = {}
+    for line in open(os.path.join(ROOT, "tests", "golden", "decompose_c64.txt")):
+        if line.strip() and not line.startswith("#"):
+            k, v = line.split()
+            g[k] = float(v)
+    got = rk.decompose(64 * 512, 512, 128)
+    assert got["c"] == g["c"] and round(got["r"], 2) == g["r"]
+    assert round(got["stage1"], 1) == g["stage1"] and round(got["stage2"], 1) == g["stage2"]
+    assert got["page_size"] == g["page"] and round(got["head_ratio"], 1) == g["head_ratio"]
+    for S in (1, 100, 4096, 32768, 131072, 1 << 20):
+        for t in (1, 256, 512, 1024, 4096, 16384):
+            for D in (64, 128):
+                got = rk.decompose(S, t, D)
+                ref = oracle.decompose(max(1.0, S / t))
+                want = oracle.decompose_budget(S, t, D)
+                for k_lib, k_or in (("r", "r"), ("stage1", "stage1"), ("stage2", "stage2"),
+                                    ("head_ratio", "head_ratio")):
+                    assert abs(got[k_lib] - ref[k_or]) <= 1e-12 * max(1.0, abs(ref[k_or]))
+                assert (got["page_size"], got["keep_budget"], got["channel_budget"], got["attend_tokens"]) == \
+                    (want["page"], want["keep"], want["channels"], want["attend_tokens"]), (S, t, D)
+    out = rk.SplitStruct()
+    assert L.rocketkv_decompose(0, 512, 128, C.byref(out)) == rk.INVALID_ARG
+    assert L.rocketkv_decompose(4096, 0, 128, C.byref(out)) == rk.INVALID_ARG
+    assert L.rocketkv_decompose(4096, 512, 128, None) == rk.INVALID_ARG
+
+
+def test_layout_field_is_validated(L):
+    st = fake_cache(v_layout=7)
+    assert L.rocketkv_workspace_bytes(rk.OP_DENSE_DECODE, C.byref(st), 0, 0) == 0
+    assert "v_layout" in rk.last_error()
+    # token-major caches may have any page size up to 64; channel-major attention needs 16
+    tm = fake_cache(page_size=3, stride_page=8 * 3 * 128, stride_head=3 * 128, v_layout=rk.V_TOKEN_MAJOR)
+    assert L.rocketkv_workspace_bytes(rk.OP_HSA_DECODE, C.byref(tm), 256, 0) > 0

@@ -383,6 +383,28 @@ def test_decomposition_clamps_and_recombines(oracle):
     assert oracle.decompose(1.0)["r"] == 0.2
 
 
+def test_decomposed_operating_point_reproduces_the_budget(oracle):
+    """Appendix A.3 splits the budget t evenly: Step 2 reads keep/page summary rows of `channels`
+    elements (one of max/min per channel), i.e. keep*channels/(page*2D) key/value pairs = t/2, and
+    Step 3 attends to t/2 tokens.  The integer point must reproduce that up to its own rounding,
+    and its ratios must be the ones the section prints for c = 64."""
+    g = read_golden("decompose_c64.txt")
+    S, t, D = 64 * 1024, 1024, 128
+    p = oracle.decompose_budget(S, t, D)
+    assert p["page"] == g["page"]
+    assert round(S / p["keep"], 1) == g["stage1"]
+    assert abs(D / p["channels"] - g["head_ratio"]) < 0.05
+    assert p["attend_tokens"] == t // 2
+    for S, t in [(32768, 256), (32768, 512), (32768, 4096), (131072, 1024), (131072, 16384), (8192, 512)]:
+        p = oracle.decompose_budget(S, t, D)
+        step2_pairs = p["keep"] * p["channels"] / (p["page"] * 2.0 * D)
+        assert abs(step2_pairs - t / 2) <= 0.02 * t / 2 + 1, (S, t, p)
+        assert p["attend_tokens"] == t // 2
+    # no compression asked for: nothing evicted, every channel, single-token pages
+    p = oracle.decompose_budget(1000, 4096, D)
+    assert (p["page"], p["keep"], p["channels"]) == (1, 1000, D)
+
+
 def test_kv_size_example_matches_byte_accounting():
     g = read_golden("kv_size_example.txt")
     total = (g["layers"] * g["batch"] * g["kv_heads"] * g["context"] * g["head_dim"]
