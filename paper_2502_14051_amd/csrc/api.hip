@@ -125,8 +125,9 @@ int check_attend_shape(const rocketkv_cache_t* c, const char* who) {
 // token-major cache of another page size is planned on the token slots its entries add up to.
 AttendPlan attend_plan_for(const CacheView& v, int row_len) {
   if (!v.v_token_major) return plan_attend(v, row_len);
+  // whole entries only: the kernel's last wavefront absorbs a remainder of fewer than 16 slots
   const int64_t slots = (int64_t)row_len * v.page_size;
-  return plan_attend(v, (int)((slots + kAttnPage - 1) / kAttnPage));
+  return plan_attend(v, slots >= kAttnPage ? (int)(slots / kAttnPage) : 1);
 }
 
 hipError_t launch_attend_any(const CacheView& v, const bf16_t* q, const int32_t* pages, int row_len,
@@ -139,7 +140,7 @@ hipError_t launch_attend_any(const CacheView& v, const bf16_t* q, const int32_t*
 struct DecodePlan {
   AttendPlan attend;
   int row_len;
-  size_t list_off, attend_off, total;
+  size_t list_off, scores_off, attend_off, total;
 };
 
 DecodePlan plan_decode(const rocketkv_cache_t* c, int T) {
@@ -152,6 +153,8 @@ DecodePlan plan_decode(const rocketkv_cache_t* c, int T) {
   off += d.attend.total_bytes;
   d.list_off = off;
   off += ((size_t)c->batch * c->n_kv_heads * d.row_len * sizeof(int32_t) + 255) / 256 * 256;
+  d.scores_off = off;  // page scores, for selections that run as a score launch plus a top-k launch
+  off += ((size_t)c->batch * c->n_kv_heads * c->pages_cap * sizeof(float) + 255) / 256 * 256;
   d.total = off;
   return d;
 }
@@ -241,6 +244,7 @@ int32_t rocketkv_hsa_select(const rocketkv_cache_t* cache, const void* q, const 
   a.row_len2 = 0;
   a.out_channels = out_channels;
   a.out_scores = out_scores;
+  a.in_scores = nullptr;
   a.zero_counters = nullptr;
   const hipError_t e = launch_hsa_select(view_of(cache), a, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? ROCKETKV_OK : hip_fail(e, who);
@@ -304,6 +308,7 @@ int decode_impl(const char* who, const rocketkv_cache_t* cache, const void* q, c
   a.row_len = d.row_len;
   a.out_channels = out_channels;
   a.out_scores = nullptr;
+  a.in_scores = nullptr;
   AppendArgs ap = {static_cast<const bf16_t*>(k_new), static_cast<const bf16_t*>(v_new),
                    static_cast<bf16_t*>(kmax), static_cast<bf16_t*>(kmin)};
   hipError_t e;
@@ -324,6 +329,7 @@ int decode_impl(const char* who, const rocketkv_cache_t* cache, const void* q, c
   a.out_pages2 = out_pages;
   a.row_len2 = d.row_len;
   a.zero_counters = d.attend.n_split > 1 ? attend_counters(ws + d.attend_off, d.attend) : nullptr;
+  if (select_wants_split(v, a.k1)) a.out_scores = reinterpret_cast<float*>(ws + d.scores_off);
   e = launch_hsa_select(v, a, st);
   if (e != hipSuccess) return hip_fail(e, who);
   e = launch_attend_any(v, a.q, a.out_pages, d.row_len, static_cast<bf16_t*>(out), out_lse,

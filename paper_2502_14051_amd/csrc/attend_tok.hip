@@ -84,11 +84,13 @@ void attend_tokens_kernel(CacheView c, AttendArgs a, TokenRun t) {
   if (n > c.pages_cap * ps) n = c.pages_cap * ps;
   const int32_t* list = a.pages ? a.pages + (int64_t)unit * a.row_len : nullptr;
 
-  // this wave's share of the token slots (chunk and per_wave are multiples of 32)
+  // this wave's share of the token slots (chunk and per_wave are multiples of 32).  The plan is laid
+  // out on whole 16-slot entries; the last wavefront of the last workgroup also takes the few slots
+  // left over when pages do not fill the last entry, rather than a workgroup being launched for them.
   const int e_begin = split * a.chunk;
-  const int e_end = min(e_begin + a.chunk, t.tokens);
-  const int wb = e_begin + wave * a.per_wave;
-  const int we = min(wb + a.per_wave, e_end);
+  const int e_end = split == a.n_split - 1 ? t.tokens : min(e_begin + a.chunk, t.tokens);
+  const int wb = min(e_begin + wave * a.per_wave, e_end);
+  const int we = wave == WAVES - 1 ? e_end : min(wb + a.per_wave, e_end);
 
   u32x4 qf[4];
   {
@@ -124,11 +126,13 @@ void attend_tokens_kernel(CacheView c, AttendArgs a, TokenRun t) {
     const int e = f / ps, slot = f - e * ps;
     int page = -1;
     if (ok) page = list ? list[e] : e;
-    ok = ok && page >= 0 && page * ps + slot < n;
+    // the row address needs only a page inside the table; the sequence length (possibly still on
+    // its way from memory) enters the mask alone
+    ok = ok && page >= 0 && page < c.pages_cap;
     const int64_t pp = ok ? phys_page(c, b, page) : -1;
     ok = ok && pp >= 0;
     const int64_t off = ok ? pp * c.stride_page + slot * kHeadDim : 0;
-    const unsigned long long live = __ballot(ok);
+    const unsigned long long live = __ballot(ok && page * ps + slot < n);
     const int cnt = min(kWave, we - base);
     for (int i = 0; i * 32 < cnt; ++i) {
       u32x4 kf[2][4], vr[2][4];

@@ -95,8 +95,13 @@ struct SelectArgs {
   int row_len2;
   int32_t* out_channels;  // optional
   float* out_scores;      // optional
+  const float* in_scores; // set by the launcher when the scores come from a separate launch
   uint32_t* zero_counters;  // optional [units]: cleared for the attention kernel that follows
 };
+// One launch when the picked summary rows are small enough for a workgroup per (sequence, KV head);
+// otherwise, and only if a.out_scores gives it somewhere to put the scores, a score launch split over
+// the pages followed by the top-k launch.
+bool select_wants_split(const CacheView& c, int k1);
 hipError_t launch_hsa_select(const CacheView& c, const SelectArgs& a, hipStream_t st);
 
 struct AttendPlan {

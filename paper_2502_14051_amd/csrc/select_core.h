@@ -170,6 +170,50 @@ __device__ __forceinline__ void select_channels(const CacheView& c, const Select
   __syncthreads();
 }
 
+// The kp-th largest of the P order keys in `keys` (LDS) by four 8-bit radix passes, as (tau, need_eq):
+// the selection is every key above tau plus the first need_eq keys equal to it.  Needs kp < P and
+// `hist` (LDS, 4 x 256 counters, 16-byte aligned) zeroed; every thread gets the result.
+template <int NT>
+__device__ __forceinline__ void radix_threshold(const uint32_t* keys, int P, int kp, uint32_t (*hist)[256],
+                                                uint32_t& tau, uint32_t& need_eq) {
+  const int tid = threadIdx.x, lane = tid % kWave;
+  uint32_t prefix = 0, mask = 0, k = (uint32_t)kp;
+  for (int pass = 0; pass < 4; ++pass) {
+    const int shift = 24 - 8 * pass;
+    for (int p = tid; p < P; p += NT) {
+      const uint32_t key = keys[p];
+      if ((key & mask) == prefix) atomicAdd(&hist[pass][(key >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    // every wavefront finds the bucket holding the k-th largest on its own (no broadcast needed):
+    // lane L owns bins 4(63-L)..4(63-L)+3, so a prefix sum over lanes counts the keys in higher bins
+    const int b0 = 4 * (kWave - 1 - lane);
+    const uint4 h = *reinterpret_cast<const uint4*>(&hist[pass][b0]);
+    const uint32_t s3 = h.w, s2 = h.z + s3, s1 = h.y + s2, s0 = h.x + s1;  // suffix sums inside the lane
+    const uint32_t above = wave_incl_scan(s0) - s0;                          // keys in bins of lower lanes
+    const uint32_t in[4] = {above + s0, above + s1, above + s2, above + s3};
+    const uint32_t hc[4] = {h.x, h.y, h.z, h.w};
+    int found = -1;
+    uint32_t newk = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint32_t exc = in[j] - hc[j];
+      if (exc < k && k <= in[j]) {
+        found = b0 + j;
+        newk = k - exc;
+      }
+    }
+    const unsigned long long who = __ballot(found >= 0);
+    const int src = __ffsll((long long)who) - 1;
+    const uint32_t bucket = (uint32_t)__builtin_amdgcn_readlane(found, src);
+    k = (uint32_t)__builtin_amdgcn_readlane((int)newk, src);
+    prefix |= bucket << shift;
+    mask |= 0xffu << shift;
+  }
+  tau = prefix;
+  need_eq = k;
+}
+
 // Step 2, second half for a sequence of n tokens: page scores from the picked summary rows, exact
 // top-kp pages.  `keys` is LDS scratch of ceil8(pages_cap) words.  The ascending list goes to
 // `list_lds` (if not null, kp entries) and, when `write_global`, to a.out_pages / a.out_pages2 (-1
@@ -179,7 +223,7 @@ template <int NT>
 __device__ __forceinline__ int select_pages(const CacheView& c, const SelectArgs& a, int unit, int n,
                                             SelectShared<NT>& sh, uint32_t* keys, int32_t* list_lds,
                                             bool write_global, const TailPatch& tp) {
-  const int tid = threadIdx.x, lane = tid % kWave;
+  const int tid = threadIdx.x;
   const int ps = c.page_size;
   int P = (n + ps - 1) / ps;
   if (P > c.pages_cap) P = c.pages_cap;
@@ -243,43 +287,7 @@ __device__ __forceinline__ int select_pages(const CacheView& c, const SelectArgs
 
   // ---- i2: exact kp-th largest key by 4 x 8-bit radix passes -------------------------------------
   uint32_t tau = 0, need_eq = (uint32_t)P;  // defaults select everything (kp == P)
-  if (kp < P) {
-    uint32_t prefix = 0, mask = 0, k = (uint32_t)kp;
-    for (int pass = 0; pass < 4; ++pass) {
-      const int shift = 24 - 8 * pass;
-      for (int p = tid; p < P; p += NT) {
-        const uint32_t key = keys[p];
-        if ((key & mask) == prefix) atomicAdd(&sh.hist[pass][(key >> shift) & 255u], 1u);
-      }
-      __syncthreads();
-      // every wavefront finds the bucket holding the k-th largest on its own (no broadcast needed):
-      // lane L owns bins 4(63-L)..4(63-L)+3, so a prefix sum over lanes counts the keys in higher bins
-      const int b0 = 4 * (kWave - 1 - lane);
-      const uint4 h = *reinterpret_cast<const uint4*>(&sh.hist[pass][b0]);
-      const uint32_t s3 = h.w, s2 = h.z + s3, s1 = h.y + s2, s0 = h.x + s1;  // suffix sums inside the lane
-      const uint32_t above = wave_incl_scan(s0) - s0;                          // keys in bins of lower lanes
-      const uint32_t in[4] = {above + s0, above + s1, above + s2, above + s3};
-      const uint32_t hc[4] = {h.x, h.y, h.z, h.w};
-      int found = -1;
-      uint32_t newk = 0;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const uint32_t exc = in[j] - hc[j];
-        if (exc < k && k <= in[j]) {
-          found = b0 + j;
-          newk = k - exc;
-        }
-      }
-      const unsigned long long who = __ballot(found >= 0);
-      const int src = __ffsll((long long)who) - 1;
-      const uint32_t bucket = (uint32_t)__builtin_amdgcn_readlane(found, src);
-      k = (uint32_t)__builtin_amdgcn_readlane((int)newk, src);
-      prefix |= bucket << shift;
-      mask |= 0xffu << shift;
-    }
-    tau = prefix;
-    need_eq = k;
-  }
+  if (kp < P) radix_threshold<NT>(keys, P, kp, sh.hist, tau, need_eq);
 
   // ---- emit ascending: every key > tau, plus the first need_eq keys == tau -----------------------
   const int ipt = (P + NT - 1) / NT;
@@ -313,6 +321,237 @@ __device__ __forceinline__ int select_pages(const CacheView& c, const SelectArgs
     if (key > tau) ++gt;
   }
   return kp;
+}
+
+__device__ __forceinline__ float f32_from_order_key(uint32_t k) {
+  return __uint_as_float((k & 0x80000000u) ? (k ^ 0x80000000u) : ~k);
+}
+
+// Step 2's top-k (Algorithm 1, i2) on page scores that an earlier launch left in a.in_scores: the
+// pick of the large-summary path.  A thread keeps its contiguous run of a few scores in registers
+// from the one batch of loads to the ordered emission, so no pass waits on LDS reads.
+//
+// The kp-th largest score is found by counting, not by radix digits: one pass over 1023 equal-width
+// value bins between the smallest and the largest finite score (+inf, the forced recent pages, has a
+// bin of its own), a scan over the bins, then an exact rank among the few scores that share the bin
+// of the kp-th.  Page scores differ in their low mantissa bits rather than in their exponents, so
+// value bins spread them where the leading radix digits would pile them into one or two counters.
+// Binning is monotone, hence the result is exactly the radix select's, ties to the lower page
+// included.  Scores without a finite range, or more than 1024 of them in that one bin, fall back to
+// the radix passes on the LDS copy of the keys.  `keys`: LDS, ceil8(pages_cap) words.
+template <int NT>
+struct PickShared {
+  __align__(16) uint32_t hist[4][256];  // 1024 value bins, or the four radix histograms of the fallback
+  uint32_t cand[1024];
+  float wmin[NT / kWave], wmax[NT / kWave];
+  uint32_t wsum[NT / kWave];
+  int found[6];
+  uint32_t cnt0;
+};
+
+template <int NT>
+__device__ __forceinline__ void pick_from_scores(const CacheView& c, const SelectArgs& a, int unit, int n,
+                                                 PickShared<NT>& sh, uint32_t* keys) {
+  constexpr int kVec = ROCKETKV_MAX_PAGES / 4 / NT;  // float4 loads per thread at the largest P
+  constexpr int NB = 1024, BPT = NB / NT, CAP = 1024;
+  static_assert(kVec >= 1 && NB % NT == 0, "thread count does not fit the pick");
+  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+  // ---- this thread's run of pages, [4 * v_begin, 4 * v_begin + 4 * per), laid out on pages_cap so
+  // that the loads go out before the sequence length is known ---------------------------------------
+  const int per = (c.pages_cap / 4 + NT - 1) / NT;  // rows hold pages_cap (a multiple of 8) floats
+  const int v_begin = tid * per;
+  const float4* in4 = reinterpret_cast<const float4*>(a.in_scores + (int64_t)unit * c.pages_cap);
+  float4 v[kVec];
+#pragma unroll
+  for (int i = 0; i < kVec; ++i)
+    v[i] = (i < per && (v_begin + i) * 4 < c.pages_cap) ? in4[v_begin + i] : make_float4(0.f, 0.f, 0.f, 0.f);
+  const int ps = c.page_size;
+  int P = (n + ps - 1) / ps;
+  if (P > c.pages_cap) P = c.pages_cap;
+  int kp = pages_to_pick(n, ps, a.T);
+  if (kp > P) kp = P;
+  if (kp > a.row_len) kp = a.row_len;
+  if (a.out_pages)
+    for (int i = kp + tid; i < a.row_len; i += NT) a.out_pages[(int64_t)unit * a.row_len + i] = -1;
+  if (a.out_pages2)
+    for (int i = kp + tid; i < a.row_len2; i += NT) a.out_pages2[(int64_t)unit * a.row_len2 + i] = -1;
+  if (P == 0) return;
+  uint32_t key[kVec * 4];
+  float lo = INFINITY, hi = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < kVec; ++i) {
+    const float x[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int pg = (v_begin + i) * 4 + e;
+      const bool live = i < per && pg < P;
+      float sc = live ? x[e] : -INFINITY;
+      if (live && pg >= P - a.n_recent) sc = INFINITY;
+      key[i * 4 + e] = f32_order_key(sc);
+      if (live) {
+        keys[pg] = key[i * 4 + e];
+        if (fabsf(sc) < INFINITY) {
+          lo = fminf(lo, sc);
+          hi = fmaxf(hi, sc);
+        }
+      }
+    }
+  }
+  // `live` again, as a test on the register index alone
+  const auto is_live = [&](int r) { return r / 4 < per && (v_begin + r / 4) * 4 + (r & 3) < P; };
+
+  uint32_t tau = 0, need_eq = (uint32_t)P;  // defaults select everything (kp == P)
+  if (kp < P) {
+    uint32_t* hist = &sh.hist[0][0];
+    uint32_t* cand = sh.cand;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+      lo = fminf(lo, __shfl_xor(lo, off));
+      hi = fmaxf(hi, __shfl_xor(hi, off));
+    }
+    if (lane == 0) {
+      sh.wmin[wave] = lo;
+      sh.wmax[wave] = hi;
+    }
+    if (tid == 0) sh.cnt0 = 0;
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < NT / kWave; ++w) {
+      lo = fminf(lo, sh.wmin[w]);
+      hi = fmaxf(hi, sh.wmax[w]);
+    }
+    const float scale = (float)(NB - 1) / (hi - lo);
+    bool decided = (hi > lo) && (scale < 3.0e38f);  // same for every thread
+    if (decided) {
+      const auto bin_of = [&](uint32_t k) -> int {
+        const float f = f32_from_order_key(k);
+        if (f == INFINITY) return NB - 1;
+        const int b = (int)((f - lo) * scale);
+        return min(max(b, 0), NB - 2);
+      };
+      int bin[kVec * 4];
+#pragma unroll
+      for (int r = 0; r < kVec * 4; ++r) {
+        bin[r] = bin_of(key[r]);
+        if (is_live(r)) atomicAdd(&hist[bin[r]], 1u);
+      }
+      __syncthreads();
+      // thread t owns the BPT bins below NB - t*BPT: a prefix sum over threads counts the bins above
+      uint32_t h[BPT], total = 0;
+#pragma unroll
+      for (int j = 0; j < BPT; ++j) {
+        h[j] = hist[NB - 1 - tid * BPT - j];  // j = 0: the thread's highest bin
+        total += h[j];
+      }
+      uint32_t above = block_excl_scan<NT>(total, sh.wsum);
+#pragma unroll
+      for (int j = 0; j < BPT; ++j) {
+        if (above < (uint32_t)kp && (uint32_t)kp <= above + h[j]) {
+          sh.found[0] = NB - 1 - tid * BPT - j;
+          sh.found[1] = (int)((uint32_t)kp - above);
+          sh.found[2] = (int)h[j];
+        }
+        above += h[j];
+      }
+      __syncthreads();
+      const int bstar = sh.found[0], need = sh.found[1], cnum = sh.found[2];
+      decided = cnum <= CAP;
+      if (decided) {
+#pragma unroll
+        for (int r = 0; r < kVec * 4; ++r)
+          if (is_live(r) && bin[r] == bstar) cand[atomicAdd(&sh.cnt0, 1u)] = key[r];
+        __syncthreads();
+        for (int i = tid; i < cnum; i += NT) {
+          const uint32_t ki = cand[i];
+          int gt = 0, ge = 0;
+          for (int j = 0; j < cnum; ++j) {
+            const uint32_t kj = cand[j];
+            gt += kj > ki;
+            ge += kj >= ki;
+          }
+          if (gt < need && need <= ge) {  // ki is the need-th largest; equal keys write the same pair
+            sh.found[4] = (int)ki;
+            sh.found[5] = need - gt;
+          }
+        }
+        __syncthreads();
+        tau = (uint32_t)sh.found[4];
+        need_eq = (uint32_t)sh.found[5];
+      }
+    }
+    if (!decided) {
+      __syncthreads();
+      for (int i = tid; i < 4 * 256; i += NT) hist[i] = 0;
+      __syncthreads();
+      radix_threshold<NT>(keys, P, kp, sh.hist, tau, need_eq);
+      __syncthreads();
+    }
+  }
+
+  // ---- emit ascending: every key > tau, plus the first need_eq keys == tau -----------------------
+  uint32_t cnt = 0;  // low 16 bits: keys > tau, high 16 bits: keys == tau
+#pragma unroll
+  for (int r = 0; r < kVec * 4; ++r) {
+    if (is_live(r)) {
+      cnt += (key[r] > tau) ? 1u : 0u;
+      cnt += (key[r] == tau) ? 0x10000u : 0u;
+    }
+  }
+  const uint32_t before = block_excl_scan<NT>(cnt, sh.wsum);
+  uint32_t gt = before & 0xffffu, eq = before >> 16;
+#pragma unroll
+  for (int r = 0; r < kVec * 4; ++r) {
+    if (is_live(r)) {
+      const int pg = (v_begin + r / 4) * 4 + (r & 3);
+      bool take = key[r] > tau;
+      if (key[r] == tau) {
+        take = eq < need_eq;
+        ++eq;
+      }
+      if (take) {
+        const uint32_t eq_taken = (key[r] == tau) ? eq - 1 : min(eq, need_eq);
+        const uint32_t pos = gt + eq_taken;
+        if ((int)pos < kp) {
+          if (a.out_pages) a.out_pages[(int64_t)unit * a.row_len + pos] = pg;
+          if (a.out_pages2 && (int)pos < a.row_len2) a.out_pages2[(int64_t)unit * a.row_len2 + pos] = pg;
+        }
+      }
+      if (key[r] > tau) ++gt;
+    }
+  }
+}
+
+// Page scores of the eight-page runs [o_begin, o_begin + n_runs) of one unit, n_runs <= NT, written as
+// raw fp32 sums to `scores_row[page]` for page < P.  For summaries too large for one workgroup to
+// stream at a useful rate: several workgroups take a slice each (every one repeats the cheap channel
+// pick), and the top-k runs afterwards on the scores.  Needs sh.s_chan / sh.s_wgt; ends with a barrier.
+template <int NT>
+__device__ __forceinline__ void score_chunk(const CacheView& c, const SelectArgs& a, int unit, int P,
+                                            SelectShared<NT>& sh, int o_begin, int n_runs,
+                                            float* scores_row) {
+  const int tid = threadIdx.x;
+  const TailPatch none = {-1, 0, nullptr, nullptr};
+  const int64_t rows = (int64_t)unit * kHeadDim;
+  int npow = 1;
+  while (npow < n_runs) npow <<= 1;
+  const int R = NT / npow;  // row groups summed separately, then in order
+  const int r = tid / npow, o = tid % npow;
+  float acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+  if (o < n_runs)
+    for (int j0 = r; j0 < a.k1; j0 += 8 * R)
+      score_rows8(a, sh.s_chan, sh.s_wgt, rows, c.pages_cap, o_begin + o, j0, R, none, acc);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) sh.partial[(r * npow + o) * 8 + i] = acc[i];
+  __syncthreads();
+  for (int p = tid; p < n_runs * 8; p += NT) {
+    float s = 0.f;
+    for (int rr = 0; rr < R; ++rr) s += sh.partial[rr * npow * 8 + p];
+    const int page = o_begin * 8 + p;
+    if (page < P) scores_row[page] = s;
+  }
+  __syncthreads();
 }
 
 // Both halves back to back.

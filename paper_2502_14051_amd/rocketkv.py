@@ -131,6 +131,8 @@ class Cache:
     k_pool: bf16 [n_phys_pages][n_kv_heads][page_size][head_dim]
     v_pool: bf16 [n_phys_pages][n_kv_heads][head_dim][page_size], or
             [n_phys_pages][n_kv_heads][page_size][head_dim] when v_layout is V_TOKEN_MAJOR
+    Both may be strided views of one allocation (`interleaved`: the K tile of a (page, head) is
+    followed by its V tile), which the C descriptor expresses through its strides.
     seq_lens: int32 [batch]; block_table: int32 [batch][pages_cap] or None (identity).
     """
     batch: int
@@ -146,10 +148,10 @@ class Cache:
     v_layout: int = V_CHANNEL_MAJOR
 
     def struct(self) -> CacheStruct:
-        tile = self.page_size * self.head_dim
+        assert self.k_pool.stride()[:2] == self.v_pool.stride()[:2], "K and V pools must share strides"
         return CacheStruct(self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim,
                            self.page_size, self.pages_cap, int(self.k_pool.shape[0]),
-                           self.n_kv_heads * tile, tile, _ptr(self.seq_lens),
+                           int(self.k_pool.stride(0)), int(self.k_pool.stride(1)), _ptr(self.seq_lens),
                            _ptr(self.block_table), _ptr(self.k_pool), _ptr(self.v_pool), self.v_layout)
 
     @property
@@ -158,21 +160,27 @@ class Cache:
 
 
 def alloc_cache(batch, n_q_heads, n_kv_heads, head_dim, page_size, pages_cap, device,
-                block_table=None, n_phys_pages=None, zero=False, v_layout=V_CHANNEL_MAJOR) -> Cache:
+                block_table=None, n_phys_pages=None, zero=False, v_layout=V_CHANNEL_MAJOR,
+                interleaved=False) -> Cache:
     import torch
     pages_cap = (pages_cap + 7) // 8 * 8
     n_phys = n_phys_pages if n_phys_pages is not None else batch * pages_cap
     mk = torch.zeros if zero else torch.empty
-    k_pool = mk((n_phys, n_kv_heads, page_size, head_dim), dtype=torch.bfloat16, device=device)
     v_shape = (page_size, head_dim) if v_layout == V_TOKEN_MAJOR else (head_dim, page_size)
-    v_pool = mk((n_phys, n_kv_heads) + v_shape, dtype=torch.bfloat16, device=device)
+    if interleaved:
+        both = mk((n_phys, n_kv_heads, 2, page_size * head_dim), dtype=torch.bfloat16, device=device)
+        k_pool = both[:, :, 0].view(n_phys, n_kv_heads, page_size, head_dim)
+        v_pool = both[:, :, 1].view((n_phys, n_kv_heads) + v_shape)
+    else:
+        k_pool = mk((n_phys, n_kv_heads, page_size, head_dim), dtype=torch.bfloat16, device=device)
+        v_pool = mk((n_phys, n_kv_heads) + v_shape, dtype=torch.bfloat16, device=device)
     seq_lens = torch.zeros((batch,), dtype=torch.int32, device=device)
     return Cache(batch, n_q_heads, n_kv_heads, head_dim, page_size, pages_cap, k_pool, v_pool,
                  seq_lens, block_table, v_layout)
 
 
 def pack_cache(K, V, seq_lens, n_q_heads, page_size, pages_cap=None, block_table=None,
-               n_phys_pages=None, v_layout=V_CHANNEL_MAJOR) -> Cache:
+               n_phys_pages=None, v_layout=V_CHANNEL_MAJOR, interleaved=False) -> Cache:
     """Lay token-major bf16 K, V ([B][Hkv][n][D] torch tensors on the device) out as a paged cache.
 
     Pure data movement (pad, reshape, permute, scatter by the block table)."""
@@ -181,7 +189,7 @@ def pack_cache(K, V, seq_lens, n_q_heads, page_size, pages_cap=None, block_table
     need = (n + page_size - 1) // page_size
     pages_cap = max(need, pages_cap or 0, 1)
     cache = alloc_cache(B, n_q_heads, Hkv, D, page_size, pages_cap, K.device, block_table,
-                        n_phys_pages, zero=True, v_layout=v_layout)
+                        n_phys_pages, zero=True, v_layout=v_layout, interleaved=interleaved)
     pc = cache.pages_cap
     pad = pc * page_size - n
     Kp = torch.nn.functional.pad(K, (0, 0, 0, pad)) if pad else K

@@ -268,3 +268,35 @@ def test_snapkv_into_token_major(env, oracle, src_layout, dst_layout, dps):
             assert_topk_within_band(ref["pooled"][b, g, :L], row[:N - W], N - W, f"kept b{b} g{g}")
             assert np.array_equal(Kd[b, g, :N], d["K"][b, g, row])
             assert np.array_equal(Vd[b, g, :N], d["V"][b, g, row])
+
+
+@pytest.mark.parametrize("mode", ["pairs", "constant", "spread"])
+def test_split_selection_breaks_ties_towards_lower_index(env, oracle, mode):
+    """Large summaries take the score launch + top-k launch; its pick must resolve exact ties the way
+    Algorithm 1's argtopk is read here (larger score, then lower page), whether the value-binned
+    search decides or, for scores without a range, the radix passes behind it."""
+    torch, rk, dev = env
+    w = small("tiny", context=1100, page_size=1, channel_budget=128, token_budget=150, n_heavy=0)
+    say("split select ties", mode)
+    d = wl.generate(w)
+    K = d["K"].copy()
+    if mode == "pairs":
+        K[:, :, 1::2] = K[:, :, 0:-1:2]          # every key twice: every score twice
+    elif mode == "constant":
+        K[:] = K[:, :, :1]                       # one key everywhere: every score equal
+    d["K"] = K
+    cache, q = to_device_cache(rk, torch, d, w.n_q_heads, 1, dev, v_layout=TM)
+    kmax, kmin = rk.alloc_summaries(cache)
+    rk.build_page_summaries(cache, kmax, kmin)
+    row = rk.pages_row_len(cache, w.token_budget)
+    pages = torch.empty((1, w.n_kv_heads, row), dtype=torch.int32, device=dev)
+    scores = torch.empty((1, w.n_kv_heads, cache.pages_cap), dtype=torch.float32, device=dev)
+    rk.hsa_select(cache, q, kmax, kmin, 128, w.token_budget, 0, pages, None, scores)
+    torch.cuda.synchronize()
+    gp, gs = pages.cpu().numpy(), scores.cpu().numpy()
+    for g in range(w.n_kv_heads):
+        # exact expectation from the GPU's own fp32 scores: stable sort, larger first, lower index first
+        sc = gs[0, g, :1100]
+        want = np.sort(np.argsort(-sc.astype(np.float64), kind="stable")[:150])
+        assert np.array_equal(gp[0, g, :150], want), (mode, g)
+    check_selection(oracle, d, w, cache.pages_cap, gp, None, gs)
