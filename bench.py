@@ -48,6 +48,8 @@ def parse():
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--kernel-reps", type=int, default=20)
     ap.add_argument("--tune", type=str, default="", help="waves,pairs_per_wave override of the attention split")
+    ap.add_argument("--no-decomposed", action="store_true",
+                    help="skip the secondary measurement at the operating point of the adaptive decomposition")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (a known-size reference "
                          "for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
@@ -116,7 +118,7 @@ def main():
                  ws=rk.alloc_workspace(rk.OP_HSA_DECODE, dst, T))
         layers.append(L)
         if layer < n_dense:
-            dense_layers.append(dict(cache=src, q=L["q"],
+            dense_layers.append(dict(cache=src, q=L["q"], qobs=d["qobs"],
                                      out=torch.empty((B, Hq, D), dtype=torch.bfloat16, device=dev),
                                      ws=rk.alloc_workspace(rk.OP_DENSE_DECODE, src)))
         del d
@@ -237,6 +239,55 @@ def main():
 
     dense_us = timed_graph(dense_all, max(3, args.kernel_reps // 4)) * 1e3 / max(1, n_dense)
 
+    # ------------------------------------------------------------------ the method's own operating point
+    # Same model shape and the same traffic budget, but split the way Section 3.6 prescribes: the
+    # token budget t counts Step 2 and Step 3 together (t = 2T), and the decomposition of c = S / t
+    # gives the SnapKV keep budget, the page size and the channel count.  Token-major V layout, the
+    # selection split into a score launch and a top-k launch, token-gather attention.
+    dec_pt = None
+    if not args.no_decomposed and n_dense > 0:
+        sp = rk.decompose(w.context, 2 * T, D)
+        ps2, k12, T2, N2 = sp["page_size"], sp["channel_budget"], sp["attend_tokens"], sp["keep_budget"]
+        cap2 = ((N2 + total_steps + 8 + ps2 - 1) // ps2 + 7) // 8 * 8
+        pl = []
+        snap2_ws = rk.alloc_workspace(rk.OP_SNAPKV, dense_layers[0]["cache"], W, N2)
+        for Ld in dense_layers:
+            dst2 = rk.alloc_cache(B, Hq, Hkv, D, ps2, cap2, dev, zero=True, v_layout=rk.V_TOKEN_MAJOR)
+            rk.snapkv_compress(Ld["qobs"], Ld["cache"], W, w.pool_kernel, N2, dst2, None, snap2_ws)
+            km2, kn2 = rk.alloc_summaries(dst2)
+            rk.build_page_summaries(dst2, km2, kn2)
+            pl.append(dict(cache=dst2, kmax=km2, kmin=kn2, q=Ld["q"], out=Ld["out"],
+                           new_k=layers[0]["new_k"], new_v=layers[0]["new_v"],
+                           ws=rk.alloc_workspace(rk.OP_HSA_DECODE, dst2, T2)))
+        torch.cuda.synchronize()
+
+        def dec_pt_all():
+            for L in pl:
+                rk.hsa_decode_append(L["cache"], L["q"], L["new_k"], L["new_v"], L["kmax"], L["kmin"], k12, T2, 0,
+                                     L["out"], None, None, None, L["ws"], stream)
+
+        def dec_pt_plain():
+            for L in pl:
+                rk.hsa_decode(L["cache"], L["q"], L["kmax"], L["kmin"], k12, T2, 0, L["out"], None, None, None,
+                              L["ws"], stream)
+
+        pt_plain_us = timed_graph(dec_pt_plain, args.kernel_reps) * 1e3 / len(pl)
+        pt_us = timed_graph(dec_pt_all, max(2, args.kernel_reps // 2)) * 1e3 / len(pl)
+        n2 = int(pl[0]["cache"].seq_lens[0].item())
+        P2 = (n2 + ps2 - 1) // ps2
+        kp2 = min(P2, max(1, T2 // ps2))
+        pt_bytes = units * (kp2 * ps2 * D * 2 * 2 + 2 * G * D * 2            # Step 3: K and V rows, q, out
+                            + k12 * ((P2 + 7) // 8 * 8) * 2 + P2 * 4 * 2 + kp2 * 4 * 2  # Step 2: rows, scores, list
+                            + 2 * D * 2 + 2 * D * 2 * 2)                        # the appended token
+        pt_gbs = pt_bytes / (pt_us * 1e-6) / 1e9
+        dec_pt = {"workload": f"same shape, t = {2 * T} split by Section 3.6: SnapKV keeps {N2}, page {ps2}, "
+                              f"k1 {k12}, {T2} tokens attended, token-major V, {len(pl)} layers",
+                  "us_per_layer_step": round(pt_us, 3), "us_per_layer_step_no_append": round(pt_plain_us, 3),
+                  "bytes_per_layer_step": pt_bytes, "achieved_GBs": round(pt_gbs, 1),
+                  "frac_of_hbm_peak": round(pt_gbs / HBM_PEAK_GBS, 4),
+                  "speedup_vs_dense_full_kv": round(dense_us / pt_us, 2)}
+        del pl
+
     # ------------------------------------------------------------------ bytes
     kp = min(P_now, T // ps)
     attend_bytes = units * (kp * ps * D * 2 * 2 + 2 * G * D * 2)
@@ -312,6 +363,7 @@ def main():
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(hsa_gbs / HBM_PEAK_GBS, 4),
                      "traffic": TRAFFIC_BYTES_PER_LAUNCH, "us_per_launch": round(us_layer, 3),
                      "bytes_per_launch": hsa_bytes},
+        "decomposed_operating_point": dec_pt,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))
