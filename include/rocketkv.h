@@ -240,6 +240,81 @@ int32_t rocketkv_snapkv_compress(const void* q_obs, const rocketkv_cache_t* src,
                                  size_t workspace_bytes, void* stream);
 
 /*
+ * RocketKV-MT (Section 3.5): the multi-turn variant.  Stage 1 evicts nothing: the cache keeps every
+ * token of the conversation, and Stage 2 runs over the subset Stage 1 filtered for the current turn
+ * plus the tokens generated since, reached through an index.  At the next turn the filter runs
+ * again over the whole cache, so a token passed over in one turn can come back in a later one.
+ *
+ * rocketkv_index_t describes that subset, the "logical sequence" of a (sequence, KV head):
+ *   token_index[b][g][j] = position in the cache of logical token j, ascending in j;
+ *   n_indexed[b]         = number of logical tokens (the same for every KV head of a sequence);
+ *   page_size, pages_cap = page size and page capacity of Stage 2 over the logical order: page p
+ *                          holds logical tokens p*page_size ..; summaries are
+ *                          [batch][n_kv_heads][head_dim][pages_cap].
+ * token_index rows have pages_cap * page_size entries.  The struct lives in host memory; its
+ * pointers are device pointers, written by rocketkv_snapkv_filter and the *_append calls.
+ * The cache itself must have token-major V (a token's row is what is gathered); its own page size
+ * is free.  A logical sequence is exactly what rocketkv_snapkv_compress would have copied out, so
+ * every mt call computes what its counterpart computes on that compacted cache.
+ */
+typedef struct rocketkv_index {
+  int32_t* token_index;
+  int32_t* n_indexed;
+  int32_t page_size;
+  int32_t pages_cap;
+} rocketkv_index_t;
+
+/*
+ * Stage 1 as a filter (Section 3.5): the selection of rocketkv_snapkv_compress on `src` (all of its
+ * rules, arguments and limits apply) written to index->token_index / index->n_indexed instead of a
+ * compacted copy; src is left untouched.  Needs index->pages_cap * index->page_size >= keep_budget.
+ * workspace: rocketkv_workspace_bytes(ROCKETKV_OP_SNAPKV, src, window, keep_budget).
+ */
+int32_t rocketkv_snapkv_filter(const void* q_obs, const rocketkv_cache_t* src, int32_t window,
+                               int32_t pool_kernel, int32_t keep_budget, const rocketkv_index_t* index,
+                               void* workspace, size_t workspace_bytes, void* stream);
+
+/* rocketkv_build_page_summaries over the logical order of `index` (Section 3.4 Step 1 on the
+ * filtered subset). */
+int32_t rocketkv_mt_build_page_summaries(const rocketkv_cache_t* cache, const rocketkv_index_t* index,
+                                         void* kmax, void* kmin, int32_t first_page, int32_t n_pages,
+                                         void* stream);
+
+/* Scratch bytes of rocketkv_mt_hsa_decode / rocketkv_mt_hsa_decode_append (0 on an invalid request). */
+size_t rocketkv_mt_workspace_bytes(const rocketkv_cache_t* cache, const rocketkv_index_t* index,
+                                   int32_t token_budget);
+
+/*
+ * rocketkv_hsa_decode over the logical sequence (Algorithm 1 restricted to the filtered subset):
+ * selection on the logical pages, exact attention over the cache rows the picked logical tokens
+ * point at.  out_pages holds logical page ids (row length min(index->pages_cap,
+ * ceil(token_budget / index->page_size))).
+ */
+int32_t rocketkv_mt_hsa_decode(const rocketkv_cache_t* cache, const rocketkv_index_t* index,
+                               const void* q, const void* kmax, const void* kmin,
+                               int32_t channel_budget, int32_t token_budget, int32_t n_recent_pages,
+                               void* out, float* out_lse, int32_t* out_pages, int32_t* out_channels,
+                               void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * A generated token enters both the cache (position cache->seq_lens[b], as rocketkv_append_kv does)
+ * and the logical sequence (entry index->n_indexed[b] of every KV head's index row, and the logical
+ * tail page's kmax / kmin); both lengths grow by one.  A sequence whose cache or index is full is
+ * left unchanged.
+ */
+int32_t rocketkv_mt_append_kv(const rocketkv_cache_t* cache, const rocketkv_index_t* index,
+                              const void* k_new, const void* v_new, void* kmax, void* kmin,
+                              void* stream);
+
+/* rocketkv_mt_append_kv followed by rocketkv_mt_hsa_decode: one decode step of RocketKV-MT. */
+int32_t rocketkv_mt_hsa_decode_append(const rocketkv_cache_t* cache, const rocketkv_index_t* index,
+                                      const void* q, const void* k_new, const void* v_new, void* kmax,
+                                      void* kmin, int32_t channel_budget, int32_t token_budget,
+                                      int32_t n_recent_pages, void* out, float* out_lse,
+                                      int32_t* out_pages, int32_t* out_channels, void* workspace,
+                                      size_t workspace_bytes, void* stream);
+
+/*
  * Adaptive compression decomposition (Section 3.6): for a sequence of seq_len
  * tokens and a total token budget t (memory traffic of one attention call in
  * key/value pairs, Step 2 and Step 3 together), c = seq_len / t (at least 1),

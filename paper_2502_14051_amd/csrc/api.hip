@@ -133,8 +133,29 @@ AttendPlan attend_plan_for(const CacheView& v, int row_len) {
 hipError_t launch_attend_any(const CacheView& v, const bf16_t* q, const int32_t* pages, int row_len,
                              bf16_t* out, float* out_lse, void* ws, const AttendPlan& plan,
                              hipStream_t st) {
-  return v.v_token_major ? launch_attend_tokens(v, q, pages, row_len, out, out_lse, ws, plan, st)
+  return v.v_token_major ? launch_attend_tokens(v, q, pages, row_len, out, out_lse, ws, plan, nullptr, st)
                          : launch_attend(v, q, pages, row_len, out, out_lse, ws, plan, st);
+}
+
+// argument rules of Stage 1 that involve the source only
+int check_snapkv_args(const void* q_obs, const rocketkv_cache_t* src, int32_t window, int32_t pool_kernel,
+                      int32_t keep_budget, const char* who) {
+  if (!q_obs) return fail(ROCKETKV_INVALID_ARG, "%s: q_obs must not be NULL", who);
+  if (((uintptr_t)q_obs) & 15) return fail(ROCKETKV_INVALID_ARG, "%s: q_obs must be 16-byte aligned", who);
+  if (src->page_size != kAttnPage)
+    return fail(ROCKETKV_UNSUPPORTED, "%s: src needs page_size %d (got %d)", who, kAttnPage, src->page_size);
+  if (window < 1 || window > 128 || window % 16 != 0)
+    return fail(window < 1 ? ROCKETKV_INVALID_ARG : ROCKETKV_UNSUPPORTED,
+                "%s: window %d must be a multiple of 16 in [16, 128]", who, window);
+  if ((src->n_q_heads / src->n_kv_heads) * window > 256)
+    return fail(ROCKETKV_UNSUPPORTED, "%s: group size x window (%d) exceeds 256", who,
+                (src->n_q_heads / src->n_kv_heads) * window);
+  if (pool_kernel < 1 || pool_kernel % 2 == 0)
+    return fail(ROCKETKV_INVALID_ARG, "%s: pool_kernel %d must be odd and positive", who, pool_kernel);
+  if (pool_kernel > 1023) return fail(ROCKETKV_UNSUPPORTED, "%s: pool_kernel %d > 1023", who, pool_kernel);
+  if (keep_budget <= window)
+    return fail(ROCKETKV_INVALID_ARG, "%s: keep_budget %d must exceed window %d", who, keep_budget, window);
+  return ROCKETKV_OK;
 }
 
 struct DecodePlan {
@@ -384,26 +405,12 @@ int32_t rocketkv_snapkv_compress(const void* q_obs, const rocketkv_cache_t* src,
   const char* who = "rocketkv_snapkv_compress";
   if (int r = check_cache(src, true, who)) return r;
   if (int r = check_cache(dst, true, who)) return r;
-  if (!q_obs) return fail(ROCKETKV_INVALID_ARG, "%s: q_obs must not be NULL", who);
-  if (((uintptr_t)q_obs) & 15) return fail(ROCKETKV_INVALID_ARG, "%s: q_obs must be 16-byte aligned", who);
+  if (int r = check_snapkv_args(q_obs, src, window, pool_kernel, keep_budget, who)) return r;
   if (src->batch != dst->batch || src->n_q_heads != dst->n_q_heads || src->n_kv_heads != dst->n_kv_heads)
     return fail(ROCKETKV_INVALID_ARG, "%s: src and dst must agree on batch and head counts", who);
-  if (src->page_size != kAttnPage)
-    return fail(ROCKETKV_UNSUPPORTED, "%s: src needs page_size %d (got %d)", who, kAttnPage, src->page_size);
   if (dst->v_layout == ROCKETKV_V_CHANNEL_MAJOR && dst->page_size != kAttnPage)
     return fail(ROCKETKV_UNSUPPORTED, "%s: a dst with channel-major V needs page_size %d (got %d)", who,
                 kAttnPage, dst->page_size);
-  if (window < 1 || window > 128 || window % 16 != 0)
-    return fail(window < 1 ? ROCKETKV_INVALID_ARG : ROCKETKV_UNSUPPORTED,
-                "%s: window %d must be a multiple of 16 in [16, 128]", who, window);
-  if ((src->n_q_heads / src->n_kv_heads) * window > 256)
-    return fail(ROCKETKV_UNSUPPORTED, "%s: group size x window (%d) exceeds 256", who,
-                (src->n_q_heads / src->n_kv_heads) * window);
-  if (pool_kernel < 1 || pool_kernel % 2 == 0)
-    return fail(ROCKETKV_INVALID_ARG, "%s: pool_kernel %d must be odd and positive", who, pool_kernel);
-  if (pool_kernel > 1023) return fail(ROCKETKV_UNSUPPORTED, "%s: pool_kernel %d > 1023", who, pool_kernel);
-  if (keep_budget <= window)
-    return fail(ROCKETKV_INVALID_ARG, "%s: keep_budget %d must exceed window %d", who, keep_budget, window);
   if ((int64_t)dst->pages_cap * dst->page_size < keep_budget)
     return fail(ROCKETKV_INVALID_ARG, "%s: dst holds %lld tokens per sequence < keep_budget %d", who,
                 (long long)dst->pages_cap * dst->page_size, keep_budget);
@@ -416,7 +423,7 @@ int32_t rocketkv_snapkv_compress(const void* q_obs, const rocketkv_cache_t* src,
                 workspace ? workspace_bytes : (size_t)0, plan.total_bytes);
   if ((uintptr_t)workspace & 255) return fail(ROCKETKV_INVALID_ARG, "%s: workspace must be 256-byte aligned", who);
   const hipError_t e = launch_snapkv(static_cast<const bf16_t*>(q_obs), sv, window, pool_kernel,
-                                     keep_budget, dv, kept_idx, workspace, plan,
+                                     keep_budget, &dv, kept_idx, keep_budget, dv.seq_lens, workspace, plan,
                                      static_cast<hipStream_t>(stream));
   return e == hipSuccess ? ROCKETKV_OK : hip_fail(e, who);
 }
@@ -444,6 +451,195 @@ int32_t rocketkv_decompose(int64_t seq_len, int32_t token_budget, int32_t head_d
   s.attend_tokens = token_budget / 2 > 1 ? token_budget / 2 : 1;
   *out = s;
   return ROCKETKV_OK;
+}
+
+}  // extern "C"
+
+namespace {
+
+int check_index(const rocketkv_cache_t* c, const rocketkv_index_t* ix, const char* who) {
+  if (!ix) return fail(ROCKETKV_INVALID_ARG, "%s: index is NULL", who);
+  if (!ix->token_index || !ix->n_indexed)
+    return fail(ROCKETKV_INVALID_ARG, "%s: index->token_index / n_indexed must not be NULL", who);
+  if (ix->page_size < 1) return fail(ROCKETKV_INVALID_ARG, "%s: index->page_size must be >= 1", who);
+  if (ix->page_size > 64) return fail(ROCKETKV_UNSUPPORTED, "%s: index->page_size %d > 64", who, ix->page_size);
+  if (ix->pages_cap < 1 || ix->pages_cap % 8 != 0)
+    return fail(ROCKETKV_INVALID_ARG, "%s: index->pages_cap (%d) must be a positive multiple of 8", who,
+                ix->pages_cap);
+  if ((int64_t)ix->pages_cap * ix->page_size > (int64_t)1 << 30)
+    return fail(ROCKETKV_INVALID_ARG, "%s: index->pages_cap * page_size overflows", who);
+  if (c->v_layout != ROCKETKV_V_TOKEN_MAJOR)
+    return fail(ROCKETKV_UNSUPPORTED, "%s: the cache behind an index needs token-major V", who);
+  return ROCKETKV_OK;
+}
+
+LogicalView logical_of(const rocketkv_index_t* ix) {
+  LogicalView lv;
+  lv.token_index = ix->token_index;
+  lv.n_indexed = ix->n_indexed;
+  lv.page_size = ix->page_size;
+  lv.pages_cap = ix->pages_cap;
+  return lv;
+}
+
+// The cache as Step 2 sees it under an index: lengths, page size and page capacity of the logical
+// sequence (the selection never touches the pools).
+rocketkv_cache_t logical_cache(const rocketkv_cache_t* c, const rocketkv_index_t* ix) {
+  rocketkv_cache_t lc = *c;
+  lc.seq_lens = ix->n_indexed;
+  lc.page_size = ix->page_size;
+  lc.pages_cap = ix->pages_cap;
+  return lc;
+}
+
+int mt_decode_impl(const char* who, const rocketkv_cache_t* cache, const rocketkv_index_t* index,
+                   const void* q, const void* k_new, const void* v_new, void* kmax, void* kmin,
+                   int32_t channel_budget, int32_t token_budget, int32_t n_recent_pages, void* out,
+                   float* out_lse, int32_t* out_pages, int32_t* out_channels, void* workspace,
+                   size_t workspace_bytes, void* stream) {
+  if (int r = check_cache(cache, true, who)) return r;
+  if (int r = check_index(cache, index, who)) return r;
+  const rocketkv_cache_t lc = logical_cache(cache, index);
+  if (int r = check_select_args(&lc, q, kmax, kmin, channel_budget, token_budget, n_recent_pages, who)) return r;
+  if (!out) return fail(ROCKETKV_INVALID_ARG, "%s: out must not be NULL", who);
+  const DecodePlan d = plan_decode(&lc, token_budget);
+  if (!workspace || workspace_bytes < d.total)
+    return fail(ROCKETKV_WORKSPACE_TOO_SMALL, "%s: workspace %zu bytes < %zu needed", who,
+                workspace ? workspace_bytes : (size_t)0, d.total);
+  if ((uintptr_t)workspace & 255) return fail(ROCKETKV_INVALID_ARG, "%s: workspace must be 256-byte aligned", who);
+  const CacheView v = view_of(cache), lcv = view_of(&lc);
+  const LogicalView lv = logical_of(index);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+  hipError_t e;
+  if (k_new) {
+    e = launch_append_indexed(v, lv, static_cast<const bf16_t*>(k_new), static_cast<const bf16_t*>(v_new),
+                              static_cast<bf16_t*>(kmax), static_cast<bf16_t*>(kmin), st);
+    if (e != hipSuccess) return hip_fail(e, who);
+  }
+  SelectArgs a;
+  a.q = static_cast<const bf16_t*>(q);
+  a.kmax = static_cast<const bf16_t*>(kmax);
+  a.kmin = static_cast<const bf16_t*>(kmin);
+  a.k1 = channel_budget;
+  a.T = token_budget;
+  a.n_recent = n_recent_pages;
+  a.out_pages = reinterpret_cast<int32_t*>(ws + d.list_off);
+  a.row_len = d.row_len;
+  a.out_pages2 = out_pages;
+  a.row_len2 = d.row_len;
+  a.out_channels = out_channels;
+  a.out_scores = select_wants_split(lcv, a.k1) ? reinterpret_cast<float*>(ws + d.scores_off) : nullptr;
+  a.in_scores = nullptr;
+  a.zero_counters = nullptr;
+  e = launch_hsa_select(lcv, a, st);
+  if (e != hipSuccess) return hip_fail(e, who);
+  e = launch_attend_tokens(v, a.q, a.out_pages, d.row_len, static_cast<bf16_t*>(out), out_lse,
+                           ws + d.attend_off, d.attend, &lv, st);
+  return e == hipSuccess ? ROCKETKV_OK : hip_fail(e, who);
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t rocketkv_snapkv_filter(const void* q_obs, const rocketkv_cache_t* src, int32_t window,
+                               int32_t pool_kernel, int32_t keep_budget, const rocketkv_index_t* index,
+                               void* workspace, size_t workspace_bytes, void* stream) {
+  g_err[0] = 0;
+  const char* who = "rocketkv_snapkv_filter";
+  if (int r = check_cache(src, true, who)) return r;
+  if (int r = check_snapkv_args(q_obs, src, window, pool_kernel, keep_budget, who)) return r;
+  if (!index || !index->token_index || !index->n_indexed)
+    return fail(ROCKETKV_INVALID_ARG, "%s: index and its arrays must not be NULL", who);
+  if (index->page_size < 1 || index->pages_cap < 1 ||
+      (int64_t)index->pages_cap * index->page_size < keep_budget)
+    return fail(ROCKETKV_INVALID_ARG, "%s: index rows hold %lld entries < keep_budget %d", who,
+                (long long)index->pages_cap * index->page_size, keep_budget);
+  const CacheView sv = view_of(src);
+  const SnapPlan plan = plan_snapkv(sv, window, keep_budget);
+  if (!workspace || workspace_bytes < plan.total_bytes)
+    return fail(ROCKETKV_WORKSPACE_TOO_SMALL, "%s: workspace %zu bytes < %zu needed", who,
+                workspace ? workspace_bytes : (size_t)0, plan.total_bytes);
+  if ((uintptr_t)workspace & 255) return fail(ROCKETKV_INVALID_ARG, "%s: workspace must be 256-byte aligned", who);
+  const hipError_t e = launch_snapkv(static_cast<const bf16_t*>(q_obs), sv, window, pool_kernel, keep_budget,
+                                     nullptr, index->token_index, index->pages_cap * index->page_size,
+                                     index->n_indexed, workspace, plan, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? ROCKETKV_OK : hip_fail(e, who);
+}
+
+int32_t rocketkv_mt_build_page_summaries(const rocketkv_cache_t* cache, const rocketkv_index_t* index,
+                                         void* kmax, void* kmin, int32_t first_page, int32_t n_pages,
+                                         void* stream) {
+  g_err[0] = 0;
+  const char* who = "rocketkv_mt_build_page_summaries";
+  if (int r = check_cache(cache, true, who)) return r;
+  if (int r = check_index(cache, index, who)) return r;
+  if (!kmax || !kmin) return fail(ROCKETKV_INVALID_ARG, "%s: kmax / kmin must not be NULL", who);
+  if (first_page < 0 || first_page > index->pages_cap)
+    return fail(ROCKETKV_INVALID_ARG, "%s: first_page %d outside [0, %d]", who, first_page, index->pages_cap);
+  const hipError_t e = launch_page_summaries_indexed(view_of(cache), logical_of(index),
+                                                     static_cast<bf16_t*>(kmax), static_cast<bf16_t*>(kmin),
+                                                     first_page, n_pages, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? ROCKETKV_OK : hip_fail(e, who);
+}
+
+size_t rocketkv_mt_workspace_bytes(const rocketkv_cache_t* cache, const rocketkv_index_t* index,
+                                   int32_t token_budget) {
+  g_err[0] = 0;
+  const char* who = "rocketkv_mt_workspace_bytes";
+  if (check_cache(cache, false, who)) return 0;
+  if (!index || index->page_size < 1 || index->page_size > 64 || index->pages_cap < 1 || index->pages_cap % 8) {
+    fail(ROCKETKV_INVALID_ARG, "%s: index needs page_size in [1, 64] and pages_cap a positive multiple of 8", who);
+    return 0;
+  }
+  if (token_budget < 1) { fail(ROCKETKV_INVALID_ARG, "%s: token_budget must be >= 1", who); return 0; }
+  rocketkv_cache_t lc = *cache;
+  lc.page_size = index->page_size;
+  lc.pages_cap = index->pages_cap;
+  lc.v_layout = ROCKETKV_V_TOKEN_MAJOR;
+  return plan_decode(&lc, token_budget).total;
+}
+
+int32_t rocketkv_mt_hsa_decode(const rocketkv_cache_t* cache, const rocketkv_index_t* index,
+                               const void* q, const void* kmax, const void* kmin,
+                               int32_t channel_budget, int32_t token_budget, int32_t n_recent_pages,
+                               void* out, float* out_lse, int32_t* out_pages, int32_t* out_channels,
+                               void* workspace, size_t workspace_bytes, void* stream) {
+  g_err[0] = 0;
+  return mt_decode_impl("rocketkv_mt_hsa_decode", cache, index, q, nullptr, nullptr, const_cast<void*>(kmax),
+                        const_cast<void*>(kmin), channel_budget, token_budget, n_recent_pages, out, out_lse,
+                        out_pages, out_channels, workspace, workspace_bytes, stream);
+}
+
+int32_t rocketkv_mt_append_kv(const rocketkv_cache_t* cache, const rocketkv_index_t* index,
+                              const void* k_new, const void* v_new, void* kmax, void* kmin,
+                              void* stream) {
+  g_err[0] = 0;
+  const char* who = "rocketkv_mt_append_kv";
+  if (int r = check_cache(cache, true, who)) return r;
+  if (int r = check_index(cache, index, who)) return r;
+  if (!k_new || !v_new || !kmax || !kmin)
+    return fail(ROCKETKV_INVALID_ARG, "%s: k_new / v_new / kmax / kmin must not be NULL", who);
+  const hipError_t e = launch_append_indexed(view_of(cache), logical_of(index),
+                                             static_cast<const bf16_t*>(k_new), static_cast<const bf16_t*>(v_new),
+                                             static_cast<bf16_t*>(kmax), static_cast<bf16_t*>(kmin),
+                                             static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? ROCKETKV_OK : hip_fail(e, who);
+}
+
+int32_t rocketkv_mt_hsa_decode_append(const rocketkv_cache_t* cache, const rocketkv_index_t* index,
+                                      const void* q, const void* k_new, const void* v_new, void* kmax,
+                                      void* kmin, int32_t channel_budget, int32_t token_budget,
+                                      int32_t n_recent_pages, void* out, float* out_lse,
+                                      int32_t* out_pages, int32_t* out_channels, void* workspace,
+                                      size_t workspace_bytes, void* stream) {
+  g_err[0] = 0;
+  const char* who = "rocketkv_mt_hsa_decode_append";
+  if (!k_new || !v_new) return fail(ROCKETKV_INVALID_ARG, "%s: k_new / v_new must not be NULL", who);
+  return mt_decode_impl(who, cache, index, q, k_new, v_new, kmax, kmin, channel_budget, token_budget,
+                        n_recent_pages, out, out_lse, out_pages, out_channels, workspace, workspace_bytes,
+                        stream);
 }
 
 }  // extern "C"

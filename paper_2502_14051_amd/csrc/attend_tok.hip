@@ -20,6 +20,12 @@ namespace rkv {
 struct TokenRun {
   int ps;      // tokens per list entry
   int tokens;  // list entries x ps: token slots per (sequence, KV head)
+  // RocketKV-MT (Section 3.5): the list addresses pages of a logical sequence, whose token j sits at
+  // position index[unit][j] of the cache; null = the cache's own order
+  const int32_t* index;
+  int index_stride;          // entries per (sequence, KV head) row of `index`
+  const int32_t* n_logical;  // [batch] logical lengths
+  int logical_pages_cap;
 };
 
 // One step over two 16-token tiles.  `row_ok[x]`: this lane's row (token hn of tile x) is real;
@@ -69,7 +75,7 @@ __device__ __forceinline__ void token_round(u32x4 (&kf)[2][4], u32x4 (&vr)[2][4]
   softmax_pv<1>(acc, vf, O, m, l, have_acc, sc);
 }
 
-template <int WAVES>
+template <int WAVES, bool INDEXED>
 __global__ __launch_bounds__(WAVES* kWave) __attribute__((amdgpu_waves_per_eu(2)))
 void attend_tokens_kernel(CacheView c, AttendArgs a, TokenRun t) {
   extern __shared__ float smem[];  // sO[WAVES][G][128], sM[WAVES][G], sL[WAVES][G]
@@ -80,8 +86,9 @@ void attend_tokens_kernel(CacheView c, AttendArgs a, TokenRun t) {
   const int b = unit / c.n_kv_heads, g = unit % c.n_kv_heads;
   const int G = c.group;
   const int ps = t.ps;
-  int n = c.seq_lens[b];
-  if (n > c.pages_cap * ps) n = c.pages_cap * ps;
+  const int cap_pages = INDEXED ? t.logical_pages_cap : c.pages_cap;
+  int n = INDEXED ? t.n_logical[b] : c.seq_lens[b];
+  if (n > cap_pages * ps) n = cap_pages * ps;
   const int32_t* list = a.pages ? a.pages + (int64_t)unit * a.row_len : nullptr;
 
   // this wave's share of the token slots (chunk and per_wave are multiples of 32).  The plan is laid
@@ -126,13 +133,28 @@ void attend_tokens_kernel(CacheView c, AttendArgs a, TokenRun t) {
     const int e = f / ps, slot = f - e * ps;
     int page = -1;
     if (ok) page = list ? list[e] : e;
-    // the row address needs only a page inside the table; the sequence length (possibly still on
-    // its way from memory) enters the mask alone
-    ok = ok && page >= 0 && page < c.pages_cap;
-    const int64_t pp = ok ? phys_page(c, b, page) : -1;
-    ok = ok && pp >= 0;
-    const int64_t off = ok ? pp * c.stride_page + slot * kHeadDim : 0;
-    const unsigned long long live = __ballot(ok && page * ps + slot < n);
+    ok = ok && page >= 0 && page < cap_pages;
+    int64_t off = 0;
+    unsigned long long live;
+    if (INDEXED) {
+      // logical token -> position in the cache -> page and slot of the cache's own paging
+      const int j = page * ps + slot;
+      ok = ok && j < n;
+      const int pos = ok ? t.index[(int64_t)unit * t.index_stride + j] : 0;
+      const int sp = pos / c.page_size, ss = pos - sp * c.page_size;
+      ok = ok && pos >= 0 && sp < c.pages_cap;
+      const int64_t pp = ok ? phys_page(c, b, sp) : -1;
+      ok = ok && pp >= 0;
+      if (ok) off = pp * c.stride_page + ss * kHeadDim;
+      live = __ballot(ok);
+    } else {
+      // the row address needs only a page inside the table; the sequence length (possibly still on
+      // its way from memory) enters the mask alone
+      const int64_t pp = ok ? phys_page(c, b, page) : -1;
+      ok = ok && pp >= 0;
+      if (ok) off = pp * c.stride_page + slot * kHeadDim;
+      live = __ballot(ok && page * ps + slot < n);
+    }
     const int cnt = min(kWave, we - base);
     for (int i = 0; i * 32 < cnt; ++i) {
       u32x4 kf[2][4], vr[2][4];
@@ -169,7 +191,7 @@ void attend_tokens_kernel(CacheView c, AttendArgs a, TokenRun t) {
 
 hipError_t launch_attend_tokens(const CacheView& c, const bf16_t* q, const int32_t* pages, int row_len,
                                 bf16_t* out, float* out_lse, void* ws, const AttendPlan& plan,
-                                hipStream_t st) {
+                                const LogicalView* lv, hipStream_t st) {
   const int units = c.batch * c.n_kv_heads;
   AttendArgs a;
   a.q = q;
@@ -183,14 +205,25 @@ hipError_t launch_attend_tokens(const CacheView& c, const bf16_t* q, const int32
   a.chunk = plan.chunk * kAttnPage;        // the plan counts 16-token entries
   a.per_wave = plan.per_wave * kAttnPage;  // even number of entries: a multiple of 32 slots
   TokenRun t;
-  t.ps = c.page_size;
-  t.tokens = row_len * c.page_size;
+  t.ps = lv ? lv->page_size : c.page_size;
+  t.tokens = row_len * t.ps;
+  t.index = lv ? lv->token_index : nullptr;
+  t.index_stride = lv ? lv->pages_cap * lv->page_size : 0;
+  t.n_logical = lv ? lv->n_indexed : nullptr;
+  t.logical_pages_cap = lv ? lv->pages_cap : 0;
   const size_t smem = (size_t)plan.waves * c.group * (kHeadDim + 2) * sizeof(float);
   const dim3 grid(plan.n_split, units);
-  if (plan.waves == 8)
-    hipLaunchKernelGGL((attend_tokens_kernel<8>), grid, dim3(8 * kWave), smem, st, c, a, t);
-  else
-    hipLaunchKernelGGL((attend_tokens_kernel<4>), grid, dim3(4 * kWave), smem, st, c, a, t);
+  if (plan.waves == 8) {
+    if (lv)
+      hipLaunchKernelGGL((attend_tokens_kernel<8, true>), grid, dim3(8 * kWave), smem, st, c, a, t);
+    else
+      hipLaunchKernelGGL((attend_tokens_kernel<8, false>), grid, dim3(8 * kWave), smem, st, c, a, t);
+  } else {
+    if (lv)
+      hipLaunchKernelGGL((attend_tokens_kernel<4, true>), grid, dim3(4 * kWave), smem, st, c, a, t);
+    else
+      hipLaunchKernelGGL((attend_tokens_kernel<4, false>), grid, dim3(4 * kWave), smem, st, c, a, t);
+  }
   return hipGetLastError();
 }
 

@@ -118,11 +118,23 @@ hipError_t launch_attend(const CacheView& c, const bf16_t* q, const int32_t* pag
                          bf16_t* out, float* out_lse, void* ws, const AttendPlan& plan,
                          hipStream_t st);
 hipError_t launch_zero(void* p, size_t bytes, hipStream_t st);
+// The logical sequence of RocketKV-MT (Section 3.5): token j of (sequence, KV head) u sits at
+// position token_index[u * pages_cap * page_size + j] of the cache.
+struct LogicalView {
+  int32_t* token_index;
+  int32_t* n_indexed;  // [batch]
+  int32_t page_size, pages_cap;
+};
 // Step 3 over token-major caches of any page size; `row_len` counts list entries (pages), the plan
-// comes from plan_attend(c, ceil(row_len * page_size / 16)).
+// comes from plan_attend on the 16-slot entries they add up to.  `lv` (optional): the list addresses
+// pages of that logical sequence.
 hipError_t launch_attend_tokens(const CacheView& c, const bf16_t* q, const int32_t* pages, int row_len,
                                 bf16_t* out, float* out_lse, void* ws, const AttendPlan& plan,
-                                hipStream_t st);
+                                const LogicalView* lv, hipStream_t st);
+hipError_t launch_page_summaries_indexed(const CacheView& c, const LogicalView& lv, bf16_t* kmax,
+                                         bf16_t* kmin, int first_page, int n_pages, hipStream_t st);
+hipError_t launch_append_indexed(const CacheView& c, const LogicalView& lv, const bf16_t* k_new,
+                                 const bf16_t* v_new, bf16_t* kmax, bf16_t* kmin, hipStream_t st);
 // Step 2 + Step 3 in one launch; usable when fused_decode_lds_bytes() fits kMaxLdsBytes
 constexpr size_t kMaxLdsBytes = 64 * 1024;
 size_t fused_decode_lds_bytes(const CacheView& c, int row_len, const AttendPlan& plan);
@@ -146,8 +158,9 @@ struct SnapPlan {
   int chunk_pages;
 };
 SnapPlan plan_snapkv(const CacheView& src, int window, int keep);
+// dst == nullptr: filter only (indices to kept_idx, rows of kept_stride entries; counts to n_out)
 hipError_t launch_snapkv(const bf16_t* q_obs, const CacheView& src, int window, int pool_kernel,
-                         int keep, const CacheView& dst, int32_t* kept_idx, void* ws,
-                         const SnapPlan& plan, hipStream_t st);
+                         int keep, const CacheView* dst, int32_t* kept_idx, int kept_stride,
+                         int32_t* n_out, void* ws, const SnapPlan& plan, hipStream_t st);
 
 }  // namespace rkv

@@ -37,6 +37,9 @@ struct SnapArgs {
   float* votes;       // [units][s_cap]
   float* pooled;      // [units][s_cap]
   int32_t* kept;      // [units][keep]
+  int32_t* kept_user; // optional copy for the caller, rows of kept_stride entries
+  int kept_stride;
+  int32_t* n_out;     // [batch]: number of tokens kept per sequence
 };
 
 __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -283,8 +286,7 @@ __device__ __forceinline__ uint32_t order_key(float f) {
 
 // exact top-(keep-W) of pooled[0, L) + the window, ascending; one 1024-thread workgroup per unit
 constexpr int kSelT = 1024;
-__global__ __launch_bounds__(kSelT) void snap_select_kernel(CacheView c, SnapArgs a, CacheView dst,
-                                                           int32_t* kept_user) {
+__global__ __launch_bounds__(kSelT) void snap_select_kernel(CacheView c, SnapArgs a) {
   __shared__ uint32_t hist[256];
   __shared__ uint32_t wsum[kSelT / kWave];
   __shared__ uint32_t sh_bucket, sh_k;
@@ -293,7 +295,7 @@ __global__ __launch_bounds__(kSelT) void snap_select_kernel(CacheView c, SnapArg
   const int b = unit / c.n_kv_heads, g = unit % c.n_kv_heads;
   const int S = c.seq_lens[b];
   int32_t* kept = a.kept + (int64_t)unit * a.keep;
-  int32_t* kept2 = kept_user ? kept_user + (int64_t)unit * a.keep : nullptr;
+  int32_t* kept2 = a.kept_user ? a.kept_user + (int64_t)unit * a.kept_stride : nullptr;
   const bool small = S <= a.keep;
   const bool bad = S > c.pages_cap * kAttnPage;
   if (small || bad) {
@@ -303,7 +305,7 @@ __global__ __launch_bounds__(kSelT) void snap_select_kernel(CacheView c, SnapArg
       kept[i] = v;
       if (kept2) kept2[i] = v;
     }
-    if (g == 0 && tid == 0) dst.seq_lens[b] = cnt;
+    if (g == 0 && tid == 0) a.n_out[b] = cnt;
     return;
   }
   const int L = S - a.W;
@@ -407,7 +409,7 @@ __global__ __launch_bounds__(kSelT) void snap_select_kernel(CacheView c, SnapArg
     kept[k_pref + w] = L + w;
     if (kept2) kept2[k_pref + w] = L + w;
   }
-  if (g == 0 && tid == 0) dst.seq_lens[b] = a.keep;
+  if (g == 0 && tid == 0) a.n_out[b] = a.keep;
 }
 
 // copy the kept tokens into the destination cache; one workgroup per 16 kept tokens.  K rows move
@@ -524,8 +526,8 @@ SnapPlan plan_snapkv(const CacheView& src, int window, int keep) {
 }
 
 hipError_t launch_snapkv(const bf16_t* q_obs, const CacheView& src, int window, int pool_kernel,
-                         int keep, const CacheView& dst, int32_t* kept_idx, void* ws,
-                         const SnapPlan& plan, hipStream_t st) {
+                         int keep, const CacheView* dst, int32_t* kept_idx, int kept_stride,
+                         int32_t* n_out, void* ws, const SnapPlan& plan, hipStream_t st) {
   const int units = src.batch * src.n_kv_heads;
   char* base = static_cast<char*>(ws);
   auto up = [](size_t x) { return (x + 255) / 256 * 256; };
@@ -545,6 +547,9 @@ hipError_t launch_snapkv(const bf16_t* q_obs, const CacheView& src, int window, 
   a.votes = reinterpret_cast<float*>(base + plan.votes_off);
   a.pooled = reinterpret_cast<float*>(base + plan.pooled_off);
   a.kept = reinterpret_cast<int32_t*>(base + plan.kept_off);
+  a.kept_user = kept_idx;
+  a.kept_stride = kept_stride;
+  a.n_out = n_out;
 
   const dim3 sgrid(plan.n_chunks, units);
   hipLaunchKernelGGL(snap_score_kernel<false>, sgrid, dim3(256), 0, st, src, a);
@@ -553,9 +558,10 @@ hipError_t launch_snapkv(const bf16_t* q_obs, const CacheView& src, int window, 
   const dim3 pgrid((a.s_cap + kPoolTile - 1) / kPoolTile, units);
   hipLaunchKernelGGL(snap_pool_kernel, pgrid, dim3(256), (kPoolTile + 2 * a.pool_r) * sizeof(float), st,
                      src, a);
-  hipLaunchKernelGGL(snap_select_kernel, dim3(units), dim3(kSelT), 0, st, src, a, dst, kept_idx);
+  hipLaunchKernelGGL(snap_select_kernel, dim3(units), dim3(kSelT), 0, st, src, a);
+  if (!dst) return hipGetLastError();  // filter only: the indices are the result
   const dim3 ggrid((keep + kAttnPage - 1) / kAttnPage, units);
-  hipLaunchKernelGGL(snap_gather_kernel, ggrid, dim3(256), 0, st, src, dst, a);
+  hipLaunchKernelGGL(snap_gather_kernel, ggrid, dim3(256), 0, st, src, *dst, a);
   return hipGetLastError();
 }
 

@@ -25,6 +25,8 @@ EXPORTS = [
     "rocketkv_workspace_bytes", "rocketkv_workspace_init", "rocketkv_build_page_summaries", "rocketkv_hsa_select",
     "rocketkv_attend", "rocketkv_hsa_decode", "rocketkv_hsa_decode_append", "rocketkv_dense_decode", "rocketkv_append_kv",
     "rocketkv_snapkv_compress", "rocketkv_decompose", "rocketkv_last_error", "rocketkv_version",
+    "rocketkv_snapkv_filter", "rocketkv_mt_build_page_summaries", "rocketkv_mt_workspace_bytes", "rocketkv_mt_hsa_decode",
+    "rocketkv_mt_append_kv", "rocketkv_mt_hsa_decode_append",
 ]
 
 
@@ -43,6 +45,12 @@ class CacheStruct(C.Structure):
         ("seq_lens", C.c_void_p), ("block_table", C.c_void_p),
         ("k_pool", C.c_void_p), ("v_pool", C.c_void_p), ("v_layout", C.c_int32),
     ]
+
+
+class IndexStruct(C.Structure):
+    """Mirror of ``rocketkv_index_t``."""
+    _fields_ = [("token_index", C.c_void_p), ("n_indexed", C.c_void_p), ("page_size", C.c_int32),
+                ("pages_cap", C.c_int32)]
 
 
 class SplitStruct(C.Structure):
@@ -90,6 +98,19 @@ def lib():
         L.rocketkv_append_kv.argtypes = [cp, vp, vp, vp, vp, vp]
         L.rocketkv_snapkv_compress.restype = i32
         L.rocketkv_snapkv_compress.argtypes = [vp, cp, i32, i32, i32, cp, vp, vp, sz, vp]
+        ip = C.POINTER(IndexStruct)
+        L.rocketkv_snapkv_filter.restype = i32
+        L.rocketkv_snapkv_filter.argtypes = [vp, cp, i32, i32, i32, ip, vp, sz, vp]
+        L.rocketkv_mt_build_page_summaries.restype = i32
+        L.rocketkv_mt_build_page_summaries.argtypes = [cp, ip, vp, vp, i32, i32, vp]
+        L.rocketkv_mt_workspace_bytes.restype = sz
+        L.rocketkv_mt_workspace_bytes.argtypes = [cp, ip, i32]
+        L.rocketkv_mt_hsa_decode.restype = i32
+        L.rocketkv_mt_hsa_decode.argtypes = [cp, ip, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+        L.rocketkv_mt_append_kv.restype = i32
+        L.rocketkv_mt_append_kv.argtypes = [cp, ip, vp, vp, vp, vp, vp]
+        L.rocketkv_mt_hsa_decode_append.restype = i32
+        L.rocketkv_mt_hsa_decode_append.argtypes = [cp, ip, vp, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
         L.rocketkv_decompose.restype = i32
         L.rocketkv_decompose.argtypes = [C.c_int64, i32, i32, C.POINTER(SplitStruct)]
         L.rocketkv_last_error.restype = C.c_char_p
@@ -314,6 +335,85 @@ def snapkv_compress(q_obs, src: Cache, window: int, pool_kernel: int, keep_budge
     _check(lib().rocketkv_snapkv_compress(_ptr(q_obs), C.byref(s), window, pool_kernel, keep_budget,
                                           C.byref(d), _ptr(kept_idx), _ptr(workspace),
                                           workspace.numel(), _stream(stream)))
+
+
+@dataclass
+class Index:
+    """The logical sequence of RocketKV-MT in torch tensors, plus its C descriptor.
+
+    token_index: int32 [batch][n_kv_heads][pages_cap * page_size]; n_indexed: int32 [batch]."""
+    token_index: object
+    n_indexed: object
+    page_size: int
+    pages_cap: int
+
+    def struct(self) -> IndexStruct:
+        return IndexStruct(_ptr(self.token_index), _ptr(self.n_indexed), self.page_size, self.pages_cap)
+
+
+def alloc_index(cache: Cache, page_size: int, capacity_tokens: int) -> Index:
+    import torch
+    pages_cap = ((capacity_tokens + page_size - 1) // page_size + 7) // 8 * 8
+    dev = cache.k_pool.device
+    return Index(torch.full((cache.batch, cache.n_kv_heads, pages_cap * page_size), -1, dtype=torch.int32, device=dev),
+                 torch.zeros((cache.batch,), dtype=torch.int32, device=dev), page_size, pages_cap)
+
+
+def alloc_index_summaries(cache: Cache, index: Index):
+    import torch
+    shape = (cache.batch, cache.n_kv_heads, cache.head_dim, index.pages_cap)
+    return (torch.zeros(shape, dtype=torch.bfloat16, device=cache.k_pool.device),
+            torch.zeros(shape, dtype=torch.bfloat16, device=cache.k_pool.device))
+
+
+def snapkv_filter(q_obs, src: Cache, window: int, pool_kernel: int, keep_budget: int, index: Index,
+                  workspace, stream=None):
+    st, ix = src.struct(), index.struct()
+    _check(lib().rocketkv_snapkv_filter(_ptr(q_obs), C.byref(st), window, pool_kernel, keep_budget, C.byref(ix),
+                                        _ptr(workspace), workspace.numel(), _stream(stream)))
+
+
+def mt_build_page_summaries(cache: Cache, index: Index, kmax, kmin, first_page: int = 0, n_pages: int = -1,
+                            stream=None):
+    st, ix = cache.struct(), index.struct()
+    _check(lib().rocketkv_mt_build_page_summaries(C.byref(st), C.byref(ix), _ptr(kmax), _ptr(kmin), first_page,
+                                                  n_pages, _stream(stream)))
+
+
+def mt_alloc_workspace(cache: Cache, index: Index, token_budget: int, stream=None):
+    import torch
+    st, ix = cache.struct(), index.struct()
+    n = lib().rocketkv_mt_workspace_bytes(C.byref(st), C.byref(ix), token_budget)
+    if n == 0:
+        raise RocketKVError(INVALID_ARG, last_error())
+    ws = torch.empty((max(int(n), 256),), dtype=torch.uint8, device=cache.k_pool.device)
+    workspace_init(ws, stream)
+    return ws
+
+
+def mt_hsa_decode(cache: Cache, index: Index, q, kmax, kmin, channel_budget: int, token_budget: int,
+                  n_recent_pages: int, out, out_lse, out_pages, out_channels, workspace, stream=None):
+    st, ix = cache.struct(), index.struct()
+    _check(lib().rocketkv_mt_hsa_decode(C.byref(st), C.byref(ix), _ptr(q), _ptr(kmax), _ptr(kmin), channel_budget,
+                                        token_budget, n_recent_pages, _ptr(out), _ptr(out_lse), _ptr(out_pages),
+                                        _ptr(out_channels), _ptr(workspace), workspace.numel(), _stream(stream)))
+
+
+def mt_append_kv(cache: Cache, index: Index, k_new, v_new, kmax, kmin, stream=None):
+    st, ix = cache.struct(), index.struct()
+    _check(lib().rocketkv_mt_append_kv(C.byref(st), C.byref(ix), _ptr(k_new), _ptr(v_new), _ptr(kmax), _ptr(kmin),
+                                       _stream(stream)))
+
+
+def mt_hsa_decode_append(cache: Cache, index: Index, q, k_new, v_new, kmax, kmin, channel_budget: int,
+                         token_budget: int, n_recent_pages: int, out, out_lse, out_pages, out_channels,
+                         workspace, stream=None):
+    st, ix = cache.struct(), index.struct()
+    _check(lib().rocketkv_mt_hsa_decode_append(C.byref(st), C.byref(ix), _ptr(q), _ptr(k_new), _ptr(v_new),
+                                               _ptr(kmax), _ptr(kmin), channel_budget, token_budget,
+                                               n_recent_pages, _ptr(out), _ptr(out_lse), _ptr(out_pages),
+                                               _ptr(out_channels), _ptr(workspace), workspace.numel(),
+                                               _stream(stream)))
 
 
 def decompose(seq_len: int, token_budget: int, head_dim: int = 128) -> dict:

@@ -166,3 +166,24 @@ def test_layout_field_is_validated(L):
     # token-major caches may have any page size up to 64; channel-major attention needs 16
     tm = fake_cache(page_size=3, stride_page=8 * 3 * 128, stride_head=3 * 128, v_layout=rk.V_TOKEN_MAJOR)
     assert L.rocketkv_workspace_bytes(rk.OP_HSA_DECODE, C.byref(tm), 256, 0) > 0
+
+
+def test_multi_turn_argument_checks(L):
+    tm = fake_cache(v_layout=rk.V_TOKEN_MAJOR)
+    ix = rk.IndexStruct(0x3000, 0x4000, 4, 256)
+    assert L.rocketkv_mt_workspace_bytes(C.byref(tm), C.byref(ix), 512) > 0
+    assert L.rocketkv_mt_workspace_bytes(C.byref(tm), C.byref(ix), 0) == 0
+    bad = rk.IndexStruct(0x3000, 0x4000, 4, 250)  # pages_cap not a multiple of 8
+    assert L.rocketkv_mt_workspace_bytes(C.byref(tm), C.byref(bad), 512) == 0
+    # the cache behind an index must be token-major; rejected before anything is launched
+    cm = fake_cache()
+    r = L.rocketkv_mt_build_page_summaries(C.byref(cm), C.byref(ix), 0x5000, 0x6000, 0, -1, None)
+    assert r == rk.UNSUPPORTED and "token-major" in rk.last_error()
+    r = L.rocketkv_mt_append_kv(C.byref(tm), None, 0x5000, 0x6000, 0x7000, 0x8000, None)
+    assert r == rk.INVALID_ARG
+    r = L.rocketkv_mt_hsa_decode(C.byref(tm), C.byref(ix), 0x5000, 0x6000, 0x7000, 32, 512, 0, None, None, None,
+                                 None, 0x10000, 1 << 30, None)
+    assert r == rk.INVALID_ARG and "out" in rk.last_error()
+    small_ix = rk.IndexStruct(0x3000, 0x4000, 4, 8)  # 32 entries per row < keep budget
+    r = L.rocketkv_snapkv_filter(0x5000, C.byref(tm), 32, 63, 1024, C.byref(small_ix), 0x10000, 1 << 30, None)
+    assert r == rk.INVALID_ARG and "keep_budget" in rk.last_error()
