@@ -193,3 +193,61 @@ def test_long_decode_after_snapkv(env, oracle):
     valid = ~np.isnan(want_max)
     assert np.array_equal(wl.bf16_bits_to_f64(wl.to_bits(kmax))[valid], want_max[valid])
     assert np.array_equal(wl.bf16_bits_to_f64(wl.to_bits(kmin))[valid], want_min[valid])
+
+
+def test_decomposed_point_full_shape_sampled(env, oracle):
+    """The benchmark's secondary measurement at full shape: the split of Section 3.6 for t = 2048 of a
+    32768-token context (pages of 3, 81 channels), SnapKV into a token-major cache, then decode steps
+    with append through the score / pick / token-attention launches; sampled units against the oracle."""
+    torch, rk, dev = env
+    w = wl.CONFIGS["llama8b_step_b16"]
+    B, Hq, Hkv, G, W = w.batch, w.n_q_heads, w.n_kv_heads, w.group, w.window
+    sp = rk.decompose(w.context, 2 * w.token_budget, 128)
+    ps, k1, T, N = sp["page_size"], sp["channel_budget"], sp["attend_tokens"], sp["keep_budget"]
+    say("decomposed full-size", sp)
+    d = wl.generate_device(w, 0, dev, with_obs=True)
+    src = rk.pack_cache(d["K"], d["V"], d["seq_lens"].cpu().numpy(), Hq, 16)
+    steps = 3
+    dst = rk.alloc_cache(B, Hq, Hkv, 128, ps, (N + 16 + ps - 1) // ps, dev, zero=True, v_layout=rk.V_TOKEN_MAJOR)
+    kept = torch.empty((B, Hkv, N), dtype=torch.int32, device=dev)
+    ws = rk.alloc_workspace(rk.OP_SNAPKV, src, W, N)
+    rk.snapkv_compress(d["qobs"], src, W, w.pool_kernel, N, dst, kept, ws)
+    kmax, kmin = rk.alloc_summaries(dst)
+    rk.build_page_summaries(dst, kmax, kmin)
+    q = d["q"].contiguous()
+    out = torch.empty((B, Hq, 128), dtype=torch.bfloat16, device=dev)
+    row_len = rk.pages_row_len(dst, T)
+    pages = torch.empty((B, Hkv, row_len), dtype=torch.int32, device=dev)
+    wsd = rk.alloc_workspace(rk.OP_HSA_DECODE, dst, T)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(6)
+    new_k, new_v = [], []
+    for s in range(steps):
+        nk = torch.randn((B, Hkv, 128), generator=gen, device=dev).bfloat16()
+        nv = torch.randn((B, Hkv, 128), generator=gen, device=dev).bfloat16()
+        new_k.append(nk)
+        new_v.append(nv)
+        rk.hsa_decode_append(dst, q, nk, nv, kmax, kmin, k1, T, 0, out, None, pages, None, wsd)
+    torch.cuda.synchronize()
+    n = N + steps
+    assert dst.seq_lens.cpu().numpy().tolist() == [n] * B
+    gp = pages.cpu().numpy()
+    out_bits = wl.to_bits(out)
+    kept_h = kept.cpu().numpy()
+    Kc, Vc = rk.unpack_cache(dst)
+    P = (n + ps - 1) // ps
+    for (b, g) in [(0, 0), (5, 3), (15, 7)]:
+        row = kept_h[b, g]
+        Ku = np.concatenate([wl.to_bits(d["K"][b, g])[row]] + [wl.to_bits(t[b, g])[None] for t in new_k])
+        Vu = np.concatenate([wl.to_bits(d["V"][b, g])[row]] + [wl.to_bits(t[b, g])[None] for t in new_v])
+        assert np.array_equal(wl.to_bits(Kc[b, g, :n]), Ku)  # compacted rows and appended rows
+        assert np.array_equal(wl.to_bits(Vc[b, g, :n]), Vu)
+        qu = wl.to_bits(q[b, g * G:(g + 1) * G])
+        ref = oracle.hsa_decode(qu[None], Ku[None, None], Vu[None, None], [n], ps, k1, T, want_scores=True)
+        kp = oracle.pages_to_pick(n, ps, T)
+        assert_topk_within_band(ref["scores"][0, 0, :P], gp[b, g], kp, f"pages b{b} g{g}")
+        y, _ = oracle.attend_pages(qu, Ku, Vu, ps, gp[b, g][gp[b, g] >= 0])
+        assert_attention_close(out_bits[b, g * G:(g + 1) * G], y, f"y b{b} g{g}")
+        want_max, want_min = oracle.page_summaries(Ku, ps)
+        assert np.array_equal(wl.bf16_bits_to_f64(wl.to_bits(kmax[b, g, :, :P])), want_max)
+        assert np.array_equal(wl.bf16_bits_to_f64(wl.to_bits(kmin[b, g, :, :P])), want_min)
