@@ -342,16 +342,22 @@ int decode_impl(const char* who, const rocketkv_cache_t* cache, const void* q, c
     e = launch_hsa_decode_fused(v, a, ap, static_cast<bf16_t*>(out), out_lse, ws + d.attend_off, d.attend, st);
     return e == hipSuccess ? ROCKETKV_OK : hip_fail(e, who);
   }
-  if (k_new) {
-    e = launch_append(v, ap.k_new, ap.v_new, ap.kmax, ap.kmin, st);
-    if (e != hipSuccess) return hip_fail(e, who);
-  }
   a.out_pages = reinterpret_cast<int32_t*>(ws + d.list_off);
   a.out_pages2 = out_pages;
   a.row_len2 = d.row_len;
-  a.zero_counters = d.attend.n_split > 1 ? attend_counters(ws + d.attend_off, d.attend) : nullptr;
-  if (select_wants_split(v, a.k1)) a.out_scores = reinterpret_cast<float*>(ws + d.scores_off);
-  e = launch_hsa_select(v, a, st);
+  a.zero_counters = nullptr;
+  if (select_wants_split(v, a.k1)) {
+    // score launch (which also takes in the new token) + top-k launch
+    a.out_scores = reinterpret_cast<float*>(ws + d.scores_off);
+    e = launch_hsa_select_split(v, a, ap, attend_counters(ws + d.attend_off, d.attend),
+                                decode_seq_counters(ws + d.attend_off, d.attend), st);
+  } else {
+    if (k_new) {
+      e = launch_append(v, ap.k_new, ap.v_new, ap.kmax, ap.kmin, st);
+      if (e != hipSuccess) return hip_fail(e, who);
+    }
+    e = launch_hsa_select(v, a, st);
+  }
   if (e != hipSuccess) return hip_fail(e, who);
   e = launch_attend_any(v, a.q, a.out_pages, d.row_len, static_cast<bf16_t*>(out), out_lse,
                         ws + d.attend_off, d.attend, st);

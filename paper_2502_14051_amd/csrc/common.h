@@ -144,6 +144,12 @@ struct AppendArgs {      // all null: plain decode
   bf16_t* kmax;          // writable views of the summaries
   bf16_t* kmin;
 };
+// The large-summary path of Step 2 (a.out_scores must be set); with ap.k_new it also takes in the
+// generated token, using `unit_counters` ([units]) and `seq_counters` ([batch], both zero on entry and
+// on exit) for the length update.
+hipError_t launch_hsa_select_split(const CacheView& c, const SelectArgs& a, const AppendArgs& ap,
+                                   uint32_t* unit_counters, uint32_t* seq_counters, hipStream_t st);
+uint32_t* decode_seq_counters(void* ws, const AttendPlan& plan);
 hipError_t launch_hsa_decode_fused(const CacheView& c, const SelectArgs& sa, const AppendArgs& ap,
                                    bf16_t* out, float* out_lse, void* ws, const AttendPlan& plan,
                                    hipStream_t st);

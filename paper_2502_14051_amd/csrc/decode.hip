@@ -117,6 +117,10 @@ size_t fused_decode_lds_bytes(const CacheView& c, int row_len, const AttendPlan&
   return kStageBytes + round16((size_t)row_len * sizeof(int32_t)) + (sel > mrg ? sel : mrg);
 }
 
+uint32_t* decode_seq_counters(void* ws, const AttendPlan& plan) {
+  return reinterpret_cast<uint32_t*>(static_cast<char*>(ws) + plan.counter_off + kSeqCounterOff);
+}
+
 hipError_t launch_hsa_decode_fused(const CacheView& c, const SelectArgs& sa, const AppendArgs& ap,
                                    bf16_t* out, float* out_lse, void* ws, const AttendPlan& plan,
                                    hipStream_t st) {
@@ -131,7 +135,7 @@ hipError_t launch_hsa_decode_fused(const CacheView& c, const SelectArgs& sa, con
   a.n_split = plan.n_split;
   a.chunk = plan.chunk;
   a.per_wave = plan.per_wave;
-  uint32_t* seq_counters = reinterpret_cast<uint32_t*>(static_cast<char*>(ws) + plan.counter_off + kSeqCounterOff);
+  uint32_t* seq_counters = decode_seq_counters(ws, plan);
   const size_t smem = fused_decode_lds_bytes(c, sa.row_len, plan);
   const dim3 grid(c.batch * c.n_kv_heads, plan.n_split);
   const bool append = ap.k_new != nullptr;

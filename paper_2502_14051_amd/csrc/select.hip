@@ -21,16 +21,87 @@ __global__ __launch_bounds__(kSelThreads) void hsa_select_kernel(CacheView c, Se
 
 constexpr int kScoreRuns = 64;  // eight-page runs per workgroup of the split score launch
 
-__global__ __launch_bounds__(kSelThreads) void hsa_score_kernel(CacheView c, SelectArgs a) {
+// APPEND: the launch also takes in the token generated at this step (Section 3.4 Step 1, last
+// sentence).  Every workgroup reads the old length once, scores with the new key folded into the tail
+// page's bound from an LDS copy (so it does not matter whether the write-back has landed), and reports
+// its read to the sequence's counter; workgroup 0 of each (sequence, KV head) writes the key row, the
+// value row or column and the summary column; the workgroup that finds every other one of the
+// sequence has reported stores the new length, so that no reader of this launch sees it change.
+// unit_counters ([units]) and seq_counters ([batch]) are zero on entry and on exit.
+template <bool APPEND>
+__global__ __launch_bounds__(kSelThreads) void hsa_score_kernel(CacheView c, SelectArgs a, AppendArgs ap,
+                                                                uint32_t* unit_counters,
+                                                                uint32_t* seq_counters) {
   __shared__ SelectShared<kSelThreads> sh;
+  __shared__ int s_n0;
+  __shared__ bf16_t s_knew[kHeadDim];
+  const int tid = threadIdx.x;
   const int unit = blockIdx.y;
-  const int n = c.seq_lens[unit / c.n_kv_heads];  // not needed until the channels are picked
-  select_channels<kSelThreads>(c, a, unit, sh, blockIdx.x == 0);
+  const int b = unit / c.n_kv_heads, g = unit % c.n_kv_heads;
+  int n = 0;
+  bf16_t kb = 0, vb = 0;
+  if (!APPEND) {
+    n = c.seq_lens[b];  // not needed until the channels are picked
+  } else {
+    if (tid == 0) s_n0 = c.seq_lens[b];
+    if (tid < kHeadDim) {
+      kb = ap.k_new[(int64_t)unit * kHeadDim + tid];
+      if (blockIdx.x == 0) vb = ap.v_new[(int64_t)unit * kHeadDim + tid];
+      s_knew[tid] = kb;
+    }
+  }
+  select_channels<kSelThreads>(c, a, unit, sh, blockIdx.x == 0);  // its barriers publish s_n0 / s_knew
+  TailPatch tp = {-1, 0, s_knew, nullptr};
+  bool room = false;
+  if (APPEND) {
+    n = s_n0;
+    room = n < c.pages_cap * c.page_size;
+    if (room) {
+      tp.page = n / c.page_size;
+      tp.slot = n % c.page_size;
+      n += 1;
+    }
+  }
+  // the summary column the new key goes into: fetched beside the row loads, stored at the end
+  const bool writer = APPEND && room && blockIdx.x == 0 && tid < kHeadDim;
+  const int64_t sum_off = ((int64_t)unit * kHeadDim + (tid & (kHeadDim - 1))) * c.pages_cap + (room ? tp.page : 0);
+  bf16_t old_max = 0, old_min = 0;
+  if (writer && tp.slot != 0) {
+    old_max = ap.kmax[sum_off];
+    old_min = ap.kmin[sum_off];
+  }
   int P = (n + c.page_size - 1) / c.page_size;
   if (P > c.pages_cap) P = c.pages_cap;
   const int o_begin = blockIdx.x * kScoreRuns;
   const int n_runs = min(kScoreRuns, (P + 7) / 8 - o_begin);
-  if (n_runs > 0) score_chunk<kSelThreads>(c, a, unit, P, sh, o_begin, n_runs, a.out_scores + (int64_t)unit * c.pages_cap);
+  if (n_runs > 0)
+    score_chunk<kSelThreads>(c, a, unit, P, sh, o_begin, n_runs, a.out_scores + (int64_t)unit * c.pages_cap, tp);
+  if (APPEND) {
+    if (writer) {
+      const int64_t pp = phys_page(c, b, tp.page);
+      if (pp >= 0) {
+        const int64_t base = pp * c.stride_page + (int64_t)g * c.stride_head;
+        c.k_pool[base + tp.slot * kHeadDim + tid] = kb;
+        c.v_pool[base + (c.v_token_major ? tp.slot * kHeadDim + tid : tid * c.page_size + tp.slot)] = vb;
+      }
+      const float x = bf16_to_f32(kb);
+      if (tp.slot == 0 || x > bf16_to_f32(old_max)) ap.kmax[sum_off] = kb;
+      if (tp.slot == 0 || x < bf16_to_f32(old_min)) ap.kmin[sum_off] = kb;
+    }
+    if (tid == 0) {
+      // two levels, so that no counter sees more than a handful of arrivals: the workgroups of a
+      // (sequence, KV head) meet at its counter, the last of them goes on to the sequence's
+      if (__hip_atomic_fetch_add(&unit_counters[unit], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+          gridDim.x - 1u) {
+        __hip_atomic_store(&unit_counters[unit], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (__hip_atomic_fetch_add(&seq_counters[b], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+            (uint32_t)c.n_kv_heads - 1u) {
+          if (room) c.seq_lens[b] = n;
+          __hip_atomic_store(&seq_counters[b], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+      }
+    }
+  }
 }
 
 // one workgroup per (sequence, KV head) and a whole compute unit's worth of threads for it: the pick is
@@ -54,16 +125,29 @@ hipError_t launch_hsa_select(const CacheView& c, const SelectArgs& a, hipStream_
   const size_t smem = (size_t)((c.pages_cap + 7) / 8 * 8) * sizeof(uint32_t);
   const int units = c.batch * c.n_kv_heads;
   if (a.out_scores && select_wants_split(c, a.k1)) {
-    const int chunks = ((c.pages_cap + 7) / 8 + kScoreRuns - 1) / kScoreRuns;
-    hipLaunchKernelGGL(hsa_score_kernel, dim3(chunks, units), dim3(kSelThreads), 0, st, c, a);
-    SelectArgs b = a;
-    b.in_scores = a.out_scores;
-    b.out_channels = nullptr;  // written by the score launch
-    b.zero_counters = nullptr;
-    hipLaunchKernelGGL(hsa_pick_kernel, dim3(units), dim3(kPickThreads), smem, st, c, b);
-    return hipGetLastError();
+    const AppendArgs none = {nullptr, nullptr, nullptr, nullptr};
+    return launch_hsa_select_split(c, a, none, nullptr, nullptr, st);
   }
   hipLaunchKernelGGL(hsa_select_kernel, dim3(units), dim3(kSelThreads), smem, st, c, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_hsa_select_split(const CacheView& c, const SelectArgs& a, const AppendArgs& ap,
+                                   uint32_t* unit_counters, uint32_t* seq_counters, hipStream_t st) {
+  const size_t smem = (size_t)((c.pages_cap + 7) / 8 * 8) * sizeof(uint32_t);
+  const int units = c.batch * c.n_kv_heads;
+  const int chunks = ((c.pages_cap + 7) / 8 + kScoreRuns - 1) / kScoreRuns;
+  if (ap.k_new)
+    hipLaunchKernelGGL(hsa_score_kernel<true>, dim3(chunks, units), dim3(kSelThreads), 0, st, c, a, ap,
+                       unit_counters, seq_counters);
+  else
+    hipLaunchKernelGGL(hsa_score_kernel<false>, dim3(chunks, units), dim3(kSelThreads), 0, st, c, a, ap,
+                       unit_counters, seq_counters);
+  SelectArgs b = a;
+  b.in_scores = a.out_scores;
+  b.out_channels = nullptr;  // written by the score launch
+  b.zero_counters = nullptr;
+  hipLaunchKernelGGL(hsa_pick_kernel, dim3(units), dim3(kPickThreads), smem, st, c, b);
   return hipGetLastError();
 }
 

@@ -528,9 +528,8 @@ __device__ __forceinline__ void pick_from_scores(const CacheView& c, const Selec
 template <int NT>
 __device__ __forceinline__ void score_chunk(const CacheView& c, const SelectArgs& a, int unit, int P,
                                             SelectShared<NT>& sh, int o_begin, int n_runs,
-                                            float* scores_row) {
+                                            float* scores_row, const TailPatch& tp) {
   const int tid = threadIdx.x;
-  const TailPatch none = {-1, 0, nullptr, nullptr};
   const int64_t rows = (int64_t)unit * kHeadDim;
   int npow = 1;
   while (npow < n_runs) npow <<= 1;
@@ -541,7 +540,7 @@ __device__ __forceinline__ void score_chunk(const CacheView& c, const SelectArgs
   for (int i = 0; i < 8; ++i) acc[i] = 0.f;
   if (o < n_runs)
     for (int j0 = r; j0 < a.k1; j0 += 8 * R)
-      score_rows8(a, sh.s_chan, sh.s_wgt, rows, c.pages_cap, o_begin + o, j0, R, none, acc);
+      score_rows8(a, sh.s_chan, sh.s_wgt, rows, c.pages_cap, o_begin + o, j0, R, tp, acc);
 #pragma unroll
   for (int i = 0; i < 8; ++i) sh.partial[(r * npow + o) * 8 + i] = acc[i];
   __syncthreads();

@@ -188,23 +188,28 @@ def test_layouts_agree_at_page_16(env, oracle):
     assert np.abs(a - b).max() <= 4e-3
 
 
-def test_decode_append_token_major(env, oracle):
-    """A run of decode steps with the new token folded in, pages of three tokens."""
+@pytest.mark.parametrize("ps,k1,T,ctx", [
+    (3, 62, 96, 400),      # small summaries: append launch, one selection launch, attention
+    (2, 128, 96, 1100),    # large summaries: the score launch takes the token in, then top-k, attention
+    (1, 128, 64, 700),     # Exact-TopK setting, every step opens a new page
+])
+def test_decode_append_token_major(env, oracle, ps, k1, T, ctx):
+    """A run of decode steps with the new token folded in, small pages."""
     torch, rk, dev = env
-    ps, k1, T, steps = 3, 62, 96, 20
-    w = small("tiny", batch=2, context=400, page_size=ps, channel_budget=k1, token_budget=T, n_heavy=5)
-    say("decode+append token-major", ps, steps)
-    full = wl.generate(wl.scaled(w, context=400 + steps))
-    lens = np.array([400, 311], dtype=np.int32)
+    steps = 20
+    w = small("tiny", batch=2, context=ctx, page_size=ps, channel_budget=k1, token_budget=T, n_heavy=5)
+    say("decode+append token-major", ps, k1, T, ctx, steps)
+    full = wl.generate(wl.scaled(w, context=ctx + steps))
+    lens = np.array([ctx, ctx - 89], dtype=np.int32)
     d0 = dict(full)
-    d0["K"] = np.ascontiguousarray(full["K"][:, :, :400])
-    d0["V"] = np.ascontiguousarray(full["V"][:, :, :400])
+    d0["K"] = np.ascontiguousarray(full["K"][:, :, :ctx])
+    d0["V"] = np.ascontiguousarray(full["V"][:, :, :ctx])
     d0["seq_lens"] = lens.copy()
-    cache, q = to_device_cache(rk, torch, d0, w.n_q_heads, ps, dev, pages_cap=(400 + steps + ps - 1) // ps,
+    cache, q = to_device_cache(rk, torch, d0, w.n_q_heads, ps, dev, pages_cap=(ctx + steps + ps - 1) // ps,
                                shuffle_rng=np.random.default_rng(70), v_layout=TM)
     kmax, kmin = rk.alloc_summaries(cache)
     rk.build_page_summaries(cache, kmax, kmin)
-    Kref = np.zeros((2, w.n_kv_heads, 400 + steps, 128), dtype=np.uint16)
+    Kref = np.zeros((2, w.n_kv_heads, ctx + steps, 128), dtype=np.uint16)
     Vref = np.zeros_like(Kref)
     for b in range(2):
         Kref[b, :, :lens[b]] = full["K"][b, :, :lens[b]]
@@ -214,7 +219,7 @@ def test_decode_append_token_major(env, oracle):
     pages = torch.empty((2, w.n_kv_heads, row), dtype=torch.int32, device=dev)
     ws = rk.alloc_workspace(rk.OP_HSA_DECODE, cache, T)
     for s in range(steps):
-        kn, vn = full["K"][:, :, 400 + s], full["V"][:, :, 400 + s]
+        kn, vn = full["K"][:, :, ctx + s], full["V"][:, :, ctx + s]
         for b in range(2):
             Kref[b, :, lens[b]] = kn[b]
             Vref[b, :, lens[b]] = vn[b]
