@@ -342,6 +342,16 @@ int decode_impl(const char* who, const rocketkv_cache_t* cache, const void* q, c
     e = launch_hsa_decode_fused(v, a, ap, static_cast<bf16_t*>(out), out_lse, ws + d.attend_off, d.attend, st);
     return e == hipSuccess ? ROCKETKV_OK : hip_fail(e, who);
   }
+  if (v.v_token_major && !select_wants_split(v, a.k1) &&
+      fused_decode_tok_lds_bytes(v, d.row_len, d.attend) + 64 <= kMaxLdsBytes) {
+    a.out_pages = out_pages;
+    a.out_pages2 = nullptr;
+    a.row_len2 = 0;
+    a.zero_counters = nullptr;
+    e = launch_hsa_decode_tok_fused(v, nullptr, a, ap, static_cast<bf16_t*>(out), out_lse, ws + d.attend_off,
+                                    d.attend, st);
+    return e == hipSuccess ? ROCKETKV_OK : hip_fail(e, who);
+  }
   a.out_pages = reinterpret_cast<int32_t*>(ws + d.list_off);
   a.out_pages2 = out_pages;
   a.row_len2 = d.row_len;
@@ -518,11 +528,6 @@ int mt_decode_impl(const char* who, const rocketkv_cache_t* cache, const rocketk
   hipStream_t st = static_cast<hipStream_t>(stream);
   char* ws = static_cast<char*>(workspace);
   hipError_t e;
-  if (k_new) {
-    e = launch_append_indexed(v, lv, static_cast<const bf16_t*>(k_new), static_cast<const bf16_t*>(v_new),
-                              static_cast<bf16_t*>(kmax), static_cast<bf16_t*>(kmin), st);
-    if (e != hipSuccess) return hip_fail(e, who);
-  }
   SelectArgs a;
   a.q = static_cast<const bf16_t*>(q);
   a.kmax = static_cast<const bf16_t*>(kmax);
@@ -530,11 +535,30 @@ int mt_decode_impl(const char* who, const rocketkv_cache_t* cache, const rocketk
   a.k1 = channel_budget;
   a.T = token_budget;
   a.n_recent = n_recent_pages;
-  a.out_pages = reinterpret_cast<int32_t*>(ws + d.list_off);
   a.row_len = d.row_len;
+  a.out_channels = out_channels;
+  if (!select_wants_split(lcv, a.k1) && fused_decode_tok_lds_bytes(lcv, d.row_len, d.attend) + 64 <= kMaxLdsBytes) {
+    // one launch: selection on the logical sequence, attention through the index, append folded in
+    const AppendArgs ap = {static_cast<const bf16_t*>(k_new), static_cast<const bf16_t*>(v_new),
+                           static_cast<bf16_t*>(kmax), static_cast<bf16_t*>(kmin)};
+    a.out_pages = out_pages;
+    a.out_pages2 = nullptr;
+    a.row_len2 = 0;
+    a.out_scores = nullptr;
+    a.in_scores = nullptr;
+    a.zero_counters = nullptr;
+    e = launch_hsa_decode_tok_fused(v, &lv, a, ap, static_cast<bf16_t*>(out), out_lse, ws + d.attend_off,
+                                    d.attend, st);
+    return e == hipSuccess ? ROCKETKV_OK : hip_fail(e, who);
+  }
+  if (k_new) {
+    e = launch_append_indexed(v, lv, static_cast<const bf16_t*>(k_new), static_cast<const bf16_t*>(v_new),
+                              static_cast<bf16_t*>(kmax), static_cast<bf16_t*>(kmin), st);
+    if (e != hipSuccess) return hip_fail(e, who);
+  }
+  a.out_pages = reinterpret_cast<int32_t*>(ws + d.list_off);
   a.out_pages2 = out_pages;
   a.row_len2 = d.row_len;
-  a.out_channels = out_channels;
   a.out_scores = select_wants_split(lcv, a.k1) ? reinterpret_cast<float*>(ws + d.scores_off) : nullptr;
   a.in_scores = nullptr;
   a.zero_counters = nullptr;

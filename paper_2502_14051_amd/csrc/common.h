@@ -98,6 +98,12 @@ struct SelectArgs {
   const float* in_scores; // set by the launcher when the scores come from a separate launch
   uint32_t* zero_counters;  // optional [units]: cleared for the attention kernel that follows
 };
+struct AppendArgs {      // all null: plain decode
+  const bf16_t* k_new;   // [B][Hkv][128]
+  const bf16_t* v_new;
+  bf16_t* kmax;          // writable views of the summaries
+  bf16_t* kmin;
+};
 // One launch when the picked summary rows are small enough for a workgroup per (sequence, KV head);
 // otherwise, and only if a.out_scores gives it somewhere to put the scores, a score launch split over
 // the pages followed by the top-k launch.
@@ -131,6 +137,13 @@ struct LogicalView {
 hipError_t launch_attend_tokens(const CacheView& c, const bf16_t* q, const int32_t* pages, int row_len,
                                 bf16_t* out, float* out_lse, void* ws, const AttendPlan& plan,
                                 const LogicalView* lv, hipStream_t st);
+// Step 2 + Step 3 (+ the token append) in one launch for token-major caches; `lv` (optional): over the
+// logical sequence of RocketKV-MT.  Usable when fused_decode_tok_lds_bytes() fits kMaxLdsBytes and the
+// summaries are not large enough to want the split selection.
+size_t fused_decode_tok_lds_bytes(const CacheView& lc, int row_len, const AttendPlan& plan);
+hipError_t launch_hsa_decode_tok_fused(const CacheView& c, const LogicalView* lv, const SelectArgs& sa,
+                                       const AppendArgs& ap, bf16_t* out, float* out_lse, void* ws,
+                                       const AttendPlan& plan, hipStream_t st);
 hipError_t launch_page_summaries_indexed(const CacheView& c, const LogicalView& lv, bf16_t* kmax,
                                          bf16_t* kmin, int first_page, int n_pages, hipStream_t st);
 hipError_t launch_append_indexed(const CacheView& c, const LogicalView& lv, const bf16_t* k_new,
@@ -138,12 +151,6 @@ hipError_t launch_append_indexed(const CacheView& c, const LogicalView& lv, cons
 // Step 2 + Step 3 in one launch; usable when fused_decode_lds_bytes() fits kMaxLdsBytes
 constexpr size_t kMaxLdsBytes = 64 * 1024;
 size_t fused_decode_lds_bytes(const CacheView& c, int row_len, const AttendPlan& plan);
-struct AppendArgs {      // all null: plain decode
-  const bf16_t* k_new;   // [B][Hkv][128]
-  const bf16_t* v_new;
-  bf16_t* kmax;          // writable views of the summaries
-  bf16_t* kmin;
-};
 // The large-summary path of Step 2 (a.out_scores must be set); with ap.k_new it also takes in the
 // generated token, using `unit_counters` ([units]) and `seq_counters` ([batch], both zero on entry and
 // on exit) for the length update.

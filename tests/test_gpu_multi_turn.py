@@ -80,10 +80,15 @@ def decode_check(env, oracle, rk_objs, w_logical, q_bits, Kfull, Vfull, n_recent
     return Kc, nl
 
 
-@pytest.mark.parametrize("lps,cache_ps,k1,T", [(16, 16, 32, 128), (3, 16, 70, 90), (4, 5, 128, 64)])
-def test_two_turns(env, oracle, lps, cache_ps, k1, T):
+@pytest.mark.parametrize("lps,cache_ps,k1,T,N", [
+    (16, 16, 32, 128, 400),     # one fused launch per step
+    (3, 16, 70, 90, 400),
+    (4, 5, 128, 64, 400),       # cache paged differently from the logical sequence
+    (1, 16, 128, 64, 600),      # large logical summaries: append, score, top-k and attention launches
+])
+def test_two_turns(env, oracle, lps, cache_ps, k1, T, N):
     torch, rk, dev = env
-    B, S1, steps, M2, N, W, ks = 2, 2000, 6, 900, 400, 32, 63
+    B, S1, steps, M2, W, ks = 2, 2000, 6, 900, 32, 63
     S2 = S1 + steps + M2
     say("multi-turn", lps, cache_ps, k1, T)
     # the whole conversation's K/V, with planted tokens that matter to the SECOND turn's queries
