@@ -13,7 +13,9 @@ launch per layer.  Projections, MLPs and
 weights are outside the path and not run.  Inputs are seeded synthetic data resident in HBM; the
 one-time SnapKV stage and the summary build run untimed in set-up, through the same library.
 
-Prints one JSON line (see README for the fields).
+Prints one JSON line: metric / value / unit, the roofline of the dominant kernel, the CPU oracle
+baseline, and secondary measurements (per-stage times, the decomposed operating point, the
+multi-turn variant).
 """
 from __future__ import annotations
 

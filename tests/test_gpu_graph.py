@@ -1,0 +1,115 @@
+"""The decode step replayed from a captured HIP graph (the way bench.py issues it) against the same
+step launched eagerly on a twin cache: every replay must give the eager result bit for bit, with the
+program's own eager work and synchronisations in between."""
+import sys
+
+import numpy as np
+import pytest
+
+from paper_2502_14051_amd import workloads as wl
+from helpers import to_device_cache
+from test_gpu_parity import small
+
+pytestmark = pytest.mark.gpu
+TM = 1
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    from paper_2502_14051_amd import rocketkv as rk
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    rk.lib()
+    return torch, rk, torch.device("cuda:0")
+
+
+def say(*a):
+    print("[case]", *a, flush=True)
+    sys.stdout.flush()
+
+
+CASES = [
+    # name, page size, channels, token budget, context, V layout, multi-turn index
+    ("fused channel-major", 16, 32, 256, 3000, 0, False),
+    ("fused token-major", 4, 40, 200, 1500, TM, False),
+    ("score/pick/attention launches", 2, 128, 96, 1100, TM, False),
+    ("fused multi-turn", 16, 32, 128, 2000, TM, True),
+]
+
+
+@pytest.mark.parametrize("name,ps,k1,T,ctx,layout,mt", CASES)
+def test_graph_replay_equals_eager(env, name, ps, k1, T, ctx, layout, mt):
+    torch, rk, dev = env
+    steps = 6
+    say("graph replay", name)
+    w = small("tiny", batch=2, context=ctx, page_size=ps, channel_budget=k1, token_budget=T, n_heavy=6)
+    d = wl.generate(w, with_obs=mt)
+    d["seq_lens"] = np.array([ctx, ctx - 61], dtype=np.int32)
+    Hq, Hkv = w.n_q_heads, w.n_kv_heads
+
+    def make():
+        cps = 16 if mt else ps
+        cache, _ = to_device_cache(rk, torch, d, Hq, cps, dev, pages_cap=(ctx + steps + 8 + cps - 1) // cps,
+                                   shuffle_rng=np.random.default_rng(3), v_layout=layout)
+        if mt:
+            N = 512
+            index = rk.alloc_index(cache, ps, N + steps + 8)
+            ws_s = rk.alloc_workspace(rk.OP_SNAPKV, cache, 32, N)
+            rk.snapkv_filter(wl.from_bits(d["qobs"], dev), cache, 32, 63, N, index, ws_s)
+            kmax, kmin = rk.alloc_index_summaries(cache, index)
+            rk.mt_build_page_summaries(cache, index, kmax, kmin)
+            ws = rk.mt_alloc_workspace(cache, index, T)
+            row = min(index.pages_cap, (T + ps - 1) // ps)
+        else:
+            index = None
+            kmax, kmin = rk.alloc_summaries(cache)
+            rk.build_page_summaries(cache, kmax, kmin)
+            ws = rk.alloc_workspace(rk.OP_HSA_DECODE, cache, T)
+            row = rk.pages_row_len(cache, T)
+        out = torch.zeros((2, Hq, 128), dtype=torch.bfloat16, device=dev)
+        pages = torch.zeros((2, Hkv, row), dtype=torch.int32, device=dev)
+        return dict(cache=cache, index=index, kmax=kmax, kmin=kmin, ws=ws, out=out, pages=pages)
+
+    A, B = make(), make()
+    q = torch.zeros((2, Hq, 128), dtype=torch.bfloat16, device=dev)
+    kn = torch.zeros((2, Hkv, 128), dtype=torch.bfloat16, device=dev)
+    vn = torch.zeros((2, Hkv, 128), dtype=torch.bfloat16, device=dev)
+
+    def step(S, stream):
+        if mt:
+            rk.mt_hsa_decode_append(S["cache"], S["index"], q, kn, vn, S["kmax"], S["kmin"], k1, T, 1, S["out"], None,
+                                    S["pages"], None, S["ws"], stream)
+        else:
+            rk.hsa_decode_append(S["cache"], q, kn, vn, S["kmax"], S["kmin"], k1, T, 1, S["out"], None, S["pages"],
+                                 None, S["ws"], stream)
+
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step(A, side)
+    torch.cuda.synchronize()
+    # capture does not execute: both twins are still at their initial lengths
+    assert torch.equal(A["cache"].seq_lens, B["cache"].seq_lens)
+    rng = np.random.default_rng(17)
+    for s in range(steps):
+        q.copy_(wl.from_bits(wl.f32_to_bf16_bits(rng.standard_normal((2, Hq, 128)).astype(np.float32)), dev))
+        kn.copy_(wl.from_bits(wl.f32_to_bf16_bits(rng.standard_normal((2, Hkv, 128)).astype(np.float32)), dev))
+        vn.copy_(wl.from_bits(wl.f32_to_bf16_bits(rng.standard_normal((2, Hkv, 128)).astype(np.float32)), dev))
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            graph.replay()
+        side.synchronize()
+        step(B, None)  # eager, on the current stream
+        torch.cuda.synchronize()
+        assert torch.equal(A["out"], B["out"]), f"replay {s}: outputs differ"
+        assert torch.equal(A["pages"], B["pages"]), f"replay {s}: page lists differ"
+        assert torch.equal(A["cache"].seq_lens, B["cache"].seq_lens)
+        assert A["cache"].seq_lens.cpu().numpy().tolist() == [ctx + s + 1, ctx - 61 + s + 1]
+        if mt:
+            assert torch.equal(A["index"].n_indexed, B["index"].n_indexed)
+    assert torch.equal(A["cache"].k_pool, B["cache"].k_pool) and torch.equal(A["cache"].v_pool, B["cache"].v_pool)
+    assert torch.equal(A["kmax"], B["kmax"]) and torch.equal(A["kmin"], B["kmin"])
+    if mt:
+        assert torch.equal(A["index"].token_index, B["index"].token_index)
