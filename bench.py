@@ -330,6 +330,45 @@ def main():
         mt_pt["achieved_GBs"] = round(mt_pt["bytes_per_layer_step"] / (mt_us * 1e-6) / 1e9, 1)
         del ml
 
+    # ------------------------------------------------------------------ one layer, batch 1, uncompressed context
+    # BASELINE configs[1]: a single sequence of 32768 tokens, no SnapKV stage, budgets 256 / 1024 / 4096.
+    # Eight (sequence, KV head) units only: a latency measurement more than a bandwidth one.
+    single = None
+    if not args.no_decomposed:
+        w1 = wl.CONFIGS["llama8b_layer_32k"]
+        sl = []
+        for layer in range(8):
+            d1 = wl.generate_device(w1, layer, dev)
+            c1 = rk.pack_cache(d1["K"], d1["V"], d1["seq_lens"].cpu().numpy(), w1.n_q_heads, 16,
+                               pages_cap=w1.context // 16 + 8)
+            km1, kn1 = rk.alloc_summaries(c1)
+            rk.build_page_summaries(c1, km1, kn1)
+            sl.append(dict(cache=c1, kmax=km1, kmin=kn1, q=d1["q"].contiguous(),
+                           out=torch.empty((1, w1.n_q_heads, D), dtype=torch.bfloat16, device=dev),
+                           wsd=rk.alloc_workspace(rk.OP_DENSE_DECODE, c1)))
+            del d1
+        nk1 = layers[0]["new_k"][:1].contiguous()
+        nv1 = layers[0]["new_v"][:1].contiguous()
+        single = {"workload": "llama8b_layer_32k: one layer, batch 1, 32q/8kv heads, context 32768, page 16, k1 32",
+                  "us_per_layer_step": {}}
+        for Tb in (256, 1024, 4096):
+            for L in sl:
+                L["ws"] = rk.alloc_workspace(rk.OP_HSA_DECODE, L["cache"], Tb)
+
+            def one_all():
+                for L in sl:
+                    rk.hsa_decode_append(L["cache"], L["q"], nk1, nv1, L["kmax"], L["kmin"], w1.channel_budget, Tb, 0,
+                                         L["out"], None, None, None, L["ws"], stream)
+
+            single["us_per_layer_step"][str(Tb)] = round(timed_graph(one_all, 6) * 1e3 / len(sl), 2)
+
+        def dense_one():
+            for L in sl:
+                rk.dense_decode(L["cache"], L["q"], L["out"], None, L["wsd"], stream)
+
+        single["dense_full_kv_us"] = round(timed_graph(dense_one, 6) * 1e3 / len(sl), 2)
+        del sl
+
     # ------------------------------------------------------------------ bytes
     kp = min(P_now, T // ps)
     attend_bytes = units * (kp * ps * D * 2 * 2 + 2 * G * D * 2)
@@ -407,6 +446,7 @@ def main():
                      "bytes_per_launch": hsa_bytes},
         "decomposed_operating_point": dec_pt,
         "multi_turn_variant": mt_pt,
+        "single_layer_batch1": single,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

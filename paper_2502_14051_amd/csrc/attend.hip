@@ -24,6 +24,7 @@ __global__ void zero_u32_kernel(uint32_t* p, int n) {
 }
 
 // ---- launch geometry ---------------------------------------------------------------------------------
+constexpr int kComputeUnits = 256;  // MI355X
 static int g_waves = 8;            // wavefronts per workgroup (4 or 8)
 static int g_pairs_per_wave = 2;   // page pairs a wavefront aims to own
 static int g_max_wgs = 2048;       // cap on units x splits (keeps the dense case from over-splitting)
@@ -41,9 +42,14 @@ AttendPlan plan_attend(const CacheView& c, int row_len) {
   // the LDS merge buffer must fit 64 KiB: waves * G * 130 floats
   while (waves > 4 && (size_t)waves * c.group * (kHeadDim + 2) * sizeof(float) > 60 * 1024) waves /= 2;
   p.waves = waves;
-  const int per_wg = 2 * g_pairs_per_wave * waves;  // entries one workgroup wants
+  const int per_wg = 2 * g_pairs_per_wave * waves;  // entries the smallest sensible workgroup takes
   int n_split = (row_len + per_wg - 1) / per_wg;
   const int max_split = g_max_wgs / units > 1 ? g_max_wgs / units : 1;
+  // More work than one round of workgroups over the chip: twice the smallest share per workgroup
+  // (a second round of short workgroups costs more than it hides), but never fewer workgroups than
+  // compute units.
+  const int fill = (kComputeUnits + units - 1) / units;
+  if (n_split > fill) n_split = n_split / 2 > fill ? n_split / 2 : fill;
   if (n_split > max_split) n_split = max_split;
   if (n_split < 1) n_split = 1;
   int chunk = (row_len + n_split - 1) / n_split;
