@@ -266,7 +266,6 @@ int32_t rocketkv_hsa_select(const rocketkv_cache_t* cache, const void* q, const 
   a.out_channels = out_channels;
   a.out_scores = out_scores;
   a.in_scores = nullptr;
-  a.zero_counters = nullptr;
   const hipError_t e = launch_hsa_select(view_of(cache), a, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? ROCKETKV_OK : hip_fail(e, who);
 }
@@ -338,7 +337,6 @@ int decode_impl(const char* who, const rocketkv_cache_t* cache, const void* q, c
     a.out_pages = out_pages;
     a.out_pages2 = nullptr;
     a.row_len2 = 0;
-    a.zero_counters = nullptr;
     e = launch_hsa_decode_fused(v, a, ap, static_cast<bf16_t*>(out), out_lse, ws + d.attend_off, d.attend, st);
     return e == hipSuccess ? ROCKETKV_OK : hip_fail(e, who);
   }
@@ -347,7 +345,6 @@ int decode_impl(const char* who, const rocketkv_cache_t* cache, const void* q, c
     a.out_pages = out_pages;
     a.out_pages2 = nullptr;
     a.row_len2 = 0;
-    a.zero_counters = nullptr;
     e = launch_hsa_decode_tok_fused(v, nullptr, a, ap, static_cast<bf16_t*>(out), out_lse, ws + d.attend_off,
                                     d.attend, st);
     return e == hipSuccess ? ROCKETKV_OK : hip_fail(e, who);
@@ -355,7 +352,6 @@ int decode_impl(const char* who, const rocketkv_cache_t* cache, const void* q, c
   a.out_pages = reinterpret_cast<int32_t*>(ws + d.list_off);
   a.out_pages2 = out_pages;
   a.row_len2 = d.row_len;
-  a.zero_counters = nullptr;
   if (select_wants_split(v, a.k1)) {
     // score launch (which also takes in the new token) + top-k launch
     a.out_scores = reinterpret_cast<float*>(ws + d.scores_off);
@@ -546,7 +542,6 @@ int mt_decode_impl(const char* who, const rocketkv_cache_t* cache, const rocketk
     a.row_len2 = 0;
     a.out_scores = nullptr;
     a.in_scores = nullptr;
-    a.zero_counters = nullptr;
     e = launch_hsa_decode_tok_fused(v, &lv, a, ap, static_cast<bf16_t*>(out), out_lse, ws + d.attend_off,
                                     d.attend, st);
     return e == hipSuccess ? ROCKETKV_OK : hip_fail(e, who);
@@ -561,7 +556,6 @@ int mt_decode_impl(const char* who, const rocketkv_cache_t* cache, const rocketk
   a.row_len2 = d.row_len;
   a.out_scores = select_wants_split(lcv, a.k1) ? reinterpret_cast<float*>(ws + d.scores_off) : nullptr;
   a.in_scores = nullptr;
-  a.zero_counters = nullptr;
   e = launch_hsa_select(lcv, a, st);
   if (e != hipSuccess) return hip_fail(e, who);
   e = launch_attend_tokens(v, a.q, a.out_pages, d.row_len, static_cast<bf16_t*>(out), out_lse,

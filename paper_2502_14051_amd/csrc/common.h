@@ -96,7 +96,6 @@ struct SelectArgs {
   int32_t* out_channels;  // optional
   float* out_scores;      // optional
   const float* in_scores; // set by the launcher when the scores come from a separate launch
-  uint32_t* zero_counters;  // optional [units]: cleared for the attention kernel that follows
 };
 struct AppendArgs {      // all null: plain decode
   const bf16_t* k_new;   // [B][Hkv][128]

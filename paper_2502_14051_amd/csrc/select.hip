@@ -146,7 +146,6 @@ hipError_t launch_hsa_select_split(const CacheView& c, const SelectArgs& a, cons
   SelectArgs b = a;
   b.in_scores = a.out_scores;
   b.out_channels = nullptr;  // written by the score launch
-  b.zero_counters = nullptr;
   hipLaunchKernelGGL(hsa_pick_kernel, dim3(units), dim3(kPickThreads), smem, st, c, b);
   return hipGetLastError();
 }

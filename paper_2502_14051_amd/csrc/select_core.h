@@ -110,7 +110,6 @@ __device__ __forceinline__ void select_channels(const CacheView& c, const Select
 
 #pragma unroll
   for (int i = 0; i < 4 * 256 / NT; ++i) (&sh.hist[0][0])[tid + i * NT] = 0;
-  if (write_global && a.zero_counters && tid == 0) a.zero_counters[unit] = 0;
 
   // ---- a[c] = sum_h |q|, s[c] = sum_h q (fp32, head order) -----------------------------------
   if (tid < kHeadDim) {
