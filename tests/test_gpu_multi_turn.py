@@ -204,3 +204,60 @@ def test_two_turns(env, oracle, lps, cache_ps, k1, T, N):
     ws2 = rk.mt_alloc_workspace(cache2, index2, T)
     decode_check(env, oracle, (cache2, index2, kmax2, kmin2, ws2), wlog, conv["q"], K2,
                  np.ascontiguousarray(conv["V"][:, :, :S2]))
+
+
+def test_empty_and_full_logical_sequences(env, oracle):
+    """Edge cases of the index: a sequence with nothing indexed gives zeros and -inf; a full index row
+    or a full cache leaves the sequence unchanged on append while the others take the token."""
+    torch, rk, dev = env
+    say("multi-turn edge cases")
+    B, S, T, k1, lps = 3, 640, 64, 32, 4
+    w = small("tiny", batch=B, context=S, page_size=lps, channel_budget=k1, token_budget=T, n_heavy=4)
+    d = wl.generate(w)
+    d["seq_lens"] = np.array([S, S, S - 5], dtype=np.int32)
+    # sequence 1's cache is exactly full (pages_cap * 16 == S); sequence 2 has room
+    cache, q = to_device_cache(rk, torch, d, w.n_q_heads, 16, dev, pages_cap=S // 16, v_layout=TM)
+    assert cache.pages_cap * 16 == S
+    index = rk.alloc_index(cache, lps, 96)
+    cap = index.pages_cap * lps
+    idx = np.full((B, w.n_kv_heads, cap), -1, dtype=np.int32)
+    n_idx = np.array([0, 40, cap], dtype=np.int32)   # empty / partly filled / full index row
+    rng = np.random.default_rng(8)
+    for b in range(B):
+        for g in range(w.n_kv_heads):
+            idx[b, g, :n_idx[b]] = np.sort(rng.choice(int(d["seq_lens"][b]), size=n_idx[b], replace=False))
+    index.token_index.copy_(torch.from_numpy(idx).to(dev))
+    index.n_indexed.copy_(torch.from_numpy(n_idx).to(dev))
+    kmax, kmin = rk.alloc_index_summaries(cache, index)
+    rk.mt_build_page_summaries(cache, index, kmax, kmin)
+    ws = rk.mt_alloc_workspace(cache, index, T)
+    out = torch.full((B, w.n_q_heads, 128), 3.0, dtype=torch.bfloat16, device=dev)
+    lse = torch.zeros((B, w.n_q_heads), dtype=torch.float32, device=dev)
+    row = min(index.pages_cap, (T + lps - 1) // lps)
+    pages = torch.empty((B, w.n_kv_heads, row), dtype=torch.int32, device=dev)
+    kn = wl.f32_to_bf16_bits(rng.standard_normal((B, w.n_kv_heads, 128)).astype(np.float32))
+    vn = wl.f32_to_bf16_bits(rng.standard_normal((B, w.n_kv_heads, 128)).astype(np.float32))
+    rk.mt_hsa_decode_append(cache, index, q, wl.from_bits(kn, dev), wl.from_bits(vn, dev), kmax, kmin, k1, T, 0,
+                            out, lse, pages, None, ws)
+    torch.cuda.synchronize()
+    # sequence 0: empty index, room in both -> the new token becomes its only logical token
+    # sequence 1: cache full -> unchanged; sequence 2: index full -> unchanged
+    got_n = index.n_indexed.cpu().numpy().tolist()
+    got_len = cache.seq_lens.cpu().numpy().tolist()
+    assert got_n[1:] == [40, cap] and got_len[1:] == [S, S - 5]
+    # (sequence 0's cache is full as well, so its empty index stays empty)
+    assert (got_n[0], got_len[0]) == (0, S)
+    y = wl.bf16_bits_to_f64(wl.to_bits(out))
+    assert (y[0] == 0).all() and np.isneginf(lse.cpu().numpy()[0]).all()
+    idx_now = index.token_index.cpu().numpy()
+    assert np.array_equal(idx_now, idx)
+    # sequences 1 and 2 against the oracle on their gathered rows
+    for b in (1, 2):
+        Kc = np.stack([d["K"][b, g, idx[b, g, :n_idx[b]]] for g in range(w.n_kv_heads)])[None]
+        Vc = np.stack([d["V"][b, g, idx[b, g, :n_idx[b]]] for g in range(w.n_kv_heads)])[None]
+        gp = pages.cpu().numpy()[b:b + 1]
+        want_y, want_lse = oracle.attend_given(d["q"][b:b + 1], Kc, Vc, n_idx[b:b + 1], lps, gp)
+        assert_attention_close(wl.to_bits(out)[b:b + 1], want_y, f"y b{b}")
+        wb = wl.scaled(w, batch=1)
+        check_selection(oracle, dict(q=d["q"][b:b + 1], K=Kc, V=Vc, seq_lens=n_idx[b:b + 1]), wb, index.pages_cap,
+                        gp, None, None)

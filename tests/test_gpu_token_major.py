@@ -306,3 +306,51 @@ def test_split_selection_breaks_ties_towards_lower_index(env, oracle, mode):
         want = np.sort(np.argsort(-sc.astype(np.float64), kind="stable")[:150])
         assert np.array_equal(gp[0, g, :150], want), (mode, g)
     check_selection(oracle, d, w, cache.pages_cap, gp, None, gs)
+
+
+@pytest.mark.parametrize("ps,k1,ctx,why", [(4, 32, 1000, "fused launch"), (2, 128, 1100, "score/pick/attention launches")])
+def test_append_to_a_full_cache_is_a_plain_decode(env, oracle, ps, k1, ctx, why):
+    """A sequence that already holds pages_cap * page_size tokens is left unchanged by the append and
+    still gets its attention result; its neighbour in the batch takes the token as usual."""
+    torch, rk, dev = env
+    T = 96
+    say("append to full cache, token-major", ps, k1, why)
+    cap_pages = ((ctx + ps - 1) // ps + 7) // 8 * 8
+    full_len = cap_pages * ps
+    w = small("tiny", batch=2, context=full_len, page_size=ps, channel_budget=k1, token_budget=T, n_heavy=4)
+    d = wl.generate(w)
+    d["seq_lens"] = np.array([full_len, full_len - 10], dtype=np.int32)
+    cache, q = to_device_cache(rk, torch, d, w.n_q_heads, ps, dev, pages_cap=cap_pages, v_layout=TM)
+    assert cache.pages_cap == cap_pages
+    kmax, kmin = rk.alloc_summaries(cache)
+    rk.build_page_summaries(cache, kmax, kmin)
+    row = rk.pages_row_len(cache, T)
+    out = torch.empty((2, w.n_q_heads, 128), dtype=torch.bfloat16, device=dev)
+    pages = torch.empty((2, w.n_kv_heads, row), dtype=torch.int32, device=dev)
+    ws = rk.alloc_workspace(rk.OP_HSA_DECODE, cache, T)
+    rng = np.random.default_rng(5)
+    kn = wl.f32_to_bf16_bits(rng.standard_normal((2, w.n_kv_heads, 128)).astype(np.float32))
+    vn = wl.f32_to_bf16_bits(rng.standard_normal((2, w.n_kv_heads, 128)).astype(np.float32))
+    k_before = cache.k_pool.clone()
+    rk.hsa_decode_append(cache, q, wl.from_bits(kn, dev), wl.from_bits(vn, dev), kmax, kmin, k1, T, 0, out, None,
+                         pages, None, ws)
+    torch.cuda.synchronize()
+    assert cache.seq_lens.cpu().numpy().tolist() == [full_len, full_len - 9]
+    K = d["K"].copy()
+    V = d["V"].copy()
+    K[1, :, full_len - 10] = kn[1]
+    V[1, :, full_len - 10] = vn[1]
+    lens = np.array([full_len, full_len - 9], dtype=np.int32)
+    gp = pages.cpu().numpy()
+    dd = dict(q=d["q"], K=K, V=V, seq_lens=lens)
+    check_selection(oracle, dd, w, cache.pages_cap, gp, None, None)
+    want_y, _ = oracle.attend_given(d["q"], K, V, lens, ps, gp)
+    assert_attention_close(wl.to_bits(out), want_y, "y")
+    # sequence 0's rows are untouched
+    Kg, _ = rk.unpack_cache(cache)
+    assert np.array_equal(wl.to_bits(Kg)[0], d["K"][0, :, :full_len])
+    # and the workspace is ready for the next call: same inputs, same bits
+    out2 = torch.empty_like(out)
+    rk.hsa_decode(cache, q, kmax, kmin, k1, T, 0, out2, None, None, None, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2)
