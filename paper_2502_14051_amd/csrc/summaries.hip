@@ -2,10 +2,10 @@
 // stored channel-major with the page index contiguous, plus the per-token append that keeps the
 // tail page's summary current.
 //
-// Bandwidth-bound: one pass over K.  A wavefront reads a page as coalesced 1 KiB slabs (16 lanes x
-// 16 B cover one 256 B token row, four rows per load), reduces the four row groups with two
-// cross-lane steps, and the workgroup transposes its 64 pages through LDS so that every summary
-// row is written as one 128 B run.
+// Bandwidth-bound: one pass over K.  Sixteen lanes x 16 B cover one 256 B token row; each group of 16
+// lanes reduces whole pages of its own, four rows in flight, so a wavefront has four pages under way at
+// any page size and nothing crosses lanes; the workgroup transposes its 64 pages through LDS so that
+// every summary row is written as one 128 B run.
 #include "common.h"
 
 namespace rkv {
@@ -31,7 +31,8 @@ __global__ __launch_bounds__(256) void page_summaries_kernel(CacheView c, bf16_t
   const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
   const int tg = lane / 16, cl = lane % 16;
 
-  for (int pl = wave; pl < npg; pl += 4) {
+  // every 16-lane group takes whole pages of its own (no cross-lane step), four rows in flight
+  for (int pl = wave * 4 + tg; pl < npg; pl += 16) {
     const int p = p0 + pl;
     const int64_t pp = phys_page(c, b, p);
     const int ntok = min(ps, n - p * ps);
@@ -39,31 +40,30 @@ __global__ __launch_bounds__(256) void page_summaries_kernel(CacheView c, bf16_t
 #pragma unroll
     for (int i = 0; i < 8; ++i) { mx[i] = -INFINITY; mn[i] = INFINITY; }
     if (pp >= 0) {
-      const bf16_t* tile = c.k_pool + pp * c.stride_page + (int64_t)g * c.stride_head;
-      for (int t = tg; t < ntok; t += 4) {
-        const uint4 v = *reinterpret_cast<const uint4*>(tile + t * kHeadDim + cl * 8);
-        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+      const bf16_t* tile = c.k_pool + pp * c.stride_page + (int64_t)g * c.stride_head + cl * 8;
+      for (int t0 = 0; t0 < ntok; t0 += 4) {
+        uint4 v[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const float lo = bf16lo_to_f32(w[i]), hi = bf16hi_to_f32(w[i]);
-          mx[2 * i] = fmaxf(mx[2 * i], lo); mn[2 * i] = fminf(mn[2 * i], lo);
-          mx[2 * i + 1] = fmaxf(mx[2 * i + 1], hi); mn[2 * i + 1] = fminf(mn[2 * i + 1], hi);
+        for (int u = 0; u < 4; ++u)
+          v[u] = *reinterpret_cast<const uint4*>(tile + min(t0 + u, ntok - 1) * kHeadDim);  // a repeat is harmless
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const uint32_t w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float lo = bf16lo_to_f32(w[i]), hi = bf16hi_to_f32(w[i]);
+            mx[2 * i] = fmaxf(mx[2 * i], lo); mn[2 * i] = fminf(mn[2 * i], lo);
+            mx[2 * i + 1] = fmaxf(mx[2 * i + 1], hi); mn[2 * i + 1] = fminf(mn[2 * i + 1], hi);
+          }
         }
       }
     }
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      mx[i] = fmaxf(mx[i], __shfl_xor(mx[i], 16)); mx[i] = fmaxf(mx[i], __shfl_xor(mx[i], 32));
-      mn[i] = fminf(mn[i], __shfl_xor(mn[i], 16)); mn[i] = fminf(mn[i], __shfl_xor(mn[i], 32));
-    }
-    if (tg == 0) {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        // an absent page contributes neutral zeros
-        const float a = pp >= 0 ? mx[i] : 0.f, z = pp >= 0 ? mn[i] : 0.f;
-        tmax[(cl * 8 + i) * kSumPad + pl] = (bf16_t)(__float_as_uint(a) >> 16);
-        tmin[(cl * 8 + i) * kSumPad + pl] = (bf16_t)(__float_as_uint(z) >> 16);
-      }
+      // an absent page contributes neutral zeros
+      const float a = pp >= 0 ? mx[i] : 0.f, z = pp >= 0 ? mn[i] : 0.f;
+      tmax[(cl * 8 + i) * kSumPad + pl] = (bf16_t)(__float_as_uint(a) >> 16);
+      tmin[(cl * 8 + i) * kSumPad + pl] = (bf16_t)(__float_as_uint(z) >> 16);
     }
   }
   __syncthreads();
