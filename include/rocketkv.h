@@ -325,11 +325,16 @@ int32_t rocketkv_mt_hsa_decode_append(const rocketkv_cache_t* cache, const rocke
  *   channel_budget = round(head_dim / head_ratio)     in [1, head_dim],
  *   attend_tokens  = max(1, t / 2)                    the token_budget argument
  *                                                     of the decode entry points.
+ * storage, storage_mt and traffic are the RocketKV and RocketKV-MT rows of Table 1 as printed:
+ *   storage = 1/c^r + 2/c^((1+r)/2),  storage_mt = 1 + 2/c^((1+r)/2),  traffic = 1/c,
+ * relative to the full KV cache; they bound what the buffers of this library need (the K_max /
+ * K_min pair of a page size ps costs 1/ps of the kept K/V, half of Table 1's auxiliary term).
  * Host arithmetic only (double precision); `out` is a host struct.
  */
 typedef struct rocketkv_split {
   double c, r, stage1, stage2, head_ratio;
   int32_t page_size, keep_budget, channel_budget, attend_tokens;
+  double storage, storage_mt, traffic;
 } rocketkv_split_t;
 int32_t rocketkv_decompose(int64_t seq_len, int32_t token_budget, int32_t head_dim,
                            rocketkv_split_t* out);

@@ -230,6 +230,12 @@ def decompose(c):
     _load().okv_decompose(C.c_double(float(c)), _p(out, C.c_double))
     return dict(r=out[0], stage1=out[1], stage2=out[2], page=int(out[3]), head_ratio=out[4])
 
+def cost_model(c):
+    """Table 1 (RocketKV / RocketKV-MT rows): dict(storage, storage_mt, traffic) relative to full KV."""
+    out = np.zeros(3, dtype=np.float64)
+    _load().okv_cost_model(C.c_double(float(c)), _p(out, C.c_double))
+    return dict(storage=out[0], storage_mt=out[1], traffic=out[2])
+
 
 def decompose_budget(S, t, D):
     """Section 3.6 + Appendix A.3: integer operating point dict(page, keep, channels, attend_tokens)."""

@@ -422,6 +422,20 @@ void okv_decompose(double c, double* out) {
   out[0] = r; out[1] = c1; out[2] = c2; out[3] = page; out[4] = c2 / page;
 }
 
+/* Table 1, rows RocketKV and RocketKV-MT: storage (KV cache plus the K_max / */
+/* K_min tensors) and traffic relative to the full KV cache at compression   */
+/* ratio c, as printed: 1/c^r + 2/c^((1+r)/2), 1 + 2/c^((1+r)/2), 1/c.       */
+/* out: storage, storage_mt, traffic.                                        */
+void okv_cost_model(double c, double* out) {
+  double sp[5];
+  okv_decompose(c, sp);
+  double r = sp[0];
+  double aux = 2.0 / pow(c, (1.0 + r) / 2.0);
+  out[0] = 1.0 / pow(c, r) + aux;
+  out[1] = 1.0 + aux;
+  out[2] = 1.0 / c;
+}
+
 /* Integer operating point that follows from the split when the budget t is   */
 /* shared evenly by Step 2 and Step 3 (Appendix A.3): Stage 1 keeps S / c^r   */
 /* tokens, Step 2 reads D / head_ratio channels of one summary row per page,  */

@@ -461,6 +461,10 @@ int32_t rocketkv_decompose(int64_t seq_len, int32_t token_budget, int32_t head_d
   const double ch = floor((double)head_dim / s.head_ratio + 0.5);
   s.channel_budget = (int32_t)fmin(fmax(ch, 1.0), (double)head_dim);
   s.attend_tokens = token_budget / 2 > 1 ? token_budget / 2 : 1;
+  const double aux = 2.0 / pow(s.c, 0.5 * (1.0 + s.r));  // K_max and K_min, Table 1's accounting
+  s.storage = 1.0 / s.stage1 + aux;
+  s.storage_mt = 1.0 + aux;
+  s.traffic = 1.0 / s.c;
   *out = s;
   return ROCKETKV_OK;
 }

@@ -59,6 +59,7 @@ class SplitStruct(C.Structure):
         ("c", C.c_double), ("r", C.c_double), ("stage1", C.c_double), ("stage2", C.c_double),
         ("head_ratio", C.c_double), ("page_size", C.c_int32), ("keep_budget", C.c_int32),
         ("channel_budget", C.c_int32), ("attend_tokens", C.c_int32),
+        ("storage", C.c_double), ("storage_mt", C.c_double), ("traffic", C.c_double),
     ]
 
 

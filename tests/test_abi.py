@@ -153,6 +153,9 @@ def test_decompose_is_host_arithmetic_and_matches_oracle(L, oracle):
                     assert abs(got[k_lib] - ref[k_or]) <= 1e-12 * max(1.0, abs(ref[k_or]))
                 assert (got["page_size"], got["keep_budget"], got["channel_budget"], got["attend_tokens"]) == \
                     (want["page"], want["keep"], want["channels"], want["attend_tokens"]), (S, t, D)
+                cm = oracle.cost_model(max(1.0, S / t))
+                for k in ("storage", "storage_mt", "traffic"):
+                    assert abs(got[k] - cm[k]) <= 1e-12 * max(1.0, cm[k])
     out = rk.SplitStruct()
     assert L.rocketkv_decompose(0, 512, 128, C.byref(out)) == rk.INVALID_ARG
     assert L.rocketkv_decompose(4096, 0, 128, C.byref(out)) == rk.INVALID_ARG

@@ -405,6 +405,33 @@ def test_decomposed_operating_point_reproduces_the_budget(oracle):
     assert (p["page"], p["keep"], p["channels"]) == (1, 1000, D)
 
 
+def test_cost_model_bounds_the_buffers_of_the_operating_point(oracle):
+    """Table 1: storage 1/c^r + 2/c^((1+r)/2) and traffic 1/c relative to the full KV cache.  Checked
+    against bytes counted from the integer operating point: kept K/V plus the K_max/K_min pair must
+    stay within the printed storage term (the pair costs 1/page of the kept K/V, half of what the
+    table books for it), the two steps' traffic must add up to S/c key/value pairs, and the
+    multi-turn row differs from the eviction row by exactly the first-stage saving."""
+    D = 128
+    for S, t in [(32768, 512), (32768, 2048), (131072, 1024), (65536, 1024)]:
+        c = S / t
+        m = oracle.cost_model(c)
+        sp = oracle.decompose(c)
+        p = oracle.decompose_budget(S, t, D)
+        full = S * 2 * D                                         # elements of K and V
+        kept = p["keep"] * 2 * D
+        aux = 2 * D * -(-p["keep"] // p["page"])                 # K_max and K_min rows
+        assert (kept + aux) / full <= m["storage"] * 1.01
+        assert (kept + 2 * aux) / full >= m["storage"] * 0.75    # the table's own (doubled) accounting
+        step2 = p["keep"] * p["channels"] / (p["page"] * 2.0 * D)
+        assert abs((step2 + p["attend_tokens"]) / S - m["traffic"]) <= 0.03 * m["traffic"]
+        np.testing.assert_allclose(m["storage_mt"] - m["storage"], 1.0 - 1.0 / sp["stage1"], rtol=1e-12)
+        np.testing.assert_allclose(m["traffic"] * c, 1.0, rtol=1e-12)
+    # c = 64, from the ratios the section prints: 1/10.3 + 2/(10.3 * sqrt(6.2)) = 0.175
+    g = read_golden("decompose_c64.txt")
+    want = 1.0 / g["stage1"] + 2.0 / (g["stage1"] * g["stage2"] ** 0.5)
+    assert abs(oracle.cost_model(g["c"])["storage"] - want) < 2e-3
+
+
 def test_kv_size_example_matches_byte_accounting():
     g = read_golden("kv_size_example.txt")
     total = (g["layers"] * g["batch"] * g["kv_heads"] * g["context"] * g["head_dim"]
