@@ -150,9 +150,10 @@ hipError_t launch_append_indexed(const CacheView& c, const LogicalView& lv, cons
 // Step 2 + Step 3 in one launch; usable when fused_decode_lds_bytes() fits kMaxLdsBytes
 constexpr size_t kMaxLdsBytes = 64 * 1024;
 size_t fused_decode_lds_bytes(const CacheView& c, int row_len, const AttendPlan& plan);
-// The large-summary path of Step 2 (a.out_scores must be set); with ap.k_new it also takes in the
-// generated token, using `unit_counters` ([units]) and `seq_counters` ([batch], both zero on entry and
-// on exit) for the length update.
+// The large-summary path of Step 2 (a.out_scores must be set).  With `unit_counters` ([units]) and
+// `seq_counters` ([batch]; both zero on entry and on exit) it is one launch and, given ap.k_new, also
+// takes in the generated token; without counters (and without append) a score launch and a top-k
+// launch.
 hipError_t launch_hsa_select_split(const CacheView& c, const SelectArgs& a, const AppendArgs& ap,
                                    uint32_t* unit_counters, uint32_t* seq_counters, hipStream_t st);
 uint32_t* decode_seq_counters(void* ws, const AttendPlan& plan);

@@ -19,22 +19,40 @@ __global__ __launch_bounds__(kSelThreads) void hsa_select_kernel(CacheView c, Se
   select_block<kSelThreads>(c, a, unit, n, sh, keys, nullptr, true, none);
 }
 
-constexpr int kScoreRuns = 64;  // eight-page runs per workgroup of the split score launch
-
+// ---- large summaries: scores by several workgroups per (sequence, KV head), then the top-k ---------
+//
+// NT threads score NT/4 eight-page runs.  Two shapes are launched:
+//   <256, APPEND, false>  small workgroups for the score launch of rocketkv_hsa_select, which has no
+//                         workspace for counters and leaves the top-k to hsa_pick_kernel;
+//   <1024, APPEND, true>  the decode step: a (sequence, KV head) is covered by one to four workgroups of
+//                         a compute unit's worth of threads; the scores go out with device-scope stores,
+//                         each workgroup reports to the unit's counter, and the last one to report
+//                         picks the top-k right there, a launch boundary and a round trip earlier.
+//
 // APPEND: the launch also takes in the token generated at this step (Section 3.4 Step 1, last
 // sentence).  Every workgroup reads the old length once, scores with the new key folded into the tail
 // page's bound from an LDS copy (so it does not matter whether the write-back has landed), and reports
-// its read to the sequence's counter; workgroup 0 of each (sequence, KV head) writes the key row, the
-// value row or column and the summary column; the workgroup that finds every other one of the
-// sequence has reported stores the new length, so that no reader of this launch sees it change.
-// unit_counters ([units]) and seq_counters ([batch]) are zero on entry and on exit.
-template <bool APPEND>
-__global__ __launch_bounds__(kSelThreads) void hsa_score_kernel(CacheView c, SelectArgs a, AppendArgs ap,
-                                                                uint32_t* unit_counters,
-                                                                uint32_t* seq_counters) {
-  __shared__ SelectShared<kSelThreads> sh;
-  __shared__ int s_n0;
+// its read; workgroup 0 of each (sequence, KV head) writes the key row, the value row or column and
+// the summary column.  Reports go to two levels of counters so that none sees more than a handful of
+// arrivals: the workgroups of a (sequence, KV head) meet at its counter, the last of them goes on to
+// the sequence's, and the last one there stores the new length: no reader of this launch sees it
+// change.  unit_counters ([units]) and seq_counters ([batch]) are zero on entry and on exit.
+constexpr int kPickThreads = 1024;
+
+template <int NT, bool PICK>
+struct ScoreLds {
+  static constexpr size_t kPick = PICK ? sizeof(PickShared<NT>) + (size_t)ROCKETKV_MAX_PAGES * sizeof(uint32_t) : 0;
+  static constexpr size_t kBytes = sizeof(SelectShared<NT>) > kPick ? sizeof(SelectShared<NT>) : kPick;
+};
+
+template <int NT, bool APPEND, bool PICK>
+__global__ __launch_bounds__(NT) void hsa_score_kernel(CacheView c, SelectArgs a, AppendArgs ap,
+                                                       uint32_t* unit_counters, uint32_t* seq_counters) {
+  constexpr int kRuns = NT / 4;  // eight-page runs per workgroup
+  __shared__ __align__(16) unsigned char lds[ScoreLds<NT, PICK>::kBytes];  // selection state, then the pick's
+  __shared__ int s_n0, s_last;
   __shared__ bf16_t s_knew[kHeadDim];
+  SelectShared<NT>& sh = *reinterpret_cast<SelectShared<NT>*>(lds);
   const int tid = threadIdx.x;
   const int unit = blockIdx.y;
   const int b = unit / c.n_kv_heads, g = unit % c.n_kv_heads;
@@ -50,7 +68,7 @@ __global__ __launch_bounds__(kSelThreads) void hsa_score_kernel(CacheView c, Sel
       s_knew[tid] = kb;
     }
   }
-  select_channels<kSelThreads>(c, a, unit, sh, blockIdx.x == 0);  // its barriers publish s_n0 / s_knew
+  select_channels<NT>(c, a, unit, sh, blockIdx.x == 0);  // its barriers publish s_n0 / s_knew
   TailPatch tp = {-1, 0, s_knew, nullptr};
   bool room = false;
   if (APPEND) {
@@ -72,41 +90,50 @@ __global__ __launch_bounds__(kSelThreads) void hsa_score_kernel(CacheView c, Sel
   }
   int P = (n + c.page_size - 1) / c.page_size;
   if (P > c.pages_cap) P = c.pages_cap;
-  const int o_begin = blockIdx.x * kScoreRuns;
-  const int n_runs = min(kScoreRuns, (P + 7) / 8 - o_begin);
+  const int o_begin = blockIdx.x * kRuns;
+  const int n_runs = min(kRuns, (P + 7) / 8 - o_begin);
   if (n_runs > 0)
-    score_chunk<kSelThreads>(c, a, unit, P, sh, o_begin, n_runs, a.out_scores + (int64_t)unit * c.pages_cap, tp);
-  if (APPEND) {
-    if (writer) {
-      const int64_t pp = phys_page(c, b, tp.page);
-      if (pp >= 0) {
-        const int64_t base = pp * c.stride_page + (int64_t)g * c.stride_head;
-        c.k_pool[base + tp.slot * kHeadDim + tid] = kb;
-        c.v_pool[base + (c.v_token_major ? tp.slot * kHeadDim + tid : tid * c.page_size + tp.slot)] = vb;
-      }
-      const float x = bf16_to_f32(kb);
-      if (tp.slot == 0 || x > bf16_to_f32(old_max)) ap.kmax[sum_off] = kb;
-      if (tp.slot == 0 || x < bf16_to_f32(old_min)) ap.kmin[sum_off] = kb;
+    score_chunk<NT, PICK>(c, a, unit, P, sh, o_begin, n_runs, a.out_scores + (int64_t)unit * c.pages_cap, tp);
+  if (writer) {
+    const int64_t pp = phys_page(c, b, tp.page);
+    if (pp >= 0) {
+      const int64_t base = pp * c.stride_page + (int64_t)g * c.stride_head;
+      c.k_pool[base + tp.slot * kHeadDim + tid] = kb;
+      c.v_pool[base + (c.v_token_major ? tp.slot * kHeadDim + tid : tid * c.page_size + tp.slot)] = vb;
     }
-    if (tid == 0) {
-      // two levels, so that no counter sees more than a handful of arrivals: the workgroups of a
-      // (sequence, KV head) meet at its counter, the last of them goes on to the sequence's
-      if (__hip_atomic_fetch_add(&unit_counters[unit], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
-          gridDim.x - 1u) {
-        __hip_atomic_store(&unit_counters[unit], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (__hip_atomic_fetch_add(&seq_counters[b], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
-            (uint32_t)c.n_kv_heads - 1u) {
-          if (room) c.seq_lens[b] = n;
-          __hip_atomic_store(&seq_counters[b], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-      }
-    }
+    const float x = bf16_to_f32(kb);
+    if (tp.slot == 0 || x > bf16_to_f32(old_max)) ap.kmax[sum_off] = kb;
+    if (tp.slot == 0 || x < bf16_to_f32(old_min)) ap.kmin[sum_off] = kb;
   }
+  if (!APPEND && !PICK) return;
+  // (score_chunk ended with a barrier: with PICK, this workgroup's scores have been acknowledged)
+  if (tid == 0) {
+    const bool last = __hip_atomic_fetch_add(&unit_counters[unit], 1u, __ATOMIC_RELAXED,
+                                             __HIP_MEMORY_SCOPE_AGENT) == gridDim.x - 1u;
+    if (last) {
+      __hip_atomic_store(&unit_counters[unit], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (APPEND && __hip_atomic_fetch_add(&seq_counters[b], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+                        (uint32_t)c.n_kv_heads - 1u) {
+        if (room) c.seq_lens[b] = n;
+        __hip_atomic_store(&seq_counters[b], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+    s_last = last;
+  }
+  if (!PICK) return;
+  __syncthreads();  // also: every thread is done with the selection state in `lds`
+  if (!s_last) return;
+  PickShared<NT>& ph = *reinterpret_cast<PickShared<NT>*>(lds);
+  uint32_t* keys = reinterpret_cast<uint32_t*>(lds + sizeof(PickShared<NT>));
+  for (int i = tid; i < 4 * 256; i += NT) (&ph.hist[0][0])[i] = 0;
+  __syncthreads();
+  SelectArgs pa = a;
+  pa.in_scores = a.out_scores;
+  pick_from_scores<NT, true>(c, pa, unit, n, ph, keys);
 }
 
 // one workgroup per (sequence, KV head) and a whole compute unit's worth of threads for it: the pick is
 // short dependent phases of per-score work, so lanes are what shortens it
-constexpr int kPickThreads = 1024;
 __global__ __launch_bounds__(kPickThreads) void hsa_pick_kernel(CacheView c, SelectArgs a) {
   extern __shared__ uint32_t keys[];
   __shared__ PickShared<kPickThreads> sh;
@@ -134,15 +161,23 @@ hipError_t launch_hsa_select(const CacheView& c, const SelectArgs& a, hipStream_
 
 hipError_t launch_hsa_select_split(const CacheView& c, const SelectArgs& a, const AppendArgs& ap,
                                    uint32_t* unit_counters, uint32_t* seq_counters, hipStream_t st) {
-  const size_t smem = (size_t)((c.pages_cap + 7) / 8 * 8) * sizeof(uint32_t);
   const int units = c.batch * c.n_kv_heads;
-  const int chunks = ((c.pages_cap + 7) / 8 + kScoreRuns - 1) / kScoreRuns;
-  if (ap.k_new)
-    hipLaunchKernelGGL(hsa_score_kernel<true>, dim3(chunks, units), dim3(kSelThreads), 0, st, c, a, ap,
-                       unit_counters, seq_counters);
-  else
-    hipLaunchKernelGGL(hsa_score_kernel<false>, dim3(chunks, units), dim3(kSelThreads), 0, st, c, a, ap,
-                       unit_counters, seq_counters);
+  const int runs = (c.pages_cap + 7) / 8;
+  if (unit_counters) {
+    // with counters to meet at: scores and top-k in one launch
+    const dim3 grid((runs + kPickThreads / 4 - 1) / (kPickThreads / 4), units);
+    if (ap.k_new)
+      hipLaunchKernelGGL((hsa_score_kernel<kPickThreads, true, true>), grid, dim3(kPickThreads), 0, st, c, a, ap,
+                         unit_counters, seq_counters);
+    else
+      hipLaunchKernelGGL((hsa_score_kernel<kPickThreads, false, true>), grid, dim3(kPickThreads), 0, st, c, a, ap,
+                         unit_counters, seq_counters);
+    return hipGetLastError();
+  }
+  const size_t smem = (size_t)((c.pages_cap + 7) / 8 * 8) * sizeof(uint32_t);
+  const dim3 grid((runs + kSelThreads / 4 - 1) / (kSelThreads / 4), units);
+  hipLaunchKernelGGL((hsa_score_kernel<kSelThreads, false, false>), grid, dim3(kSelThreads), 0, st, c, a, ap,
+                     unit_counters, seq_counters);
   SelectArgs b = a;
   b.in_scores = a.out_scores;
   b.out_channels = nullptr;  // written by the score launch

@@ -348,7 +348,9 @@ struct PickShared {
   uint32_t cnt0;
 };
 
-template <int NT>
+// COHERENT: the scores were written earlier in the SAME launch by other workgroups (with device-scope
+// write-through stores): they are read with device-scope loads, which do not trust this XCD's L2.
+template <int NT, bool COHERENT = false>
 __device__ __forceinline__ void pick_from_scores(const CacheView& c, const SelectArgs& a, int unit, int n,
                                                  PickShared<NT>& sh, uint32_t* keys) {
   constexpr int kVec = ROCKETKV_MAX_PAGES / 4 / NT;  // float4 loads per thread at the largest P
@@ -362,8 +364,20 @@ __device__ __forceinline__ void pick_from_scores(const CacheView& c, const Selec
   const float4* in4 = reinterpret_cast<const float4*>(a.in_scores + (int64_t)unit * c.pages_cap);
   float4 v[kVec];
 #pragma unroll
-  for (int i = 0; i < kVec; ++i)
-    v[i] = (i < per && (v_begin + i) * 4 < c.pages_cap) ? in4[v_begin + i] : make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int i = 0; i < kVec; ++i) {
+    v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (i < per && (v_begin + i) * 4 < c.pages_cap) {
+      if (COHERENT) {
+        const float* f = reinterpret_cast<const float*>(in4 + v_begin + i);
+        v[i] = make_float4(__hip_atomic_load(f + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT),
+                           __hip_atomic_load(f + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT),
+                           __hip_atomic_load(f + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT),
+                           __hip_atomic_load(f + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+      } else {
+        v[i] = in4[v_begin + i];
+      }
+    }
+  }
   const int ps = c.page_size;
   int P = (n + ps - 1) / ps;
   if (P > c.pages_cap) P = c.pages_cap;
@@ -524,7 +538,7 @@ __device__ __forceinline__ void pick_from_scores(const CacheView& c, const Selec
 // raw fp32 sums to `scores_row[page]` for page < P.  For summaries too large for one workgroup to
 // stream at a useful rate: several workgroups take a slice each (every one repeats the cheap channel
 // pick), and the top-k runs afterwards on the scores.  Needs sh.s_chan / sh.s_wgt; ends with a barrier.
-template <int NT>
+template <int NT, bool COHERENT = false>
 __device__ __forceinline__ void score_chunk(const CacheView& c, const SelectArgs& a, int unit, int P,
                                             SelectShared<NT>& sh, int o_begin, int n_runs,
                                             float* scores_row, const TailPatch& tp) {
@@ -547,7 +561,12 @@ __device__ __forceinline__ void score_chunk(const CacheView& c, const SelectArgs
     float s = 0.f;
     for (int rr = 0; rr < R; ++rr) s += sh.partial[rr * npow * 8 + p];
     const int page = o_begin * 8 + p;
-    if (page < P) scores_row[page] = s;
+    if (page < P) {
+      if (COHERENT)  // read back by another workgroup of this launch: write through, device scope
+        __hip_atomic_store(&scores_row[page], s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      else
+        scores_row[page] = s;
+    }
   }
   __syncthreads();
 }
