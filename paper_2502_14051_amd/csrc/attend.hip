@@ -42,7 +42,11 @@ AttendPlan plan_attend(const CacheView& c, int row_len) {
   // the LDS merge buffer must fit 64 KiB: waves * G * 130 floats
   while (waves > 4 && (size_t)waves * c.group * (kHeadDim + 2) * sizeof(float) > 60 * 1024) waves /= 2;
   p.waves = waves;
-  const int per_wg = 2 * g_pairs_per_wave * waves;  // entries the smallest sensible workgroup takes
+  // entries the smallest sensible workgroup takes: normally g_pairs_per_wave page pairs per wavefront,
+  // one pair when even that leaves compute units idle (few units: shorter streams beat fewer merges)
+  int pairs = g_pairs_per_wave;
+  if ((int64_t)units * ((row_len + 2 * waves - 1) / (2 * waves)) <= kComputeUnits) pairs = 1;
+  const int per_wg = 2 * pairs * waves;
   int n_split = (row_len + per_wg - 1) / per_wg;
   const int max_split = g_max_wgs / units > 1 ? g_max_wgs / units : 1;
   // More work than one round of workgroups over the chip: twice the smallest share per workgroup
