@@ -70,7 +70,7 @@
 extern "C" {
 #endif
 
-#define ROCKETKV_MAX_PAGES 8192
+#define ROCKETKV_MAX_PAGES 32768
 
 typedef enum {
   ROCKETKV_OK = 0,
@@ -147,7 +147,9 @@ int32_t rocketkv_build_page_summaries(const rocketkv_cache_t* cache, void* kmax,
  * out_pages: int32 [batch][n_kv_heads][pages_row_len], ascending page ids, -1 padded;
  *            pages_row_len must be >= min(pages_cap, ceil(token_budget / page_size)).
  * out_channels: optional int32 [batch][n_kv_heads][channel_budget], ascending.
- * out_scores: optional fp32 [batch][n_kv_heads][pages_cap] (first P entries written).
+ * out_scores: optional fp32 [batch][n_kv_heads][pages_cap] (first P entries written); required
+ *             when pages_cap exceeds 8192 (the selection then runs as a score launch and a top-k
+ *             launch with the scores in between; the decode entry points keep them in the workspace).
  */
 int32_t rocketkv_hsa_select(const rocketkv_cache_t* cache, const void* q, const void* kmax,
                             const void* kmin, int32_t channel_budget, int32_t token_budget,

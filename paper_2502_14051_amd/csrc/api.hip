@@ -249,6 +249,9 @@ int32_t rocketkv_hsa_select(const rocketkv_cache_t* cache, const void* q, const 
   if (int r = check_cache(cache, true, who)) return r;
   if (int r = check_select_args(cache, q, kmax, kmin, channel_budget, token_budget, n_recent_pages, who)) return r;
   if (!out_pages) return fail(ROCKETKV_INVALID_ARG, "%s: out_pages must not be NULL", who);
+  if (cache->pages_cap > kSingleSelectPages && !out_scores)
+    return fail(ROCKETKV_UNSUPPORTED, "%s: pages_cap %d > %d needs out_scores", who, cache->pages_cap,
+                kSingleSelectPages);
   if (pages_row_len < list_len_for_budget(cache, token_budget))
     return fail(ROCKETKV_INVALID_ARG, "%s: pages_row_len %d < %d needed for this budget", who,
                 pages_row_len, list_len_for_budget(cache, token_budget));

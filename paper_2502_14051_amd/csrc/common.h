@@ -12,6 +12,7 @@ constexpr int kHeadDim = 128;      // channels per head handled by every kernel
 constexpr int kWave = 64;          // CDNA wavefront
 constexpr int kMaxGroup = 16;      // query heads per KV head that fit one MFMA tile
 constexpr int kAttnPage = 16;      // page size of the matrix-core attention path
+constexpr int kSingleSelectPages = 8192;  // most pages a one-workgroup selection keeps in LDS
 
 typedef uint16_t bf16_t;           // raw bf16 bits
 

@@ -41,7 +41,7 @@ constexpr int kPickThreads = 1024;
 
 template <int NT, bool PICK>
 struct ScoreLds {
-  static constexpr size_t kPick = PICK ? sizeof(PickShared<NT>) + (size_t)ROCKETKV_MAX_PAGES * sizeof(uint32_t) : 0;
+  static constexpr size_t kPick = PICK ? sizeof(PickShared<NT>) : 0;
   static constexpr size_t kBytes = sizeof(SelectShared<NT>) > kPick ? sizeof(SelectShared<NT>) : kPick;
 };
 
@@ -124,28 +124,26 @@ __global__ __launch_bounds__(NT) void hsa_score_kernel(CacheView c, SelectArgs a
   __syncthreads();  // also: every thread is done with the selection state in `lds`
   if (!s_last) return;
   PickShared<NT>& ph = *reinterpret_cast<PickShared<NT>*>(lds);
-  uint32_t* keys = reinterpret_cast<uint32_t*>(lds + sizeof(PickShared<NT>));
   for (int i = tid; i < 4 * 256; i += NT) (&ph.hist[0][0])[i] = 0;
   __syncthreads();
   SelectArgs pa = a;
   pa.in_scores = a.out_scores;
-  pick_from_scores<NT, true>(c, pa, unit, n, ph, keys);
+  pick_from_scores<NT, true>(c, pa, unit, n, ph);
 }
 
 // one workgroup per (sequence, KV head) and a whole compute unit's worth of threads for it: the pick is
 // short dependent phases of per-score work, so lanes are what shortens it
 __global__ __launch_bounds__(kPickThreads) void hsa_pick_kernel(CacheView c, SelectArgs a) {
-  extern __shared__ uint32_t keys[];
   __shared__ PickShared<kPickThreads> sh;
   const int unit = blockIdx.x;
   const int n = c.seq_lens[unit / c.n_kv_heads];
   (&sh.hist[0][0])[threadIdx.x] = 0;
   __syncthreads();
-  pick_from_scores<kPickThreads>(c, a, unit, n, sh, keys);
+  pick_from_scores<kPickThreads>(c, a, unit, n, sh);
 }
 
 bool select_wants_split(const CacheView& c, int k1) {
-  return (int64_t)k1 * c.pages_cap * (int64_t)sizeof(bf16_t) >= 128 * 1024;
+  return c.pages_cap > kSingleSelectPages || (int64_t)k1 * c.pages_cap * (int64_t)sizeof(bf16_t) >= 128 * 1024;
 }
 
 hipError_t launch_hsa_select(const CacheView& c, const SelectArgs& a, hipStream_t st) {
@@ -174,14 +172,13 @@ hipError_t launch_hsa_select_split(const CacheView& c, const SelectArgs& a, cons
                          unit_counters, seq_counters);
     return hipGetLastError();
   }
-  const size_t smem = (size_t)((c.pages_cap + 7) / 8 * 8) * sizeof(uint32_t);
   const dim3 grid((runs + kSelThreads / 4 - 1) / (kSelThreads / 4), units);
   hipLaunchKernelGGL((hsa_score_kernel<kSelThreads, false, false>), grid, dim3(kSelThreads), 0, st, c, a, ap,
                      unit_counters, seq_counters);
   SelectArgs b = a;
   b.in_scores = a.out_scores;
   b.out_channels = nullptr;  // written by the score launch
-  hipLaunchKernelGGL(hsa_pick_kernel, dim3(units), dim3(kPickThreads), smem, st, c, b);
+  hipLaunchKernelGGL(hsa_pick_kernel, dim3(units), dim3(kPickThreads), 0, st, c, b);
   return hipGetLastError();
 }
 

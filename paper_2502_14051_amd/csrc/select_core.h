@@ -337,7 +337,7 @@ __device__ __forceinline__ float f32_from_order_key(uint32_t k) {
 // value bins spread them where the leading radix digits would pile them into one or two counters.
 // Binning is monotone, hence the result is exactly the radix select's, ties to the lower page
 // included.  Scores without a finite range, or more than 1024 of them in that one bin, fall back to
-// the radix passes on the LDS copy of the keys.  `keys`: LDS, ceil8(pages_cap) words.
+// radix passes over the same registers.  Up to ROCKETKV_MAX_PAGES pages.
 template <int NT>
 struct PickShared {
   __align__(16) uint32_t hist[4][256];  // 1024 value bins, or the four radix histograms of the fallback
@@ -350,10 +350,10 @@ struct PickShared {
 
 // COHERENT: the scores were written earlier in the SAME launch by other workgroups (with device-scope
 // write-through stores): they are read with device-scope loads, which do not trust this XCD's L2.
-template <int NT, bool COHERENT = false>
-__device__ __forceinline__ void pick_from_scores(const CacheView& c, const SelectArgs& a, int unit, int n,
-                                                 PickShared<NT>& sh, uint32_t* keys) {
-  constexpr int kVec = ROCKETKV_MAX_PAGES / 4 / NT;  // float4 loads per thread at the largest P
+// kVec: float4 loads per thread, i.e. NT * kVec * 4 >= pages_cap (the wrapper below picks it).
+template <int NT, bool COHERENT, int kVec>
+__device__ __forceinline__ void pick_from_scores_n(const CacheView& c, const SelectArgs& a, int unit, int n,
+                                                   PickShared<NT>& sh) {
   constexpr int NB = 1024, BPT = NB / NT, CAP = 1024;
   static_assert(kVec >= 1 && NB % NT == 0, "thread count does not fit the pick");
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
@@ -402,7 +402,6 @@ __device__ __forceinline__ void pick_from_scores(const CacheView& c, const Selec
       if (live && pg >= P - a.n_recent) sc = INFINITY;
       key[i * 4 + e] = f32_order_key(sc);
       if (live) {
-        keys[pg] = key[i * 4 + e];
         if (fabsf(sc) < INFINITY) {
           lo = fminf(lo, sc);
           hi = fmaxf(hi, sc);
@@ -493,10 +492,42 @@ __device__ __forceinline__ void pick_from_scores(const CacheView& c, const Selec
       }
     }
     if (!decided) {
+      // four 8-bit radix passes over the keys in registers (same scan as radix_threshold)
       __syncthreads();
       for (int i = tid; i < 4 * 256; i += NT) hist[i] = 0;
       __syncthreads();
-      radix_threshold<NT>(keys, P, kp, sh.hist, tau, need_eq);
+      uint32_t prefix = 0, mask = 0, k = (uint32_t)kp;
+      for (int pass = 0; pass < 4; ++pass) {
+        const int shift = 24 - 8 * pass;
+#pragma unroll
+        for (int r = 0; r < kVec * 4; ++r)
+          if (is_live(r) && (key[r] & mask) == prefix) atomicAdd(&sh.hist[pass][(key[r] >> shift) & 255u], 1u);
+        __syncthreads();
+        const int b0 = 4 * (kWave - 1 - lane);
+        const uint4 h = *reinterpret_cast<const uint4*>(&sh.hist[pass][b0]);
+        const uint32_t s3 = h.w, s2 = h.z + s3, s1 = h.y + s2, s0 = h.x + s1;
+        const uint32_t above = wave_incl_scan(s0) - s0;
+        const uint32_t in[4] = {above + s0, above + s1, above + s2, above + s3};
+        const uint32_t hc[4] = {h.x, h.y, h.z, h.w};
+        int found = -1;
+        uint32_t newk = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const uint32_t exc = in[j] - hc[j];
+          if (exc < k && k <= in[j]) {
+            found = b0 + j;
+            newk = k - exc;
+          }
+        }
+        const unsigned long long who = __ballot(found >= 0);
+        const int src = __ffsll((long long)who) - 1;
+        const uint32_t bucket = (uint32_t)__builtin_amdgcn_readlane(found, src);
+        k = (uint32_t)__builtin_amdgcn_readlane((int)newk, src);
+        prefix |= bucket << shift;
+        mask |= 0xffu << shift;
+      }
+      tau = prefix;
+      need_eq = k;
       __syncthreads();
     }
   }
@@ -532,6 +563,20 @@ __device__ __forceinline__ void pick_from_scores(const CacheView& c, const Selec
       if (key[r] > tau) ++gt;
     }
   }
+}
+
+// The pick with the per-thread run sized to the cache (instruction count follows the unrolled run
+// length, so a short cache must not pay for the longest one).
+template <int NT, bool COHERENT = false>
+__device__ __forceinline__ void pick_from_scores(const CacheView& c, const SelectArgs& a, int unit, int n,
+                                                 PickShared<NT>& sh) {
+  constexpr int kMaxVec = ROCKETKV_MAX_PAGES / 4 / NT;
+  static_assert(kMaxVec >= 1, "thread count does not fit the pick");
+  const int per = (c.pages_cap / 4 + NT - 1) / NT;  // same for every thread
+  if (per <= 1) pick_from_scores_n<NT, COHERENT, 1>(c, a, unit, n, sh);
+  else if (per <= 2 || kMaxVec < 4) pick_from_scores_n<NT, COHERENT, (kMaxVec < 2 ? kMaxVec : 2)>(c, a, unit, n, sh);
+  else if (per <= 4 || kMaxVec < 8) pick_from_scores_n<NT, COHERENT, (kMaxVec < 4 ? kMaxVec : 4)>(c, a, unit, n, sh);
+  else pick_from_scores_n<NT, COHERENT, kMaxVec>(c, a, unit, n, sh);
 }
 
 // Page scores of the eight-page runs [o_begin, o_begin + n_runs) of one unit, n_runs <= NT, written as

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "librocketkv.so")
 
 OK, INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, HIP_ERROR = 0, -1, -2, -3, -4
 OP_HSA_DECODE, OP_DENSE_DECODE, OP_SNAPKV, OP_ATTEND = 0, 1, 2, 3
-MAX_PAGES = 8192
+MAX_PAGES = 32768
 V_CHANNEL_MAJOR, V_TOKEN_MAJOR = 0, 1
 
 EXPORTS = [

@@ -278,6 +278,7 @@ DECODE_CASES = [
     ("llama8b_step_b16", dict(batch=4, context=4096, n_layers=1), None, 0, False),   # compacted shape of the bench
     ("llama70b_step_b16", dict(batch=2, context=4096, n_layers=1, heavy_nats=2.0), None, 0, False),
     ("mistral_snap_128k", dict(context=8448), None, 1, False),                 # decode shape after SnapKV + 256 steps
+    ("tiny", dict(n_q_heads=8, n_kv_heads=2, context=140000, token_budget=2048, n_heavy=32), None, 0, False),  # > 8192 pages
 ]
 
 

@@ -163,6 +163,7 @@ DECODE_TM = [
     (3, 76, 8192, dict(context=700), None, 0),                                             # budget covers all
     (8, 32, 512, dict(n_q_heads=64, n_kv_heads=8, context=3000, n_heavy=0), None, 0),      # G = 8
     (1, 4, 4000, dict(context=8000, n_heavy=20), None, 0),   # list too long for LDS: separate launches
+    (1, 16, 500, dict(context=12000, n_heavy=10), None, 0),  # more than 8192 pages: scores through the workspace
 ]
 
 
