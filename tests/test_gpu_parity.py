@@ -189,6 +189,7 @@ ATTEND_CASES = [
     ("tiny", dict(n_q_heads=4, n_kv_heads=4, context=777, n_heavy=3), None, False),      # MHA, G = 1
     ("tiny", dict(n_q_heads=32, n_kv_heads=2, context=2048, heavy_nats=1.0), None, True),  # G = 16
     ("llama70b_step_b16", dict(batch=2, context=3000, n_layers=1, n_heavy=0), None, False),  # G = 8
+    ("tiny", dict(n_q_heads=12, n_kv_heads=2, context=1111, n_heavy=3), None, True),          # G = 6
 ]
 
 
@@ -278,6 +279,8 @@ DECODE_CASES = [
     ("llama8b_step_b16", dict(batch=4, context=4096, n_layers=1), None, 0, False),   # compacted shape of the bench
     ("llama70b_step_b16", dict(batch=2, context=4096, n_layers=1, heavy_nats=2.0), None, 0, False),
     ("mistral_snap_128k", dict(context=8448), None, 1, False),                 # decode shape after SnapKV + 256 steps
+    ("tiny", dict(batch=2, n_q_heads=12, n_kv_heads=2, context=2222, token_budget=300), None, 0, True),   # G = 6
+    ("tiny", dict(batch=2, n_q_heads=21, n_kv_heads=3, context=1500, token_budget=128), None, 1, False),  # G = 7
     ("tiny", dict(n_q_heads=8, n_kv_heads=2, context=140000, token_budget=2048, n_heavy=32), None, 0, False),  # > 8192 pages
 ]
 

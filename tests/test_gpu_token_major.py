@@ -162,6 +162,7 @@ DECODE_TM = [
     (4, 72, 200, dict(n_q_heads=8, n_kv_heads=8, context=2000), None, 2),                  # MHA
     (3, 76, 8192, dict(context=700), None, 0),                                             # budget covers all
     (8, 32, 512, dict(n_q_heads=64, n_kv_heads=8, context=3000, n_heavy=0), None, 0),      # G = 8
+    (5, 48, 200, dict(batch=2, n_q_heads=12, n_kv_heads=4, context=1700), None, 0),        # G = 3
     (1, 4, 4000, dict(context=8000, n_heavy=20), None, 0),   # list too long for LDS: separate launches
     (1, 16, 500, dict(context=12000, n_heavy=10), None, 0),  # more than 8192 pages: scores through the workspace
 ]
