@@ -188,8 +188,6 @@ const char* rocketkv_last_error(void) { return g_err; }
 
 int32_t rocketkv_version(void) { return 100; }
 
-// Internal tuning hook for experiments: wavefronts per workgroup, page pairs per wavefront and the
-// workgroup cap of the attention split (0 keeps a value).  Not part of the documented interface.
 void rocketkv_tune_attend(int32_t waves, int32_t pairs_per_wave, int32_t max_wgs) {
   tune_attend(waves, pairs_per_wave, max_wgs);
 }

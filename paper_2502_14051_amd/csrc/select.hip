@@ -142,8 +142,13 @@ __global__ __launch_bounds__(kPickThreads) void hsa_pick_kernel(CacheView c, Sel
   pick_from_scores<kPickThreads>(c, a, unit, n, sh);
 }
 
+// Picked summary rows of this size or more per (sequence, KV head) are streamed by several workgroups:
+// one workgroup reads them at about 11 GB/s, i.e. 128 KiB already costs it some 12 us.
+constexpr int64_t kSplitSummaryBytes = 128 * 1024;
+
 bool select_wants_split(const CacheView& c, int k1) {
-  return c.pages_cap > kSingleSelectPages || (int64_t)k1 * c.pages_cap * (int64_t)sizeof(bf16_t) >= 128 * 1024;
+  return c.pages_cap > kSingleSelectPages ||
+         (int64_t)k1 * c.pages_cap * (int64_t)sizeof(bf16_t) >= kSplitSummaryBytes;
 }
 
 hipError_t launch_hsa_select(const CacheView& c, const SelectArgs& a, hipStream_t st) {

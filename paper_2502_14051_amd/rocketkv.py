@@ -26,7 +26,7 @@ EXPORTS = [
     "rocketkv_attend", "rocketkv_hsa_decode", "rocketkv_hsa_decode_append", "rocketkv_dense_decode", "rocketkv_append_kv",
     "rocketkv_snapkv_compress", "rocketkv_decompose", "rocketkv_last_error", "rocketkv_version",
     "rocketkv_snapkv_filter", "rocketkv_mt_build_page_summaries", "rocketkv_mt_workspace_bytes", "rocketkv_mt_hsa_decode",
-    "rocketkv_mt_append_kv", "rocketkv_mt_hsa_decode_append",
+    "rocketkv_mt_append_kv", "rocketkv_mt_hsa_decode_append", "rocketkv_tune_attend",
 ]
 
 
