@@ -52,6 +52,9 @@ def parse():
     ap.add_argument("--tune", type=str, default="", help="waves,pairs_per_wave override of the attention split")
     ap.add_argument("--no-decomposed", action="store_true",
                     help="skip the secondary measurement at the operating point of the adaptive decomposition")
+    ap.add_argument("--q-variants", type=int, default=4,
+                    help="distinct query sets cycled over the timed steps, so that consecutive steps pick "
+                         "different pages (1..window)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (a known-size reference "
                          "for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
@@ -96,6 +99,7 @@ def main():
     room_pages = (total_steps + ps - 1) // ps + 1
     pages_cap = (N // ps + room_pages + 7) // 8 * 8
     n_dense = min(args.dense_layers, w.n_layers)
+    n_var = max(1, min(args.q_variants, W))
 
     # ------------------------------------------------------------------ set-up (untimed)
     t_setup = time.time()
@@ -121,7 +125,10 @@ def main():
         gen.manual_seed(77_000 + layer)
         new_k = torch.randn((B, Hkv, D), generator=gen, device=dev).bfloat16()
         new_v = torch.randn((B, Hkv, D), generator=gen, device=dev).bfloat16()
-        L = dict(cache=dst, kmax=kmax, kmin=kmin, q=d["q"].contiguous(), new_k=new_k, new_v=new_v,
+        # query sets of later steps: rows of the observation window, i.e. the layer's q plus fresh
+        # noise of the same per-channel scales (consecutive decode queries are correlated, not equal)
+        qv = [d["q"].contiguous()] + [d["qobs"][:, :, W - j, :].contiguous() for j in range(1, n_var)]
+        L = dict(cache=dst, kmax=kmax, kmin=kmin, q=qv[0], qv=qv, new_k=new_k, new_v=new_v,
                  out=torch.empty((B, Hq, D), dtype=torch.bfloat16, device=dev),
                  ws=rk.alloc_workspace(rk.OP_HSA_DECODE, dst, T))
         layers.append(L)
@@ -147,40 +154,47 @@ def main():
 
     # Every step appends one new key/value row per layer.  The rows are fixed synthetic buffers (their
     # values do not change the work done), so a captured step can be replayed as is.
-    def one_step():
+    # Step i runs with query set i mod n_var (one captured graph per set), so the pages picked change
+    # from step to step as they do in a real decode.
+    def one_step(v=0):
         for L in layers:
-            rk.hsa_decode_append(L["cache"], L["q"], L["new_k"], L["new_v"], L["kmax"], L["kmin"], k1, T, 0,
+            rk.hsa_decode_append(L["cache"], L["qv"][v], L["new_k"], L["new_v"], L["kmax"], L["kmin"], k1, T, 0,
                                  L["out"], None, None, None, L["ws"], stream)
 
-    graph = None
+    graphs = []
     with torch.cuda.stream(stream):
         one_step()  # eager once: surfaces launch errors before capture
         stream.synchronize()
         if not args.no_graph:
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph, stream=stream):
-                one_step()
+            for v in range(n_var):
+                g_ = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g_, stream=stream):
+                    one_step(v)
+                graphs.append(g_)
+    graph = graphs[0] if graphs else None
 
-        def run_step():
-            if graph is not None:
-                graph.replay()
+    with torch.cuda.stream(stream):
+        def run_step(i):
+            if graphs:
+                graphs[i % n_var].replay()
             else:
-                one_step()
+                one_step(i % n_var)
 
-        for _ in range(args.warmup):
-            run_step()
+        for i in range(args.warmup):
+            run_step(i)
         stream.synchronize()
         torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
         t0 = time.perf_counter()
-        e0.record(stream)
-        for _ in range(args.steps):
-            run_step()
-        e1.record(stream)
+        marks[0].record(stream)
+        for i in range(args.steps):
+            run_step(args.warmup + i)
+            marks[i + 1].record(stream)
         stream.synchronize()
         torch.cuda.synchronize()
         wall_ms = (time.perf_counter() - t0) * 1e3
-    dev_ms = e0.elapsed_time(e1)
+    dev_ms = marks[0].elapsed_time(marks[-1])
+    per_step_ms = np.array([marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps)])
     ms_per_step = max(dev_ms, 0.0) / args.steps
     us_layer = ms_per_step * 1e3 / w.n_layers
     n_now = int(layers[0]["cache"].seq_lens[0].item())
@@ -246,6 +260,19 @@ def main():
             rk.dense_decode(Ld["cache"], Ld["q"], Ld["out"], None, Ld["ws"], stream)
 
     dense_us = timed_graph(dense_all, max(3, args.kernel_reps // 4)) * 1e3 / max(1, n_dense)
+
+    # measured read ceiling: a plain streaming read of the same uncompressed pools (2 GiB per layer)
+    read_gbs = None
+    if n_dense > 0:
+        sink = torch.empty((rk.lib().rocketkv_stream_read_sink_bytes(),), dtype=torch.uint8, device=dev)
+        pools = [t for Ld in dense_layers for t in (Ld["cache"].k_pool, Ld["cache"].v_pool)]
+
+        def read_all():
+            for t in pools:
+                rk.stream_read(t, sink, stream)
+
+        read_ms = timed_graph(read_all, 3)
+        read_gbs = sum(t.numel() * t.element_size() for t in pools) / (read_ms * 1e-3) / 1e9
 
     # The secondary measurements below run over at least eight layers each, so that a replay touches
     # several times the 256 MB of last-level cache and every launch reads from HBM as in a full model.
@@ -418,6 +445,8 @@ def main():
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step_median": round(float(np.median(per_step_ms)), 4),
+        "ms_per_step_min": round(float(per_step_ms.min()), 4),
         "higher_is_better": False,
         "scaling": "weak",
         "vs_baseline": None,
@@ -426,7 +455,7 @@ def main():
         "config": {"workload": f"llama8b_step_b16: {w.n_layers} layers x (32q/8kv heads, d128), batch {B}, "
                                f"ctx {w.context} -> SnapKV {N} (+{n_now - N} appended), HSA budget {T}, "
                                f"page {ps}, k1 {k1}",
-                   "graph": graph is not None},
+                   "graph": graph is not None, "query_sets_cycled": n_var},
         "decode_tokens_per_s_attention_only": round(B / (ms_per_step * 1e-3), 1),
         "hsa_achieved_GBs": round(hsa_gbs, 1),
         "hsa_frac_of_hbm_peak": round(hsa_gbs / HBM_PEAK_GBS, 4),
@@ -442,10 +471,13 @@ def main():
                                "attend_only_GBs": round(att_gbs, 1)},
         # the step is one launch of the fused kernel per layer, so its average launch time is the
         # timed region divided by the number of launches
-        "roofline": {"bound": "hbm", "kernel": "hsa_decode_kernel<8, true>", "achieved": round(hsa_gbs, 1),
+        "roofline": {"bound": "hbm", "kernel": "hsa_decode_kernel<8, true, true>", "achieved": round(hsa_gbs, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(hsa_gbs / HBM_PEAK_GBS, 4),
                      "traffic": TRAFFIC_BYTES_PER_LAUNCH, "us_per_launch": round(us_layer, 3),
-                     "bytes_per_launch": hsa_bytes},
+                     "bytes_per_launch": hsa_bytes,
+                     # what a plain streaming read reaches on this GPU, and the fraction of that
+                     "measured_read_GBs": None if read_gbs is None else round(read_gbs, 1),
+                     "frac_of_measured_read": None if read_gbs is None else round(hsa_gbs / read_gbs, 4)},
         "decomposed_operating_point": dec_pt,
         "multi_turn_variant": mt_pt,
         "single_layer_batch1": single,

@@ -350,6 +350,16 @@ int32_t rocketkv_decompose(int64_t seq_len, int32_t token_budget, int32_t head_d
  */
 void rocketkv_tune_attend(int32_t waves, int32_t pairs_per_wave, int32_t max_wgs);
 
+/*
+ * Measurement aid (no step of the method): read `bytes` (a multiple of 16) of device memory at
+ * `src` (16-byte aligned) once, front to back, with plain streaming loads, and write one checksum
+ * word per wavefront to `sink` (device, at least rocketkv_stream_read_sink_bytes() bytes).  Timed
+ * over a buffer much larger than the 256 MB last-level cache it gives the read bandwidth this GPU
+ * actually reaches, which the benchmark prints beside the published peak.  Asynchronous on `stream`.
+ */
+int32_t rocketkv_stream_read(const void* src, size_t bytes, void* sink, void* stream);
+size_t rocketkv_stream_read_sink_bytes(void);
+
 /* Thread-local description of the last error returned on this thread ("" if none). */
 const char* rocketkv_last_error(void);
 

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librocketkv.so")
-SOURCES = ["api.hip", "summaries.hip", "select.hip", "attend.hip", "attend_tok.hip", "decode.hip", "decode_tok.hip", "snapkv.hip"]
+SOURCES = ["api.hip", "summaries.hip", "select.hip", "attend.hip", "attend_tok.hip", "decode.hip", "decode_tok.hip", "snapkv.hip", "probe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC, "-Wall", "-Wno-unused-function"]

@@ -410,6 +410,19 @@ int32_t rocketkv_append_kv(const rocketkv_cache_t* cache, const void* k_new, con
   return e == hipSuccess ? ROCKETKV_OK : hip_fail(e, who);
 }
 
+size_t rocketkv_stream_read_sink_bytes(void) { return (size_t)probe_read_workgroups() * 4 * sizeof(uint32_t); }
+
+int32_t rocketkv_stream_read(const void* src, size_t bytes, void* sink, void* stream) {
+  g_err[0] = 0;
+  const char* who = "rocketkv_stream_read";
+  if (!src || !sink) return fail(ROCKETKV_INVALID_ARG, "%s: src / sink must not be NULL", who);
+  if ((bytes & 15) || ((uintptr_t)src & 15))
+    return fail(ROCKETKV_INVALID_ARG, "%s: src and bytes must be multiples of 16", who);
+  if (bytes == 0) return ROCKETKV_OK;
+  const hipError_t e = launch_stream_read(src, bytes, static_cast<uint32_t*>(sink), static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? ROCKETKV_OK : hip_fail(e, who);
+}
+
 int32_t rocketkv_snapkv_compress(const void* q_obs, const rocketkv_cache_t* src, int32_t window,
                                  int32_t pool_kernel, int32_t keep_budget,
                                  const rocketkv_cache_t* dst, int32_t* kept_idx, void* workspace,

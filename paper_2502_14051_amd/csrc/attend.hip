@@ -6,7 +6,7 @@
 
 namespace rkv {
 
-template <int WAVES, int NP>
+template <int WAVES, int NP, bool STREAM_K>
 __global__ __launch_bounds__(WAVES* kWave) __attribute__((amdgpu_waves_per_eu(2)))
 void attend_mfma_kernel(CacheView c, AttendArgs a) {
   extern __shared__ float smem[];  // sO[WAVES][G][128], sM[WAVES][G], sL[WAVES][G]
@@ -15,7 +15,7 @@ void attend_mfma_kernel(CacheView c, AttendArgs a) {
   const int n = c.seq_lens[unit / c.n_kv_heads];
   const int32_t* list = a.pages ? a.pages + (int64_t)unit * a.row_len : nullptr;
   const TailPatch none = {-1, 0, nullptr, nullptr};
-  attend_block<WAVES, NP>(c, a, unit, split, n, list, smem, &s_last, none);
+  attend_block<WAVES, NP, STREAM_K>(c, a, unit, split, n, list, smem, &s_last, none);
 }
 
 __global__ void zero_u32_kernel(uint32_t* p, int n) {
@@ -98,13 +98,17 @@ hipError_t launch_attend(const CacheView& c, const bf16_t* q, const int32_t* pag
   a.n_split = plan.n_split;
   a.chunk = plan.chunk;
   a.per_wave = plan.per_wave;
-  (void)units;
   const size_t smem = (size_t)plan.waves * c.group * (kHeadDim + 2) * sizeof(float);
   const dim3 grid(plan.n_split, units);
-  if (plan.waves == 8)
-    hipLaunchKernelGGL((attend_mfma_kernel<8, 1>), grid, dim3(8 * kWave), smem, st, c, a);
-  else
-    hipLaunchKernelGGL((attend_mfma_kernel<4, 1>), grid, dim3(4 * kWave), smem, st, c, a);
+  const bool stream_k = pages != nullptr && wants_stream_k(c, row_len);  // a large gather, not the dense read
+#define RKV_LAUNCH_ATTEND(W, S) \
+  hipLaunchKernelGGL((attend_mfma_kernel<W, 1, S>), grid, dim3(W * kWave), smem, st, c, a)
+  if (plan.waves == 8) {
+    if (stream_k) RKV_LAUNCH_ATTEND(8, true); else RKV_LAUNCH_ATTEND(8, false);
+  } else {
+    if (stream_k) RKV_LAUNCH_ATTEND(4, true); else RKV_LAUNCH_ATTEND(4, false);
+  }
+#undef RKV_LAUNCH_ATTEND
   return hipGetLastError();
 }
 

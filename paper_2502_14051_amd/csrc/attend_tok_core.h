@@ -223,12 +223,12 @@ __device__ __forceinline__ void attend_tokens_block(const CacheView& c, const At
         const bf16_t* kt = c.k_pool + lane_off + ofx;
         vt[x] = c.v_pool + lane_off + ofx;
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) kf[x][jj] = *reinterpret_cast<const u32x4*>(kt + jj * 32);
+        for (int jj = 0; jj < 4; ++jj) kf[x][jj] = ld_plain<u32x4>(kt + jj * 32);
       }
 #pragma unroll
       for (int x = 0; x < 2; ++x)
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) vr[x][jj] = *reinterpret_cast<const u32x4*>(vt[x] + jj * 32);
+        for (int jj = 0; jj < 4; ++jj) vr[x][jj] = ld_stream<u32x4>(vt[x] + jj * 32);
       const uint32_t bits = (uint32_t)(live >> (32 * i));
       const uint32_t nbits = (uint32_t)(fresh >> (32 * i));
       if (bits == 0xffffffffu && nbits == 0u) {

@@ -19,6 +19,18 @@ typedef uint16_t bf16_t;           // raw bf16 bits
 __device__ __forceinline__ float bf16_to_f32(bf16_t b) {
   return __uint_as_float(((uint32_t)b) << 16);
 }
+// 16-byte load; STREAM marks data that is read once per launch (streaming hint: it does not displace
+// what the caches hold for reuse, and large one-pass reads measure about a tenth faster with it)
+typedef uint32_t raw_u32x4 __attribute__((ext_vector_type(4)));
+template <bool STREAM>
+__device__ __forceinline__ uint4 ld16(const void* p) {
+  if (STREAM) {
+    const raw_u32x4 v = __builtin_nontemporal_load(static_cast<const raw_u32x4*>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+  }
+  return *static_cast<const uint4*>(p);
+}
+
 __device__ __forceinline__ float bf16lo_to_f32(uint32_t pair) { return __uint_as_float(pair << 16); }
 __device__ __forceinline__ float bf16hi_to_f32(uint32_t pair) { return __uint_as_float(pair & 0xffff0000u); }
 
@@ -162,6 +174,9 @@ hipError_t launch_hsa_decode_fused(const CacheView& c, const SelectArgs& sa, con
                                    bf16_t* out, float* out_lse, void* ws, const AttendPlan& plan,
                                    hipStream_t st);
 uint32_t* attend_counters(void* ws, const AttendPlan& plan);
+// measurement aid: one streaming read of a buffer; `sink` holds a word per wavefront launched
+int probe_read_workgroups();
+hipError_t launch_stream_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t st);
 
 hipError_t launch_append(const CacheView& c, const bf16_t* k_new, const bf16_t* v_new, bf16_t* kmax,
                          bf16_t* kmin, hipStream_t st);

@@ -21,7 +21,7 @@ __host__ __device__ constexpr size_t round16(size_t x) { return (x + 15) / 16 * 
 constexpr size_t kStageBytes = 2 * kHeadDim * sizeof(bf16_t);  // staged new key and value
 constexpr size_t kSeqCounterOff = ROCKETKV_WS_HEADER_BYTES / 2;  // per-sequence arrival counters
 
-template <int WAVES, bool APPEND>
+template <int WAVES, bool APPEND, bool STREAM_K>
 __global__ __launch_bounds__(WAVES* kWave) __attribute__((amdgpu_waves_per_eu(2)))
 void hsa_decode_kernel(CacheView c, SelectArgs sa, AttendArgs aa, AppendArgs ap, uint32_t* seq_counters) {
   constexpr int NT = WAVES * kWave;
@@ -99,7 +99,7 @@ void hsa_decode_kernel(CacheView c, SelectArgs sa, AttendArgs aa, AppendArgs ap,
       if (tp.slot == 0 || x < bf16_to_f32(old_min)) ap.kmin[sum_off] = kb;
     }
   };
-  attend_block<WAVES, 1>(c, aa, unit, split, n, list, reinterpret_cast<float*>(region), &s_last, tp, write_back);
+  attend_block<WAVES, 1, STREAM_K>(c, aa, unit, split, n, list, reinterpret_cast<float*>(region), &s_last, tp, write_back);
 
   if (APPEND) {
     // the last workgroup of the sequence to have read the old length stores the new one
@@ -139,17 +139,18 @@ hipError_t launch_hsa_decode_fused(const CacheView& c, const SelectArgs& sa, con
   const size_t smem = fused_decode_lds_bytes(c, sa.row_len, plan);
   const dim3 grid(c.batch * c.n_kv_heads, plan.n_split);
   const bool append = ap.k_new != nullptr;
+  const bool stream_k = wants_stream_k(c, sa.row_len);
+#define RKV_LAUNCH_DECODE(W, A, S) \
+  hipLaunchKernelGGL((hsa_decode_kernel<W, A, S>), grid, dim3(W * kWave), smem, st, c, sa, a, ap, seq_counters)
+#define RKV_LAUNCH_DECODE_S(W, A) \
+  do { if (stream_k) RKV_LAUNCH_DECODE(W, A, true); else RKV_LAUNCH_DECODE(W, A, false); } while (0)
   if (plan.waves == 8) {
-    if (append)
-      hipLaunchKernelGGL((hsa_decode_kernel<8, true>), grid, dim3(8 * kWave), smem, st, c, sa, a, ap, seq_counters);
-    else
-      hipLaunchKernelGGL((hsa_decode_kernel<8, false>), grid, dim3(8 * kWave), smem, st, c, sa, a, ap, seq_counters);
+    if (append) RKV_LAUNCH_DECODE_S(8, true); else RKV_LAUNCH_DECODE_S(8, false);
   } else {
-    if (append)
-      hipLaunchKernelGGL((hsa_decode_kernel<4, true>), grid, dim3(4 * kWave), smem, st, c, sa, a, ap, seq_counters);
-    else
-      hipLaunchKernelGGL((hsa_decode_kernel<4, false>), grid, dim3(4 * kWave), smem, st, c, sa, a, ap, seq_counters);
+    if (append) RKV_LAUNCH_DECODE_S(4, true); else RKV_LAUNCH_DECODE_S(4, false);
   }
+#undef RKV_LAUNCH_DECODE_S
+#undef RKV_LAUNCH_DECODE
   return hipGetLastError();
 }
 

@@ -47,6 +47,7 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* wsum) 
 }
 
 // accumulate eight rows' worth of eight-page runs; every load of the batch is issued before use
+template <bool STREAM = false>
 __device__ __forceinline__ void score_rows8(const SelectArgs& a, const int* s_chan, const float* s_wgt,
                                             int64_t rows, int pages_cap, int o, int j0, int jstep,
                                             const TailPatch& tp, float (&acc)[8]) {
@@ -60,7 +61,7 @@ __device__ __forceinline__ void score_rows8(const SelectArgs& a, const int* s_ch
     if (j < a.k1) {
       w[t] = s_wgt[j];
       const bf16_t* row = (w[t] >= 0.f ? a.kmax : a.kmin) + (rows + s_chan[j]) * pages_cap + o * 8;
-      v[t] = *reinterpret_cast<const uint4*>(row);
+      v[t] = ld16<STREAM>(row);
     }
   }
   if (tp.page >= 0 && o == (tp.page >> 3)) {
@@ -597,8 +598,8 @@ __device__ __forceinline__ void score_chunk(const CacheView& c, const SelectArgs
 #pragma unroll
   for (int i = 0; i < 8; ++i) acc[i] = 0.f;
   if (o < n_runs)
-    for (int j0 = r; j0 < a.k1; j0 += 8 * R)
-      score_rows8(a, sh.s_chan, sh.s_wgt, rows, c.pages_cap, o_begin + o, j0, R, tp, acc);
+    for (int j0 = r; j0 < a.k1; j0 += 8 * R)  // each slice of the rows has this one reader: streamed
+      score_rows8<true>(a, sh.s_chan, sh.s_wgt, rows, c.pages_cap, o_begin + o, j0, R, tp, acc);
 #pragma unroll
   for (int i = 0; i < 8; ++i) sh.partial[(r * npow + o) * 8 + i] = acc[i];
   __syncthreads();

@@ -103,7 +103,7 @@ void snap_score_kernel(CacheView c, SnapArgs a) {
     const int64_t pp = p < p_end ? phys_page(c, b, p) : -1;
     const bf16_t* kt = c.k_pool + (pp >= 0 ? pp : 0) * c.stride_page + lane_off;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) kf[j] = *reinterpret_cast<const uint4*>(kt + j * 32);
+    for (int j = 0; j < 4; ++j) kf[j] = ld16<false>(kt + j * 32);
     return pp >= 0;
   };
   const int n_it = p_end > p_begin ? (p_end - p_begin + npw - 1) / npw : 0;
@@ -441,8 +441,7 @@ __global__ __launch_bounds__(256) void snap_gather_kernel(CacheView src, CacheVi
   {
     uint4 val = make_uint4(0, 0, 0, 0);
     if (row_live)
-      val = *reinterpret_cast<const uint4*>(src.k_pool + spp * src.stride_page + shead +
-                                            (tok % kAttnPage) * kHeadDim + piece * 8);
+      val = ld16<false>(src.k_pool + spp * src.stride_page + shead + (tok % kAttnPage) * kHeadDim + piece * 8);
     // a channel-major destination gets whole tiles (zero rows past the end); a token-major one only
     // the rows that exist, as later pages may belong to something else
     if (dpp >= 0 && (tok >= 0 || !dst.v_token_major))
@@ -453,16 +452,14 @@ __global__ __launch_bounds__(256) void snap_gather_kernel(CacheView src, CacheVi
     if (row_live && dpp >= 0)
       *reinterpret_cast<uint4*>(dst.v_pool + dpp * dst.stride_page + dhead + (dt % dps) * kHeadDim +
                                 piece * 8) =
-          *reinterpret_cast<const uint4*>(src.v_pool + spp * src.stride_page + shead +
-                                          (tok % kAttnPage) * kHeadDim + piece * 8);
+          ld16<false>(src.v_pool + spp * src.stride_page + shead + (tok % kAttnPage) * kHeadDim + piece * 8);
     return;
   }
   // stage V as s_v[channel][token]
   if (src.v_token_major) {
     uint4 val = make_uint4(0, 0, 0, 0);
     if (row_live)
-      val = *reinterpret_cast<const uint4*>(src.v_pool + spp * src.stride_page + shead +
-                                            (tok % kAttnPage) * kHeadDim + piece * 8);
+      val = ld16<false>(src.v_pool + spp * src.stride_page + shead + (tok % kAttnPage) * kHeadDim + piece * 8);
     const uint32_t w[4] = {val.x, val.y, val.z, val.w};
 #pragma unroll
     for (int i = 0; i < 4; ++i) {

@@ -45,7 +45,7 @@ __global__ __launch_bounds__(256) void page_summaries_kernel(CacheView c, bf16_t
         uint4 v[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u)
-          v[u] = *reinterpret_cast<const uint4*>(tile + min(t0 + u, ntok - 1) * kHeadDim);  // a repeat is harmless
+          v[u] = ld16<true>(tile + min(t0 + u, ntok - 1) * kHeadDim);  // read once: streamed; a repeat is harmless
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
           const uint32_t w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
@@ -169,8 +169,7 @@ __global__ __launch_bounds__(256) void page_summaries_indexed_kernel(CacheView c
       const int64_t pp = (pos >= 0 && sp < c.pages_cap) ? phys_page(c, b, sp) : -1;
       if (pp < 0) continue;  // a token whose cache page is absent contributes nothing
       any = true;
-      const uint4 v = *reinterpret_cast<const uint4*>(c.k_pool + pp * c.stride_page +
-                                                      (int64_t)g * c.stride_head + ss * kHeadDim + cl * 8);
+      const uint4 v = ld16<true>(c.k_pool + pp * c.stride_page + (int64_t)g * c.stride_head + ss * kHeadDim + cl * 8);
       const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
       for (int i = 0; i < 4; ++i) {

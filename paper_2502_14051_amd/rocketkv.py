@@ -27,6 +27,7 @@ EXPORTS = [
     "rocketkv_snapkv_compress", "rocketkv_decompose", "rocketkv_last_error", "rocketkv_version",
     "rocketkv_snapkv_filter", "rocketkv_mt_build_page_summaries", "rocketkv_mt_workspace_bytes", "rocketkv_mt_hsa_decode",
     "rocketkv_mt_append_kv", "rocketkv_mt_hsa_decode_append", "rocketkv_tune_attend",
+    "rocketkv_stream_read", "rocketkv_stream_read_sink_bytes",
 ]
 
 
@@ -120,6 +121,10 @@ def lib():
         L.rocketkv_version.argtypes = []
         L.rocketkv_tune_attend.restype = None
         L.rocketkv_tune_attend.argtypes = [i32, i32, i32]
+        L.rocketkv_stream_read.restype = i32
+        L.rocketkv_stream_read.argtypes = [vp, C.c_size_t, vp, vp]
+        L.rocketkv_stream_read_sink_bytes.restype = C.c_size_t
+        L.rocketkv_stream_read_sink_bytes.argtypes = []
         _lib = L
     return _lib
 
@@ -431,3 +436,14 @@ def pages_row_len(cache: Cache, token_budget: int) -> int:
 
 def tune_attend(waves: int = 0, pairs_per_wave: int = 0, max_wgs: int = 0):
     lib().rocketkv_tune_attend(waves, pairs_per_wave, max_wgs)
+
+
+def stream_read(buf, sink=None, stream=None):
+    """Measurement aid: one streaming read of the whole tensor ``buf`` (see rocketkv_stream_read)."""
+    import torch
+
+    nbytes = buf.numel() * buf.element_size()
+    if sink is None:
+        sink = torch.empty((lib().rocketkv_stream_read_sink_bytes(),), dtype=torch.uint8, device=buf.device)
+    _check(lib().rocketkv_stream_read(_ptr(buf), nbytes, _ptr(sink), _stream(stream)))
+    return sink
