@@ -352,6 +352,7 @@ struct PickShared {
 // COHERENT: the scores were written earlier in the SAME launch by other workgroups (with device-scope
 // write-through stores): they are read with device-scope loads, which do not trust this XCD's L2.
 // kVec: float4 loads per thread, i.e. NT * kVec * 4 >= pages_cap (the wrapper below picks it).
+// sh.hist must be all zero on entry (the caller clears it, and synchronises, before the call).
 template <int NT, bool COHERENT, int kVec>
 __device__ __forceinline__ void pick_from_scores_n(const CacheView& c, const SelectArgs& a, int unit, int n,
                                                    PickShared<NT>& sh) {

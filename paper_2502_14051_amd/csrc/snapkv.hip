@@ -14,6 +14,8 @@
 #include <type_traits>
 
 #include "common.h"
+#include "select_core.h"
+
 
 namespace rkv {
 
@@ -44,12 +46,49 @@ struct SnapArgs {
 
 __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
 
-template <bool PASS2>
+// sum over the 16 lanes of a DPP row (the lanes that hold the 16 columns of one token group); every
+// lane of the row ends up with the total
+__device__ __forceinline__ float row16_sum(float v) {
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xf, 0xf, true));   // quad_perm 1,0,3,2
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xf, 0xf, true));   // quad_perm 2,3,0,1
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xf, 0xf, true));  // row_half_mirror
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x140, 0xf, 0xf, true));  // row_mirror
+  return v;
+}
+
+// max of three without the input canonicalisation fmaxf() brings along (three extra instructions
+// per call here); the inputs are matrix-core outputs and running maxima, never signalling NaNs
+__device__ __forceinline__ float max3_raw(float x, float y, float w) {
+  float d;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(d) : "v"(x), "v"(y), "v"(w));
+  return d;
+}
+
+__device__ __forceinline__ float max2_raw(float x, float y) {
+  float d;
+  asm("v_max_f32 %0, %1, %2" : "=v"(d) : "v"(x), "v"(y));
+  return d;
+}
+
+__device__ __forceinline__ int64_t readlane64(int64_t v, int l) {
+  return ((int64_t)__builtin_amdgcn_readlane((int)(v >> 32), l) << 32) |
+         (uint32_t)__builtin_amdgcn_readlane((int)(v & 0xffffffff), l);
+}
+
+constexpr int kSnapMaxIters = 2 * kWave;  // pages one wavefront walks in a chunk, at most
+constexpr int kSnapRing = 3;              // key tiles a wavefront keeps in flight (4 KiB of LDS each)
+constexpr size_t kSnapRingBytes = (size_t)4 * kSnapRing * 4 * kWave * 16;  // four wavefronts
+constexpr int kSnapMaxChunkPages = 128;  // pages per workgroup; pass 2 stages their votes in LDS (8 KiB)
+
+// QD: groups of four column blocks every wavefront works through (2 when some wavefront owns more
+// than four blocks with real softmax rows; blocks without any hold zero queries and are discarded).
+template <bool PASS2, int QD>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2)))
 void snap_score_kernel(CacheView c, SnapArgs a) {
   __shared__ float sM[4][kSnapColBlocks * 16], sZ[4][kSnapColBlocks * 16];
   __shared__ float sV[4][16];
-  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+  const int tid = threadIdx.x, lane = tid % kWave;
+  const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);  // scalar: page indices stay in SGPRs
   const int hn = lane % 16, kg = lane / 16;
   const int unit = blockIdx.y, chunk = blockIdx.x;
   const int b = unit / c.n_kv_heads, g = unit % c.n_kv_heads;
@@ -57,17 +96,198 @@ void snap_score_kernel(CacheView c, SnapArgs a) {
   if (S <= a.keep || S > c.pages_cap * kAttnPage) return;
   const int L = S - a.W;
   const int cgi = wave % a.CG, pw = wave / a.CG, npw = 4 / a.CG;
-  // 16-column blocks this wavefront owns that hold real softmax rows (same for all its lanes)
-  const int n_cb = __builtin_amdgcn_readfirstlane(min(kSnapColBlocks, (a.NC + 15) / 16 - cgi * kSnapColBlocks));
   const int p_begin = chunk * a.chunk_pages;
   const int p_limit = PASS2 ? (L + kAttnPage - 1) / kAttnPage : (S + kAttnPage - 1) / kAttnPage;
   const int p_end = min(p_begin + a.chunk_pages, p_limit);
+  const int n_it = p_end > p_begin ? (p_end - p_begin + npw - 1) / npw : 0;  // <= kSnapMaxIters (host)
 
-  FragS qf[kSnapColBlocks][4];
-  int limit[kSnapColBlocks];
-  float M2[kSnapColBlocks], invZ[kSnapColBlocks];
+  // Where this wavefront's pages live: lane i looks up iterations i and i + 64 once, up front, and
+  // the loop hands the tile offsets out by readlane, so it contains no table lookups and no waits
+  // on them.  -1 marks an absent page.
+  int64_t off_lo = -1, off_hi = -1;
+  {
+    const int p0 = p_begin + lane * npw + pw, p1 = p0 + kWave * npw;
+    if (lane < n_it && p0 < p_end) {
+      const int64_t pp = phys_page(c, b, p0);
+      if (pp >= 0) off_lo = pp * c.stride_page;
+    }
+    if (lane + kWave < n_it && p1 < p_end) {
+      const int64_t pp = phys_page(c, b, p1);
+      if (pp >= 0) off_hi = pp * c.stride_page;
+    }
+  }
+
+  constexpr int NCB = 4 * QD;
+  FragS qf[NCB][4];
+  int limit[NCB];
+  float M2[NCB], invZ[NCB];
+  float m[NCB], z[NCB];
 #pragma unroll
-  for (int cb = 0; cb < kSnapColBlocks; ++cb) {
+  for (int cb = 0; cb < NCB; ++cb) { m[cb] = kNegBigS; z[cb] = 0.f; }
+  const float sc = kLog2eS * 0.08838834764831845f;
+  const int64_t head_off = (int64_t)g * c.stride_head;
+
+  // Key tiles travel through a ring of kSnapRing slots of LDS per wavefront, filled by loads that
+  // write LDS directly (no registers are held for tiles in flight, so three of them fit where two
+  // register buffers used to): the tile for iteration it + kSnapRing is requested as soon as the
+  // products of iteration it have consumed the slot.  An absent or out-of-range page reads tile 0
+  // of the pool and is masked below; those loads are issued all the same, which keeps the number
+  // of loads younger than the tile being waited for constant.
+  typedef uint32_t ring_u32x4 __attribute__((ext_vector_type(4)));
+  extern __shared__ __align__(16) unsigned char snap_dyn[];
+  ring_u32x4* ring = reinterpret_cast<ring_u32x4*>(snap_dyn) + wave * (kSnapRing * 4 * kWave);
+  float* s_votes = reinterpret_cast<float*>(snap_dyn + kSnapRingBytes);  // pass 2: [chunk_pages][16]
+  const auto tile_off = [&](int it) -> int64_t {  // `it` is wave-uniform; branch-free
+    const int l = it & (kWave - 1);
+    const int64_t lo = readlane64(off_lo, l), hi = readlane64(off_hi, l);
+    return it >= n_it ? -1 : (it < kWave ? lo : hi);
+  };
+  // Pass 1 loads the keys with the streaming hint (a fifth faster here); pass 2 without, so that the
+  // part of the keys it reads last stays in the last-level cache for the gather that follows (which
+  // measures 20 us slower otherwise, more than the hint gains pass 2).
+  constexpr int kPolicyStream = 2;  // the "nt" bit of the load's cache policy
+  // Load instruction j of a tile brings in token rows 4j .. 4j+3 (1 KiB, whole cache lines); lane l
+  // lands at 16 l bytes into the instruction's KiB of the slot, and fetches the 16-byte chunk that
+  // belongs there: the chunks of a row are stored XOR-swizzled by the row number, so that the reads
+  // below (16 rows at one chunk position) spread over all LDS banks.
+  const int dma_row = lane >> 4;                 // + 4 j
+  const auto issue = [&](int it, int slot) {
+    const int64_t off = tile_off(it);
+    const bf16_t* kt = c.k_pool + (off >= 0 ? off : 0) + head_off;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int row = 4 * j + dma_row;
+      const int chunk = (lane & 15) ^ row;
+      __builtin_amdgcn_global_load_lds(reinterpret_cast<const ring_u32x4*>(kt + row * kHeadDim + chunk * 8),
+                                       ring + (slot * 4 + j) * kWave, 16, 0, PASS2 ? 0 : kPolicyStream);
+    }
+  };
+  // The work of a page is 2 * QD pieces: the products of a group of four column blocks (16 matrix
+  // instructions) and that group's softmax update (plain and transcendental vector instructions).
+  // The kernel is bound by the issue of these, not by memory, and the two kinds run on different
+  // pipes, so the loop is software-pipelined: the products of group n + 1 sit in one scheduling
+  // region with the update of group n (which may belong to the previous page).
+  const auto read_tile = [&](int slot, bf16x8* kf) {
+    // everything but the kSnapRing - 1 younger tiles (four loads each) has landed
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((kSnapRing - 1) * 4) : "memory");
+#pragma unroll
+    for (int j = 0; j < 4; ++j)  // token hn, channels 32 j + 8 kg ..: chunk 4 j + kg of row hn
+      kf[j] = __builtin_bit_cast(bf16x8, ring[slot * 4 * kWave + hn * 16 + ((4 * j + kg) ^ hn)]);
+  };
+  const auto products = [&](const bf16x8* kf, int qd, f32x4* acc) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[j], qf[qd * 4 + i][j].v, acc[i], 0, 0, 0);
+  };
+  // MASKED = false is the hot case, a page that is present and lies wholly inside the prefix, so
+  // every window row sees all of it; it is written for the fewest vector instructions: the softmax
+  // scale goes into the exponent's multiply-add, and the page maximum is taken on the raw products
+  // (the scale is positive).
+  const auto update = [&](auto masked_tag, const f32x4* acc, int qd, bool present, int tok0, float* v) {
+    constexpr bool MASKED = decltype(masked_tag)::value;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int cb = qd * 4 + i;
+      float s[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        s[r] = acc[i][r];
+        if (MASKED) s[r] = (present && tok0 + r <= limit[cb]) ? s[r] : -INFINITY;
+      }
+      if (!PASS2) {
+        // m[] is the running maximum in the log2 domain; an unchanged maximum rescales by exactly 1
+        const float mn = max2_raw(m[cb], max2_raw(max3_raw(s[0], s[1], s[2]), s[3]) * sc);
+        const float e01 = exp2_fast(fmaf(s[0], sc, -mn)) + exp2_fast(fmaf(s[1], sc, -mn));
+        const float e23 = exp2_fast(fmaf(s[2], sc, -mn)) + exp2_fast(fmaf(s[3], sc, -mn));
+        z[cb] = fmaf(z[cb], exp2_fast(m[cb] - mn), e01 + e23);
+        m[cb] = mn;
+      } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) v[r] = fmaf(exp2_fast(fmaf(s[r], sc, -M2[cb])), invZ[cb], v[r]);
+      }
+    }
+  };
+  // votes of one page (already summed over the 16 columns a token group's lanes hold): add the column
+  // groups, stage the result
+  const auto emit_votes = [&](float* v, bool live, int tok0) {
+    if (a.CG == 2) {
+      if (cgi == 1 && hn == 0) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) sV[pw][kg * 4 + r] = v[r];
+      }
+      __syncthreads();
+      if (cgi == 0) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) v[r] += sV[pw][kg * 4 + r];
+      }
+      __syncthreads();
+    }
+    // staged in LDS and written out once per chunk: a global store per page would sit among the
+    // tile loads the wait above counts, and make it wait for more of them than it needs
+    if (live && cgi == 0 && hn == 0)
+      *reinterpret_cast<float4*>(s_votes + (tok0 - p_begin * kAttnPage)) = make_float4(v[0], v[1], v[2], v[3]);
+  };
+  bf16x8 kf[4];
+  f32x4 acc_a[4], acc_b[4];  // acc_a: first group of the page at hand, products already done
+  int slot = 0;
+  // One page: on entry kf holds its tile and acc_a its first group; on exit the same for the next page
+  // (past the end that is a dummy tile whose products nobody looks at).
+  const auto page = [&](auto masked_tag, int it) {
+    constexpr bool MASKED = decltype(masked_tag)::value;
+    const int p = p_begin + it * npw + pw;
+    const bool present = MASKED ? tile_off(it) >= 0 : true;
+    const int tok0 = p * kAttnPage + kg * 4;
+    float v[4] = {0.f, 0.f, 0.f, 0.f};
+    if (QD == 2) {
+      products(kf, 1, acc_b);
+      update(masked_tag, acc_a, 0, present, tok0, v);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // the tile has been consumed (the products above had to wait for the LDS reads): refill its slot,
+    // move on to the next one
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    issue(it + kSnapRing, slot);
+    slot = slot + 1 == kSnapRing ? 0 : slot + 1;
+    read_tile(slot, kf);
+    __builtin_amdgcn_sched_barrier(0);
+    if (QD == 2) {
+      products(kf, 0, acc_a);
+      update(masked_tag, acc_b, 1, present, tok0, v);
+    } else {
+      products(kf, 0, acc_b);
+      update(masked_tag, acc_a, 0, present, tok0, v);
+    }
+    if (PASS2) {  // in the same scheduling region as the next page's products, which hide its latency
+#pragma unroll
+      for (int r = 0; r < 4; ++r) v[r] = row16_sum(v[r]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (QD == 1) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) acc_a[i] = acc_b[i];
+    }
+    if (PASS2) emit_votes(v, p < p_end, tok0);
+  };
+  // The leading run of pages that need no mask takes the hot variant: none of the wavefront's pages
+  // absent, and the page's last token inside the prefix.
+  const bool any_absent =
+      __ballot((lane < n_it && off_lo < 0) || (lane + kWave < n_it && off_hi < 0)) != 0ull;
+  int n_fast = 0;
+  if (!any_absent) {
+    // pages p_begin + it * npw + pw with p * 16 + 15 <= L, i.e. p <= (L - 15) / 16, also below p_end
+    const int p_last = min(p_end - 1, (L - (kAttnPage - 1)) >= 0 ? (L - (kAttnPage - 1)) / kAttnPage : -1);
+    if (p_last >= p_begin + pw) n_fast = (p_last - p_begin - pw) / npw + 1;
+    n_fast = min(n_fast, n_it);
+  }
+#pragma unroll
+  for (int t = 0; t < kSnapRing; ++t) issue(t, t);
+  // the queries (and pass 2's row statistics) come in behind the first tiles rather than before them
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb) {
     const int col = (cgi * kSnapColBlocks + cb) * 16 + hn;
     if (col < a.NC) {
       const int h = col / a.W, w = col % a.W;
@@ -77,8 +297,9 @@ void snap_score_kernel(CacheView c, SnapArgs a) {
       for (int j = 0; j < 4; ++j) qf[cb][j].u = *reinterpret_cast<const uint4*>(qp + j * 32);
       limit[cb] = L + w;
       if (PASS2) {
-        M2[cb] = a.stats[((int64_t)unit * a.NC + col) * 2];
-        invZ[cb] = a.stats[((int64_t)unit * a.NC + col) * 2 + 1];
+        const float2 st2 = *reinterpret_cast<const float2*>(a.stats + ((int64_t)unit * a.NC + col) * 2);
+        M2[cb] = st2.x;
+        invZ[cb] = st2.y;
       }
     } else {
 #pragma unroll
@@ -88,120 +309,22 @@ void snap_score_kernel(CacheView c, SnapArgs a) {
       invZ[cb] = 0.f;
     }
   }
-  float m[kSnapColBlocks], z[kSnapColBlocks];
-#pragma unroll
-  for (int cb = 0; cb < kSnapColBlocks; ++cb) { m[cb] = kNegBigS; z[cb] = 0.f; }
-  const float sc = kLog2eS * 0.08838834764831845f;
-  const int64_t head_off = (int64_t)g * c.stride_head;
-
-  // Key tiles are requested two pages ahead of the one being scored (two register buffers used in
-  // rotation), so the memory latency is hidden behind the matrix and exponent work of the pages
-  // in between.  An absent or out-of-range page reads tile 0 of the pool and is masked below: the
-  // loads stay unconditional and the loop body straight-line.
-  const int64_t lane_off = head_off + hn * kHeadDim + kg * 8;
-  const auto fetch = [&](int p, uint4* kf) -> bool {
-    const int64_t pp = p < p_end ? phys_page(c, b, p) : -1;
-    const bf16_t* kt = c.k_pool + (pp >= 0 ? pp : 0) * c.stride_page + lane_off;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) kf[j] = ld16<false>(kt + j * 32);
-    return pp >= 0;
-  };
-  const int n_it = p_end > p_begin ? (p_end - p_begin + npw - 1) / npw : 0;
-  // one page: consume buffer kn (its tile arrived by now), refill it with the page two steps on
-  const auto step = [&](int it, uint4* kn, bool& present_buf) {
-    const int p = p_begin + it * npw + pw;
-    const bool live = p < p_end;
-    const bool present = present_buf;
-    bf16x8 kf[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) kf[j] = __builtin_bit_cast(bf16x8, kn[j]);
-    present_buf = fetch(p + 2 * npw, kn);
-    const int tok0 = p * kAttnPage + kg * 4;
-    float v[4] = {0.f, 0.f, 0.f, 0.f};
-    // A page that lies wholly inside the prefix is visible to every window row: no causal mask.
-    // Column blocks go four at a time: four independent accumulator chains keep the matrix pipe
-    // busy, and the softmax update is branch-free so the whole group schedules as one block.
-    const auto score_page = [&](auto masked_tag) {
-      constexpr bool MASKED = decltype(masked_tag)::value;
-#pragma unroll
-      for (int qd = 0; qd < kSnapColBlocks / 4; ++qd) {
-        if (qd * 4 >= n_cb) break;  // wave-uniform: the rest of this wavefront's blocks are unused
-        f32x4 acc[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-            acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[j], qf[qd * 4 + i][j].v, acc[i], 0, 0, 0);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int cb = qd * 4 + i;
-          float s[4];
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            s[r] = acc[i][r] * sc;
-            if (MASKED) s[r] = (present && tok0 + r <= limit[cb]) ? s[r] : -INFINITY;
-          }
-          if (!PASS2) {
-            const float mn = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), m[cb]);
-            z[cb] = z[cb] * exp2_fast(m[cb] - mn) + exp2_fast(s[0] - mn) + exp2_fast(s[1] - mn) +
-                    exp2_fast(s[2] - mn) + exp2_fast(s[3] - mn);
-            m[cb] = mn;
-          } else {
-#pragma unroll
-            for (int r = 0; r < 4; ++r) v[r] += exp2_fast(s[r] - M2[cb]) * invZ[cb];
-          }
-        }
-      }
-    };
-    if (present && p * kAttnPage + kAttnPage - 1 <= L)
-      score_page(std::false_type{});
-    else
-      score_page(std::true_type{});
-    if (PASS2) {
-      // sum the 16 columns held by the lanes of one token group, then the column groups
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        v[r] += __shfl_xor(v[r], 1);
-        v[r] += __shfl_xor(v[r], 2);
-        v[r] += __shfl_xor(v[r], 4);
-        v[r] += __shfl_xor(v[r], 8);
-      }
-      if (a.CG == 2) {
-        if (cgi == 1 && hn == 0) {
-#pragma unroll
-          for (int r = 0; r < 4; ++r) sV[pw][kg * 4 + r] = v[r];
-        }
-        __syncthreads();
-        if (cgi == 0) {
-#pragma unroll
-          for (int r = 0; r < 4; ++r) v[r] += sV[pw][kg * 4 + r];
-        }
-        __syncthreads();
-      }
-      if (live && cgi == 0 && hn == 0) {
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-          if (tok0 + r < L) a.votes[(int64_t)unit * a.s_cap + tok0 + r] = v[r];
-      }
-    }
-  };
-  uint4 k0[4], k1[4];
-  bool pr0 = false, pr1 = false;
-  if (n_it > 0) {
-    pr0 = fetch(p_begin + pw, k0);
-    pr1 = fetch(p_begin + npw + pw, k1);
+  read_tile(0, kf);
+  products(kf, 0, acc_a);
+  int it = 0;
+  for (; it < n_fast; ++it) page(std::false_type{}, it);  // n_it is the same for wavefronts that share a barrier
+  for (; it < n_it; ++it) page(std::true_type{}, it);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the last refills (unused) land before LDS is reused
+  if (PASS2) {
+    __syncthreads();
+    const int tok_begin = p_begin * kAttnPage;
+    const int n_tok = min(p_end * kAttnPage, L) - tok_begin;
+    for (int i = tid; i < n_tok; i += 256) a.votes[(int64_t)unit * a.s_cap + tok_begin + i] = s_votes[i];
+    return;
   }
-  for (int it = 0; it < n_it; it += 2) {  // n_it is the same for every wavefront of the workgroup
-    step(it, k0, pr0);
-    if (it + 1 < n_it) step(it + 1, k1, pr1);
-  }
-  if (PASS2) return;
-
   // ---- pass 1: merge statistics over token groups, waves, and hand the chunk's partial out -------
 #pragma unroll
-  for (int cb = 0; cb < kSnapColBlocks; ++cb) {
+  for (int cb = 0; cb < NCB; ++cb) {
 #pragma unroll
     for (int off = 16; off <= 32; off <<= 1) {
       const float mo = __shfl_xor(m[cb], off), zo = __shfl_xor(z[cb], off);
@@ -412,6 +535,54 @@ __global__ __launch_bounds__(kSelT) void snap_select_kernel(CacheView c, SnapArg
   if (g == 0 && tid == 0) a.n_out[b] = a.keep;
 }
 
+// The same selection for prompts of up to ROCKETKV_MAX_PAGES tokens, through the register-resident
+// top-k that Step 2 of the decode path uses for its page scores (one token = one page of size 1,
+// budget = the prefix share of the keep budget): every pooled vote is read once, where the radix
+// kernel above walks the row five times, twice of them with a stride that defeats coalescing.  Same
+// result: the k largest, ties to the lower position, ascending.
+__global__ __launch_bounds__(kSelT) void snap_select_fast_kernel(CacheView c, SnapArgs a) {
+  __shared__ PickShared<kSelT> sh;
+  const int tid = threadIdx.x;
+  const int unit = blockIdx.x;
+  const int b = unit / c.n_kv_heads, g = unit % c.n_kv_heads;
+  const int S = c.seq_lens[b];
+  int32_t* kept = a.kept + (int64_t)unit * a.keep;
+  int32_t* kept2 = a.kept_user ? a.kept_user + (int64_t)unit * a.kept_stride : nullptr;
+  const bool small = S <= a.keep;
+  const bool bad = S > c.pages_cap * kAttnPage;
+  if (small || bad) {
+    const int cnt = bad ? 0 : S;
+    for (int i = tid; i < a.keep; i += kSelT) {
+      const int v = i < cnt ? i : -1;
+      kept[i] = v;
+      if (kept2) kept2[i] = v;
+    }
+    if (g == 0 && tid == 0) a.n_out[b] = cnt;
+    return;
+  }
+  const int L = S - a.W;
+  const int k_pref = a.keep - a.W;
+  for (int i = tid; i < 4 * 256; i += kSelT) (&sh.hist[0][0])[i] = 0;  // the pick expects clear counters
+  __syncthreads();
+  CacheView row = c;  // the pooled votes of this unit as one sequence of one-token pages
+  row.page_size = 1;
+  row.pages_cap = a.s_cap;
+  SelectArgs pa = {};
+  pa.in_scores = a.pooled + (int64_t)unit * a.s_cap;
+  pa.T = k_pref;
+  pa.n_recent = 0;
+  pa.out_pages = kept;
+  pa.row_len = k_pref;
+  pa.out_pages2 = kept2;
+  pa.row_len2 = k_pref;
+  pick_from_scores<kSelT>(row, pa, 0, L, sh);
+  for (int w = tid; w < a.W; w += kSelT) {
+    kept[k_pref + w] = L + w;
+    if (kept2) kept2[k_pref + w] = L + w;
+  }
+  if (g == 0 && tid == 0) a.n_out[b] = a.keep;
+}
+
 // copy the kept tokens into the destination cache; one workgroup per 16 kept tokens.  K rows move
 // as 256-byte rows.  The V values of the 16 tokens are staged in LDS as [channel][token] whatever the
 // source layout, then leave as one contiguous channel-major tile (page size 16) or as token rows.
@@ -503,8 +674,9 @@ SnapPlan plan_snapkv(const CacheView& src, int window, int keep) {
   // Pages per workgroup in the score passes.  Every wavefront loads the whole observation-window
   // query block before its first page, so long chunks amortise that; short ones keep the chip full
   // when there are few (sequence, KV head) units.  Aim for about 2048 workgroups.
+  static_assert(kSnapMaxChunkPages / 2 <= kSnapMaxIters, "a wavefront's share of the longest chunk must fit its page-offset lanes");
   int chunk_pages = 32;
-  while (chunk_pages < 256 && units * ((src.pages_cap + chunk_pages - 1) / chunk_pages) > 2048) chunk_pages *= 2;
+  while (chunk_pages < kSnapMaxChunkPages && units * ((src.pages_cap + chunk_pages - 1) / chunk_pages) > 2048) chunk_pages *= 2;
   p.chunk_pages = chunk_pages;
   p.n_chunks = (src.pages_cap + chunk_pages - 1) / chunk_pages;
   const size_t s_cap = (size_t)src.pages_cap * kAttnPage;
@@ -549,13 +721,25 @@ hipError_t launch_snapkv(const bf16_t* q_obs, const CacheView& src, int window, 
   a.n_out = n_out;
 
   const dim3 sgrid(plan.n_chunks, units);
-  hipLaunchKernelGGL(snap_score_kernel<false>, sgrid, dim3(256), 0, st, src, a);
+  const size_t vote_bytes = (size_t)a.chunk_pages * kAttnPage * sizeof(float);
+  const bool two_groups = a.NC > 4 * 16;  // some wavefront owns more than four blocks of real rows
+  if (two_groups)
+    hipLaunchKernelGGL((snap_score_kernel<false, 2>), sgrid, dim3(256), kSnapRingBytes, st, src, a);
+  else
+    hipLaunchKernelGGL((snap_score_kernel<false, 1>), sgrid, dim3(256), kSnapRingBytes, st, src, a);
   hipLaunchKernelGGL(snap_stats_kernel, dim3(units), dim3(256), 0, st, src, a);
-  hipLaunchKernelGGL(snap_score_kernel<true>, sgrid, dim3(256), 0, st, src, a);
+
+  if (two_groups)
+    hipLaunchKernelGGL((snap_score_kernel<true, 2>), sgrid, dim3(256), kSnapRingBytes + vote_bytes, st, src, a);
+  else
+    hipLaunchKernelGGL((snap_score_kernel<true, 1>), sgrid, dim3(256), kSnapRingBytes + vote_bytes, st, src, a);
   const dim3 pgrid((a.s_cap + kPoolTile - 1) / kPoolTile, units);
   hipLaunchKernelGGL(snap_pool_kernel, pgrid, dim3(256), (kPoolTile + 2 * a.pool_r) * sizeof(float), st,
                      src, a);
-  hipLaunchKernelGGL(snap_select_kernel, dim3(units), dim3(kSelT), 0, st, src, a);
+  if (a.s_cap <= ROCKETKV_MAX_PAGES)
+    hipLaunchKernelGGL(snap_select_fast_kernel, dim3(units), dim3(kSelT), 0, st, src, a);
+  else
+    hipLaunchKernelGGL(snap_select_kernel, dim3(units), dim3(kSelT), 0, st, src, a);
   if (!dst) return hipGetLastError();  // filter only: the indices are the result
   const dim3 ggrid((keep + kAttnPage - 1) / kAttnPage, units);
   hipLaunchKernelGGL(snap_gather_kernel, ggrid, dim3(256), 0, st, src, *dst, a);

@@ -406,6 +406,8 @@ SNAP_CASES = [
     ("llama70b_step_b16", dict(batch=1, context=2048, snap_keep=512, n_layers=1, n_heavy=8), None, 63, False),
     ("mistral_snap_128k", dict(context=1536, snap_keep=640, window=128, n_heavy=8,
                                n_q_heads=4, n_kv_heads=2), None, 63, False),  # multi-turn window size
+    # a prompt beyond 32768 tokens: the radix-select kernel instead of the register-resident top-k
+    ("mistral_snap_128k", dict(context=40000, snap_keep=2048, n_heavy=16, n_q_heads=4, n_kv_heads=2), None, 63, False),
 ]
 
 
