@@ -332,13 +332,15 @@ def main():
     mt_pt = None
     if not args.no_decomposed and n_dense > 0:
         ml = []
-        snapf_ws = rk.alloc_workspace(rk.OP_SNAPKV, dense_layers[0]["cache"], W, N)
+        snapf_ws = None
         for Ld in dense_layers:
             Kf, Vf = rk.unpack_cache(Ld["cache"])
             full = rk.pack_cache(Kf[:, :, :w.context], Vf[:, :, :w.context], np.full(B, w.context, dtype=np.int32), Hq,
                                  16, pages_cap=(w.context + total_steps + 8 + 15) // 16, v_layout=rk.V_TOKEN_MAJOR)
             del Kf, Vf
             ix = rk.alloc_index(full, ps, N + total_steps + 8)
+            if snapf_ws is None:
+                snapf_ws = rk.alloc_workspace(rk.OP_SNAPKV, full, W, N)
             rk.snapkv_filter(Ld["qobs"], full, W, w.pool_kernel, N, ix, snapf_ws)
             km3, kn3 = rk.alloc_index_summaries(full, ix)
             rk.mt_build_page_summaries(full, ix, km3, kn3)
