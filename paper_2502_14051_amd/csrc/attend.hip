@@ -25,12 +25,13 @@ __global__ void zero_u32_kernel(uint32_t* p, int n) {
 
 // ---- launch geometry ---------------------------------------------------------------------------------
 constexpr int kComputeUnits = 256;  // MI355X
-static int g_waves = 8;            // wavefronts per workgroup (4 or 8)
+static int g_waves = 0;            // wavefronts per workgroup (4 or 8); 0 = by the number of units
 static int g_pairs_per_wave = 2;   // page pairs a wavefront aims to own
 static int g_max_wgs = 2048;       // cap on units x splits (keeps the dense case from over-splitting)
 
 void tune_attend(int waves, int pairs_per_wave, int max_wgs) {
   if (waves == 4 || waves == 8) g_waves = waves;
+  if (waves < 0) g_waves = 0;
   if (pairs_per_wave > 0) g_pairs_per_wave = pairs_per_wave;
   if (max_wgs > 0) g_max_wgs = max_wgs;
 }
@@ -38,13 +39,20 @@ void tune_attend(int waves, int pairs_per_wave, int max_wgs) {
 AttendPlan plan_attend(const CacheView& c, int row_len) {
   AttendPlan p;
   const int units = c.batch * c.n_kv_heads;
-  int waves = g_waves;
+  // Up to one (sequence, KV head) unit per compute unit: workgroups of eight wavefronts, one per
+  // compute unit, splitting a unit's list between them if that fills the chip.  More units than
+  // compute units: workgroups of four wavefronts, two of which share a compute unit and drift apart,
+  // so that one's selection phase runs under the other's K/V stream (batch 64 of the benchmark shape:
+  // 61 against 71 us per layer-step; at exactly 256 units the eight-wavefront form is still ahead).
+  const bool many_units = units > kComputeUnits;
+  int waves = g_waves ? g_waves : (many_units ? 4 : 8);
   // the LDS merge buffer must fit 64 KiB: waves * G * 130 floats
   while (waves > 4 && (size_t)waves * c.group * (kHeadDim + 2) * sizeof(float) > 60 * 1024) waves /= 2;
   p.waves = waves;
   // entries the smallest sensible workgroup takes: normally g_pairs_per_wave page pairs per wavefront,
   // one pair when even that leaves compute units idle (few units: shorter streams beat fewer merges)
   int pairs = g_pairs_per_wave;
+  if (!g_waves && many_units) pairs = 2 * g_pairs_per_wave;  // half the wavefronts, the same share per workgroup
   if ((int64_t)units * ((row_len + 2 * waves - 1) / (2 * waves)) <= kComputeUnits) pairs = 1;
   const int per_wg = 2 * pairs * waves;
   int n_split = (row_len + per_wg - 1) / per_wg;

@@ -190,6 +190,7 @@ ATTEND_CASES = [
     ("tiny", dict(n_q_heads=32, n_kv_heads=2, context=2048, heavy_nats=1.0), None, True),  # G = 16
     ("llama70b_step_b16", dict(batch=2, context=3000, n_layers=1, n_heavy=0), None, False),  # G = 8
     ("tiny", dict(n_q_heads=12, n_kv_heads=2, context=1111, n_heavy=3), None, True),          # G = 6
+    ("tiny", dict(batch=33, n_q_heads=32, n_kv_heads=8, context=700, n_heavy=2), None, False),  # 264 units
 ]
 
 
@@ -282,6 +283,8 @@ DECODE_CASES = [
     ("tiny", dict(batch=2, n_q_heads=12, n_kv_heads=2, context=2222, token_budget=300), None, 0, True),   # G = 6
     ("tiny", dict(batch=2, n_q_heads=21, n_kv_heads=3, context=1500, token_budget=128), None, 1, False),  # G = 7
     ("tiny", dict(n_q_heads=8, n_kv_heads=2, context=140000, token_budget=2048, n_heavy=32), None, 0, False),  # > 8192 pages
+    # more (sequence, KV head) units than compute units: the four-wavefront launch geometry
+    ("tiny", dict(batch=40, n_q_heads=32, n_kv_heads=8, context=1100, token_budget=512, n_heavy=4), None, 0, True),
 ]
 
 
