@@ -162,11 +162,6 @@ void snap_score_kernel(CacheView c, SnapArgs a) {
                                        ring + (slot * 4 + j) * kWave, 16, 0, PASS2 ? 0 : kPolicyStream);
     }
   };
-  // The work of a page is 2 * QD pieces: the products of a group of four column blocks (16 matrix
-  // instructions) and that group's softmax update (plain and transcendental vector instructions).
-  // The kernel is bound by the issue of these, not by memory, and the two kinds run on different
-  // pipes, so the loop is software-pipelined: the products of group n + 1 sit in one scheduling
-  // region with the update of group n (which may belong to the previous page).
   const auto read_tile = [&](int slot, bf16x8* kf) {
     // everything but the kSnapRing - 1 younger tiles (four loads each) has landed
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"((kSnapRing - 1) * 4) : "memory");
@@ -231,45 +226,37 @@ void snap_score_kernel(CacheView c, SnapArgs a) {
     if (live && cgi == 0 && hn == 0)
       *reinterpret_cast<float4*>(s_votes + (tok0 - p_begin * kAttnPage)) = make_float4(v[0], v[1], v[2], v[3]);
   };
-  bf16x8 kf[4];
-  f32x4 acc_a[4], acc_b[4];  // acc_a: first group of the page at hand, products already done
   int slot = 0;
-  // One page: on entry kf holds its tile and acc_a its first group; on exit the same for the next page
-  // (past the end that is a dummy tile whose products nobody looks at).
+  // One page: its tile out of the ring, then per group of four column blocks the products and the
+  // update; the slot is refilled once the last products have read it.
   const auto page = [&](auto masked_tag, int it) {
     constexpr bool MASKED = decltype(masked_tag)::value;
     const int p = p_begin + it * npw + pw;
     const bool present = MASKED ? tile_off(it) >= 0 : true;
     const int tok0 = p * kAttnPage + kg * 4;
     float v[4] = {0.f, 0.f, 0.f, 0.f};
-    if (QD == 2) {
-      products(kf, 1, acc_b);
-      update(masked_tag, acc_a, 0, present, tok0, v);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    // the tile has been consumed (the products above had to wait for the LDS reads): refill its slot,
-    // move on to the next one
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    issue(it + kSnapRing, slot);
-    slot = slot + 1 == kSnapRing ? 0 : slot + 1;
+    bf16x8 kf[4];
     read_tile(slot, kf);
-    __builtin_amdgcn_sched_barrier(0);
-    if (QD == 2) {
-      products(kf, 0, acc_a);
-      update(masked_tag, acc_b, 1, present, tok0, v);
-    } else {
-      products(kf, 0, acc_b);
-      update(masked_tag, acc_a, 0, present, tok0, v);
+#pragma unroll
+    for (int qd = 0; qd < QD; ++qd) {
+      f32x4 acc[4];
+      products(kf, qd, acc);
+      if (qd == QD - 1) {
+        // the tile is in registers (the products had to wait for the LDS reads): refill its slot
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        issue(it + kSnapRing, slot);
+      }
+      // keep the groups in program order: products of a later group hoisted above this group's
+      // update would need a second set of accumulators the register file has no room for
+      __builtin_amdgcn_sched_barrier(0);
+      update(masked_tag, acc, qd, present, tok0, v);
     }
-    if (PASS2) {  // in the same scheduling region as the next page's products, which hide its latency
+    if (PASS2) {
 #pragma unroll
       for (int r = 0; r < 4; ++r) v[r] = row16_sum(v[r]);
     }
     __builtin_amdgcn_sched_barrier(0);
-    if (QD == 1) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) acc_a[i] = acc_b[i];
-    }
+    slot = slot + 1 == kSnapRing ? 0 : slot + 1;
     if (PASS2) emit_votes(v, p < p_end, tok0);
   };
   // The leading run of pages that need no mask takes the hot variant: none of the wavefront's pages
@@ -309,8 +296,6 @@ void snap_score_kernel(CacheView c, SnapArgs a) {
       invZ[cb] = 0.f;
     }
   }
-  read_tile(0, kf);
-  products(kf, 0, acc_a);
   int it = 0;
   for (; it < n_fast; ++it) page(std::false_type{}, it);  // n_it is the same for wavefronts that share a barrier
   for (; it < n_it; ++it) page(std::true_type{}, it);
