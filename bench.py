@@ -400,50 +400,54 @@ def main():
         single["dense_full_kv_us"] = round(timed_graph(dense_one, 6) * 1e3 / len(sl), 2)
         del sl
 
-    # ------------------------------------------------------------------ the same step at four times the batch
-    # Same model shape and budgets, batch 64 (512 units, two rounds of workgroups): the fixed
-    # latencies of a launch are shared by more K/V bytes, so this shows how far the same kernel gets
-    # towards the roofline at a production batch size.  Eight layers (8 GiB of compressed cache).
+    # ------------------------------------------------------------------ the same step at larger batches
+    # Same model shape and budgets at batch 64 and 128 (512 / 1024 units): the fixed latencies of a
+    # launch are shared by more K/V bytes, so this shows how far the same kernel gets towards the
+    # roofline at production batch sizes.  Eight layers each (8 / 16 GiB of compressed cache).
     big = None
     if not args.no_decomposed and not args.batch and not args.layers:
-        Bb, nlb = 4 * B, 8
-        wb = wl.scaled(w, batch=Bb, n_layers=nlb)
-        bl = []
-        snapb_ws = None
-        for layer in range(nlb):
-            d = wl.generate_device(wb, layer, dev, with_obs=True)
-            srcb = rk.pack_cache(d["K"], d["V"], d["seq_lens"].cpu().numpy(), Hq, ps)
-            dstb = rk.alloc_cache(Bb, Hq, Hkv, D, ps, pages_cap, dev, zero=True)
-            if snapb_ws is None:
-                snapb_ws = rk.alloc_workspace(rk.OP_SNAPKV, srcb, W, N)
-            rk.snapkv_compress(d["qobs"], srcb, W, w.pool_kernel, N, dstb, None, snapb_ws)
-            kmb, knb = rk.alloc_summaries(dstb)
-            rk.build_page_summaries(dstb, kmb, knb)
-            torch.cuda.synchronize()
-            gen = torch.Generator(device=dev)
-            gen.manual_seed(88_000 + layer)
-            bl.append(dict(cache=dstb, kmax=kmb, kmin=knb, q=d["q"].contiguous(),
-                           new_k=torch.randn((Bb, Hkv, D), generator=gen, device=dev).bfloat16(),
-                           new_v=torch.randn((Bb, Hkv, D), generator=gen, device=dev).bfloat16(),
-                           out=torch.empty((Bb, Hq, D), dtype=torch.bfloat16, device=dev),
-                           ws=rk.alloc_workspace(rk.OP_HSA_DECODE, dstb, T)))
-            del d, srcb
-        del snapb_ws
+        big = []
+        for Bb in (4 * B, 8 * B):
+            nlb = 8
+            wb = wl.scaled(w, batch=Bb, n_layers=nlb)
+            bl = []
+            snapb_ws = None
+            for layer in range(nlb):
+                d = wl.generate_device(wb, layer, dev, with_obs=True)
+                srcb = rk.pack_cache(d["K"], d["V"], d["seq_lens"].cpu().numpy(), Hq, ps)
+                dstb = rk.alloc_cache(Bb, Hq, Hkv, D, ps, pages_cap, dev, zero=True)
+                if snapb_ws is None:
+                    snapb_ws = rk.alloc_workspace(rk.OP_SNAPKV, srcb, W, N)
+                rk.snapkv_compress(d["qobs"], srcb, W, w.pool_kernel, N, dstb, None, snapb_ws)
+                kmb, knb = rk.alloc_summaries(dstb)
+                rk.build_page_summaries(dstb, kmb, knb)
+                torch.cuda.synchronize()
+                gen = torch.Generator(device=dev)
+                gen.manual_seed(88_000 + layer)
+                bl.append(dict(cache=dstb, kmax=kmb, kmin=knb, q=d["q"].contiguous(),
+                               new_k=torch.randn((Bb, Hkv, D), generator=gen, device=dev).bfloat16(),
+                               new_v=torch.randn((Bb, Hkv, D), generator=gen, device=dev).bfloat16(),
+                               out=torch.empty((Bb, Hq, D), dtype=torch.bfloat16, device=dev),
+                               ws=rk.alloc_workspace(rk.OP_HSA_DECODE, dstb, T)))
+                del d, srcb
+            del snapb_ws
 
-        def big_all():
-            for L in bl:
-                rk.hsa_decode_append(L["cache"], L["q"], L["new_k"], L["new_v"], L["kmax"], L["kmin"], k1, T, 0,
-                                     L["out"], None, None, None, L["ws"], stream)
+            def big_all():
+                for L in bl:
+                    rk.hsa_decode_append(L["cache"], L["q"], L["new_k"], L["new_v"], L["kmax"], L["kmin"], k1, T,
+                                         0, L["out"], None, None, None, L["ws"], stream)
 
-        big_us = timed_graph(big_all, max(2, args.kernel_reps // 2)) * 1e3 / nlb
-        nb_now = int(bl[0]["cache"].seq_lens[0].item())
-        big_bytes = hsa_bytes_at((nb_now + ps - 1) // ps, ps, k1, T) * (Bb // B)
-        big_gbs = big_bytes / (big_us * 1e-6) / 1e9
-        big = {"workload": f"same shape and budgets, batch {Bb}, {nlb} layers", "us_per_layer_step": round(big_us, 3),
-               "bytes_per_layer_step": big_bytes, "achieved_GBs": round(big_gbs, 1),
-               "frac_of_hbm_peak": round(big_gbs / HBM_PEAK_GBS, 4),
-               "decode_tokens_per_s_attention_only_32_layers": round(Bb / (big_us * 1e-6 * w.n_layers), 1)}
-        del bl
+            big_us = timed_graph(big_all, max(2, args.kernel_reps // 2)) * 1e3 / nlb
+            nb_now = int(bl[0]["cache"].seq_lens[0].item())
+            big_bytes = hsa_bytes_at((nb_now + ps - 1) // ps, ps, k1, T) * (Bb // B)
+            big_gbs = big_bytes / (big_us * 1e-6) / 1e9
+            big.append({"workload": f"same shape and budgets, batch {Bb}, {nlb} layers",
+                        "us_per_layer_step": round(big_us, 3), "bytes_per_layer_step": big_bytes,
+                        "achieved_GBs": round(big_gbs, 1), "frac_of_hbm_peak": round(big_gbs / HBM_PEAK_GBS, 4),
+                        "decode_tokens_per_s_attention_only_32_layers":
+                            round(Bb / (big_us * 1e-6 * w.n_layers), 1)})
+            del bl
+            torch.cuda.empty_cache()
 
     # ------------------------------------------------------------------ bytes
     kp = min(P_now, T // ps)
@@ -528,7 +532,7 @@ def main():
         "decomposed_operating_point": dec_pt,
         "multi_turn_variant": mt_pt,
         "single_layer_batch1": single,
-        "batch64_same_shape": big,
+        "larger_batches_same_shape": big,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))
