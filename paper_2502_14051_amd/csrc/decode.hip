@@ -74,9 +74,13 @@ void hsa_decode_kernel(CacheView c, SelectArgs sa, AttendArgs aa, AppendArgs ap,
   // the summary column the new key goes into, fetched now (beside the row loads) and stored at the end
   bf16_t old_max = 0, old_min = 0;
   const int64_t sum_off = ((int64_t)unit * kHeadDim + (tid & (kHeadDim - 1))) * c.pages_cap + (room ? tp.page : 0);
-  if (APPEND && room && split == 0 && tid < kHeadDim && tp.slot != 0) {
-    old_max = ap.kmax[sum_off];
-    old_min = ap.kmin[sum_off];
+  int64_t pp_new = -1;  // where the new token's page lives: looked up now, needed at the end
+  if (APPEND && room && split == 0 && tid < kHeadDim) {
+    pp_new = phys_page(c, b, tp.page);
+    if (tp.slot != 0) {
+      old_max = ap.kmax[sum_off];
+      old_min = ap.kmin[sum_off];
+    }
   }
   select_pages<NT>(c, sa, unit, n, sh, keys, list, split == 0, tp);
   __syncthreads();  // list complete; the selection scratch is dead and becomes the merge buffer
@@ -88,9 +92,8 @@ void hsa_decode_kernel(CacheView c, SelectArgs sa, AttendArgs aa, AppendArgs ap,
     if (tid == 0)
       arrivals = __hip_atomic_fetch_add(&seq_counters[b], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (room && split == 0 && tid < kHeadDim) {
-      const int64_t pp = phys_page(c, b, tp.page);
-      if (pp >= 0) {
-        const int64_t base = pp * c.stride_page + (int64_t)g * c.stride_head;
+      if (pp_new >= 0) {
+        const int64_t base = pp_new * c.stride_page + (int64_t)g * c.stride_head;
         c.k_pool[base + tp.slot * kHeadDim + tid] = kb;
         c.v_pool[base + tid * kAttnPage + tp.slot] = vb;
       }

@@ -47,7 +47,9 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* wsum) 
 }
 
 // accumulate eight rows' worth of eight-page runs; every load of the batch is issued before use
-template <bool STREAM = false>
+// PATCH: fold tp's new key into the run that holds its page right here, in the packed rows (the split
+// path); without it the caller overrides that page's score afterwards (tail_page_score below).
+template <bool STREAM = false, bool PATCH = true>
 __device__ __forceinline__ void score_rows8(const SelectArgs& a, const int* s_chan, const float* s_wgt,
                                             int64_t rows, int pages_cap, int o, int j0, int jstep,
                                             const TailPatch& tp, float (&acc)[8]) {
@@ -64,7 +66,7 @@ __device__ __forceinline__ void score_rows8(const SelectArgs& a, const int* s_ch
       v[t] = ld16<STREAM>(row);
     }
   }
-  if (tp.page >= 0 && o == (tp.page >> 3)) {
+  if (PATCH && tp.page >= 0 && o == (tp.page >> 3)) {
     // this run of eight pages holds the page that is receiving a token: fold the new key into its
     // bound (or start the bound from it when the token opens the page); idempotent if memory
     // already holds the updated value
@@ -98,6 +100,33 @@ __device__ __forceinline__ void score_rows8(const SelectArgs& a, const int* s_ch
       acc[2 * i + 1] = fmaf(w[t], bf16hi_to_f32(x[i]), acc[2 * i + 1]);
     }
   }
+}
+
+// The score of the page that is receiving a token (tp.page), computed on its own by the first two
+// wavefronts from the page's old bounds and the new key, one picked channel per thread: the bound of
+// a channel is the old one folded with the new key's value, or the new value alone when the token
+// opens the page (whatever memory holds for that column is then not looked at).  The two partial
+// sums go to out2[0..1]; the caller adds them (fixed order) where it turns scores into keys, after a
+// barrier.  Cheaper than patching the packed rows in every wavefront that scores them.
+template <int NT>
+__device__ __forceinline__ void tail_page_score(const SelectArgs& a, const int* s_chan, const float* s_wgt,
+                                                int64_t rows, int pages_cap, const TailPatch& tp, float* out2) {
+  const int tid = threadIdx.x;
+  if (tp.page < 0 || tid >= 2 * kWave) return;
+  float contrib = 0.f;
+  if (tid < a.k1) {
+    const float w = s_wgt[tid];
+    const int ch = s_chan[tid];
+    float f = bf16_to_f32(tp.knew[ch]);
+    if (tp.slot != 0) {
+      const float fo = bf16_to_f32(((w >= 0.f) ? a.kmax : a.kmin)[(rows + ch) * pages_cap + tp.page]);
+      f = (w >= 0.f) ? fmaxf(fo, f) : fminf(fo, f);
+    }
+    contrib = w * f;
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) contrib += __shfl_xor(contrib, off);
+  if (tid % kWave == 0) out2[tid / kWave] = contrib;
 }
 
 // Step 2, first half (needs only q): a = sum_h |q|, s = sum_h q, i1 = top-k1 channels of a, left in
@@ -243,6 +272,8 @@ __device__ __forceinline__ int select_pages(const CacheView& c, const SelectArgs
   const int n_oct = (P + 7) / 8;
   const int64_t rows = (int64_t)unit * kHeadDim;
   float* out_scores = write_global ? a.out_scores : nullptr;
+  float* tail2 = sh.s_abs;  // free since the channel pick ended; [0..1]: the two halves of tp.page's score
+  tail_page_score<NT>(a, sh.s_chan, sh.s_wgt, rows, c.pages_cap, tp, tail2);
   if (n_oct < NT) {
     int npow = 1;
     while (npow < n_oct) npow <<= 1;
@@ -252,13 +283,15 @@ __device__ __forceinline__ int select_pages(const CacheView& c, const SelectArgs
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i] = 0.f;
     if (o < n_oct)
-      for (int j0 = r; j0 < a.k1; j0 += 8 * R) score_rows8(a, sh.s_chan, sh.s_wgt, rows, c.pages_cap, o, j0, R, tp, acc);
+      for (int j0 = r; j0 < a.k1; j0 += 8 * R)
+        score_rows8<false, false>(a, sh.s_chan, sh.s_wgt, rows, c.pages_cap, o, j0, R, tp, acc);
 #pragma unroll
     for (int i = 0; i < 8; ++i) sh.partial[(r * npow + o) * 8 + i] = acc[i];
     __syncthreads();
     for (int p = tid; p < npow * 8; p += NT) {
       float s = 0.f;
       for (int rr = 0; rr < R; ++rr) s += sh.partial[rr * npow * 8 + p];
+      if (p == tp.page) s = tail2[0] + tail2[1];
       if (p < n_oct * 8) {
         if (p < P && out_scores) out_scores[(int64_t)unit * c.pages_cap + p] = s;
         if (p >= P) s = -INFINITY;
@@ -267,15 +300,18 @@ __device__ __forceinline__ int select_pages(const CacheView& c, const SelectArgs
       }
     }
   } else {
+    __syncthreads();  // tail2 is read below
     for (int o = tid; o < n_oct; o += NT) {
       float acc[8];
 #pragma unroll
       for (int i = 0; i < 8; ++i) acc[i] = 0.f;
-      for (int j0 = 0; j0 < a.k1; j0 += 8) score_rows8(a, sh.s_chan, sh.s_wgt, rows, c.pages_cap, o, j0, 1, tp, acc);
+      for (int j0 = 0; j0 < a.k1; j0 += 8)
+        score_rows8<false, false>(a, sh.s_chan, sh.s_wgt, rows, c.pages_cap, o, j0, 1, tp, acc);
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const int p = o * 8 + i;
         float s = acc[i];
+        if (p == tp.page) s = tail2[0] + tail2[1];
         if (p < P && out_scores) out_scores[(int64_t)unit * c.pages_cap + p] = s;
         if (p >= P) s = -INFINITY;
         else if (p >= P - a.n_recent) s = INFINITY;
