@@ -47,12 +47,11 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* wsum) 
 }
 
 // accumulate eight rows' worth of eight-page runs; every load of the batch is issued before use
-// PATCH: fold tp's new key into the run that holds its page right here, in the packed rows (the split
-// path); without it the caller overrides that page's score afterwards (tail_page_score below).
-template <bool STREAM = false, bool PATCH = true>
+// (the page that is receiving a token in the same launch gets its score from tail_page_score instead)
+template <bool STREAM = false>
 __device__ __forceinline__ void score_rows8(const SelectArgs& a, const int* s_chan, const float* s_wgt,
                                             int64_t rows, int pages_cap, int o, int j0, int jstep,
-                                            const TailPatch& tp, float (&acc)[8]) {
+                                            float (&acc)[8]) {
   uint4 v[8];
   float w[8];
 #pragma unroll
@@ -64,31 +63,6 @@ __device__ __forceinline__ void score_rows8(const SelectArgs& a, const int* s_ch
       w[t] = s_wgt[j];
       const bf16_t* row = (w[t] >= 0.f ? a.kmax : a.kmin) + (rows + s_chan[j]) * pages_cap + o * 8;
       v[t] = ld16<STREAM>(row);
-    }
-  }
-  if (PATCH && tp.page >= 0 && o == (tp.page >> 3)) {
-    // this run of eight pages holds the page that is receiving a token: fold the new key into its
-    // bound (or start the bound from it when the token opens the page); idempotent if memory
-    // already holds the updated value
-    const int e = tp.page & 7;
-#pragma unroll
-    for (int t = 0; t < 8; ++t) {
-      const int j = j0 + t * jstep;
-      if (j < a.k1) {
-        const uint32_t kn = tp.knew[s_chan[j]];
-        uint32_t x[4] = {v[t].x, v[t].y, v[t].z, v[t].w};
-#pragma unroll
-        for (int wd = 0; wd < 4; ++wd) {
-          if (wd == (e >> 1)) {
-            const uint32_t old = (e & 1) ? (x[wd] >> 16) : (x[wd] & 0xffffu);
-            const float fo = bf16_to_f32((bf16_t)old), fn = bf16_to_f32((bf16_t)kn);
-            const bool take_new = tp.slot == 0 || (w[t] >= 0.f ? fn > fo : fn < fo);
-            const uint32_t val = take_new ? kn : old;
-            x[wd] = (e & 1) ? ((x[wd] & 0xffffu) | (val << 16)) : ((x[wd] & 0xffff0000u) | val);
-          }
-        }
-        v[t] = make_uint4(x[0], x[1], x[2], x[3]);
-      }
     }
   }
 #pragma unroll
@@ -284,7 +258,7 @@ __device__ __forceinline__ int select_pages(const CacheView& c, const SelectArgs
     for (int i = 0; i < 8; ++i) acc[i] = 0.f;
     if (o < n_oct)
       for (int j0 = r; j0 < a.k1; j0 += 8 * R)
-        score_rows8<false, false>(a, sh.s_chan, sh.s_wgt, rows, c.pages_cap, o, j0, R, tp, acc);
+        score_rows8(a, sh.s_chan, sh.s_wgt, rows, c.pages_cap, o, j0, R, acc);
 #pragma unroll
     for (int i = 0; i < 8; ++i) sh.partial[(r * npow + o) * 8 + i] = acc[i];
     __syncthreads();
@@ -306,7 +280,7 @@ __device__ __forceinline__ int select_pages(const CacheView& c, const SelectArgs
 #pragma unroll
       for (int i = 0; i < 8; ++i) acc[i] = 0.f;
       for (int j0 = 0; j0 < a.k1; j0 += 8)
-        score_rows8<false, false>(a, sh.s_chan, sh.s_wgt, rows, c.pages_cap, o, j0, 1, tp, acc);
+        score_rows8(a, sh.s_chan, sh.s_wgt, rows, c.pages_cap, o, j0, 1, acc);
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const int p = o * 8 + i;
@@ -634,15 +608,21 @@ __device__ __forceinline__ void score_chunk(const CacheView& c, const SelectArgs
   float acc[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+  // the page that is receiving a token, if it lies in this slice: scored on its own (see tail_page_score)
+  float* tail2 = sh.s_abs;  // free since the channel pick ended
+  const int tail_local = tp.page >= 0 ? tp.page - o_begin * 8 : -1;
+  const bool owns_tail = tail_local >= 0 && tail_local < n_runs * 8;  // same for the whole workgroup
+  if (owns_tail) tail_page_score<NT>(a, sh.s_chan, sh.s_wgt, rows, c.pages_cap, tp, tail2);
   if (o < n_runs)
     for (int j0 = r; j0 < a.k1; j0 += 8 * R)  // each slice of the rows has this one reader: streamed
-      score_rows8<true>(a, sh.s_chan, sh.s_wgt, rows, c.pages_cap, o_begin + o, j0, R, tp, acc);
+      score_rows8<true>(a, sh.s_chan, sh.s_wgt, rows, c.pages_cap, o_begin + o, j0, R, acc);
 #pragma unroll
   for (int i = 0; i < 8; ++i) sh.partial[(r * npow + o) * 8 + i] = acc[i];
   __syncthreads();
   for (int p = tid; p < n_runs * 8; p += NT) {
     float s = 0.f;
     for (int rr = 0; rr < R; ++rr) s += sh.partial[rr * npow * 8 + p];
+    if (owns_tail && p == tail_local) s = tail2[0] + tail2[1];
     const int page = o_begin * 8 + p;
     if (page < P) {
       if (COHERENT)  // read back by another workgroup of this launch: write through, device scope
