@@ -241,6 +241,7 @@ __device__ __forceinline__ int select_pages(const CacheView& c, const SelectArgs
       for (int i = kp + tid; i < a.row_len2; i += NT) a.out_pages2[(int64_t)unit * a.row_len2 + i] = -1;
   }
   if (P == 0) return 0;
+  const int n_rec = min(a.n_recent, kp);  // no more forced pages than pages picked: the newest ones win
 
   // ---- s1: page scores ---------------------------------------------------------------------------
   const int n_oct = (P + 7) / 8;
@@ -269,7 +270,7 @@ __device__ __forceinline__ int select_pages(const CacheView& c, const SelectArgs
       if (p < n_oct * 8) {
         if (p < P && out_scores) out_scores[(int64_t)unit * c.pages_cap + p] = s;
         if (p >= P) s = -INFINITY;
-        else if (p >= P - a.n_recent) s = INFINITY;
+        else if (p >= P - n_rec) s = INFINITY;
         keys[p] = f32_order_key(s);
       }
     }
@@ -288,7 +289,7 @@ __device__ __forceinline__ int select_pages(const CacheView& c, const SelectArgs
         if (p == tp.page) s = tail2[0] + tail2[1];
         if (p < P && out_scores) out_scores[(int64_t)unit * c.pages_cap + p] = s;
         if (p >= P) s = -INFINITY;
-        else if (p >= P - a.n_recent) s = INFINITY;
+        else if (p >= P - n_rec) s = INFINITY;
         keys[p] = f32_order_key(s);
       }
     }
@@ -401,6 +402,7 @@ __device__ __forceinline__ void pick_from_scores_n(const CacheView& c, const Sel
   if (a.out_pages2)
     for (int i = kp + tid; i < a.row_len2; i += NT) a.out_pages2[(int64_t)unit * a.row_len2 + i] = -1;
   if (P == 0) return;
+  const int n_rec = min(a.n_recent, kp);  // no more forced pages than pages picked: the newest ones win
   uint32_t key[kVec * 4];
   float lo = INFINITY, hi = -INFINITY;
 #pragma unroll
@@ -411,7 +413,7 @@ __device__ __forceinline__ void pick_from_scores_n(const CacheView& c, const Sel
       const int pg = (v_begin + i) * 4 + e;
       const bool live = i < per && pg < P;
       float sc = live ? x[e] : -INFINITY;
-      if (live && pg >= P - a.n_recent) sc = INFINITY;
+      if (live && pg >= P - n_rec) sc = INFINITY;
       key[i * 4 + e] = f32_order_key(sc);
       if (live) {
         if (fabsf(sc) < INFINITY) {

@@ -1,0 +1,100 @@
+"""Seeded random configurations of the decode step with token append: head counts, group size, page
+size, V layout, budgets, forced recent pages, ragged lengths (short and empty sequences included),
+shuffled block tables.  Every case runs a few steps and is checked against the oracle the way the
+fixed cases are: both top-k picks within the band, attention on the GPU's own page list, cache and
+summaries bit-exact at the end."""
+import sys
+
+import numpy as np
+import pytest
+
+from paper_2502_14051_amd import workloads as wl
+from helpers import assert_attention_close, to_device_cache
+from test_gpu_parity import check_selection, small
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    from paper_2502_14051_amd import rocketkv as rk
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    rk.lib()
+    return torch, rk, torch.device("cuda:0")
+
+
+def draw(seed):
+    r = np.random.default_rng(1000 + seed)
+    token_major = bool(r.integers(0, 2))
+    ps = int(r.choice([1, 2, 3, 4, 5, 8, 16, 32, 64])) if token_major else 16
+    G = int(r.choice([1, 2, 3, 4, 6, 8]))
+    Hkv = int(r.choice([1, 2, 3, 4]))
+    batch = int(r.integers(1, 4))
+    ctx = int(r.integers(40, 2600))
+    k1 = int(r.choice([1, 8, 32, 33, 64, 100, 128]))
+    T = int(r.integers(ps, max(ps + 1, min(ctx, 700))))
+    n_recent = int(r.choice([0, 0, 1, 2]))
+    steps = int(r.integers(3, 20))
+    lens = [ctx] + [int(r.choice([ctx, ctx - 1, max(0, ctx // 3), int(r.integers(0, ctx)), 0]))
+                    for _ in range(batch - 1)]
+    return dict(token_major=token_major, ps=ps, G=G, Hkv=Hkv, batch=batch, ctx=ctx, k1=k1, T=T,
+                n_recent=n_recent, steps=steps, lens=lens, shuffle=bool(r.integers(0, 2)))
+
+
+@pytest.mark.parametrize("seed", range(48))
+def test_random_decode_append(env, oracle, seed):
+    torch, rk, dev = env
+    p = draw(seed)
+    print("[case] random", seed, p, flush=True)
+    sys.stdout.flush()
+    ps, k1, T, steps, ctx, B = p["ps"], p["k1"], p["T"], p["steps"], p["ctx"], p["batch"]
+    w = small("tiny", batch=B, n_q_heads=p["G"] * p["Hkv"], n_kv_heads=p["Hkv"], context=ctx, page_size=ps,
+              channel_budget=k1, token_budget=T, n_heavy=4, seed=seed)
+    full = wl.generate(wl.scaled(w, context=ctx + steps))
+    lens = np.array(p["lens"], dtype=np.int32)
+    d0 = dict(full)
+    d0["K"] = np.ascontiguousarray(full["K"][:, :, :ctx])
+    d0["V"] = np.ascontiguousarray(full["V"][:, :, :ctx])
+    d0["seq_lens"] = lens.copy()
+    layout = rk.V_TOKEN_MAJOR if p["token_major"] else rk.V_CHANNEL_MAJOR
+    rng = np.random.default_rng(seed) if p["shuffle"] else None
+    cache, q = to_device_cache(rk, torch, d0, w.n_q_heads, ps, dev, pages_cap=(ctx + steps + ps - 1) // ps,
+                               shuffle_rng=rng, v_layout=layout)
+    kmax, kmin = rk.alloc_summaries(cache)
+    rk.build_page_summaries(cache, kmax, kmin)
+    Kref = np.zeros((B, w.n_kv_heads, ctx + steps, 128), dtype=np.uint16)
+    Vref = np.zeros_like(Kref)
+    for b in range(B):
+        Kref[b, :, :lens[b]] = full["K"][b, :, :lens[b]]
+        Vref[b, :, :lens[b]] = full["V"][b, :, :lens[b]]
+    row = rk.pages_row_len(cache, T)
+    out = torch.empty((B, w.n_q_heads, 128), dtype=torch.bfloat16, device=dev)
+    pages = torch.empty((B, w.n_kv_heads, row), dtype=torch.int32, device=dev)
+    chans = torch.empty((B, w.n_kv_heads, k1), dtype=torch.int32, device=dev)
+    ws = rk.alloc_workspace(rk.OP_HSA_DECODE, cache, T)
+    for s in range(steps):
+        kn, vn = full["K"][:, :, ctx + s], full["V"][:, :, ctx + s]
+        for b in range(B):
+            Kref[b, :, lens[b]] = kn[b]
+            Vref[b, :, lens[b]] = vn[b]
+        lens += 1
+        rk.hsa_decode_append(cache, q, wl.from_bits(kn, dev), wl.from_bits(vn, dev), kmax, kmin, k1, T,
+                             p["n_recent"], out, None, pages, chans, ws)
+        if s in (0, steps // 2, steps - 1):
+            torch.cuda.synchronize()
+            assert cache.seq_lens.cpu().numpy().tolist() == lens.tolist()
+            ds = dict(q=d0["q"], K=Kref, V=Vref, seq_lens=lens.copy())
+            gp, gc = pages.cpu().numpy(), chans.cpu().numpy()
+            check_selection(oracle, ds, w, cache.pages_cap, gp, gc, None, p["n_recent"])
+            want_y, _ = oracle.attend_given(ds["q"], Kref, Vref, lens, ps, gp)
+            assert_attention_close(wl.to_bits(out), want_y, f"seed {seed} step {s}")
+    Kg, Vg = rk.unpack_cache(cache)
+    Kg, Vg = wl.to_bits(Kg), wl.to_bits(Vg)
+    for b in range(B):
+        assert np.array_equal(Kg[b, :, :lens[b]], Kref[b, :, :lens[b]])
+        assert np.array_equal(Vg[b, :, :lens[b]], Vref[b, :, :lens[b]])
+    want_max, want_min = oracle.build_summaries(Kref, lens, ps, cache.pages_cap)
+    valid = ~np.isnan(want_max)
+    assert np.array_equal(wl.bf16_bits_to_f64(wl.to_bits(kmax))[valid], want_max[valid])
+    assert np.array_equal(wl.bf16_bits_to_f64(wl.to_bits(kmin))[valid], want_min[valid])
