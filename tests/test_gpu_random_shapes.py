@@ -98,3 +98,64 @@ def test_random_decode_append(env, oracle, seed):
     valid = ~np.isnan(want_max)
     assert np.array_equal(wl.bf16_bits_to_f64(wl.to_bits(kmax))[valid], want_max[valid])
     assert np.array_equal(wl.bf16_bits_to_f64(wl.to_bits(kmin))[valid], want_min[valid])
+
+
+def draw_snap(seed):
+    r = np.random.default_rng(5000 + seed)
+    G = int(r.choice([1, 2, 3, 4, 8]))
+    W = int(r.choice([w for w in (16, 32, 64, 128) if G * w <= 256]))
+    Hkv = int(r.choice([1, 2, 3]))
+    batch = int(r.integers(1, 4))
+    S = int(r.integers(W + 40, 5200))
+    N = int(r.integers(W + 8, max(W + 9, min(S + 200, 1500))))
+    ks = int(r.choice([1, 3, 7, 31, 63]))
+    lens = [S] + [min(S, int(r.choice([S, S - 1, max(W + 1, S // 2), N, max(1, N - 5), int(r.integers(1, S + 1))])))
+                  for _ in range(batch - 1)]
+    src_tm, dst_tm = bool(r.integers(0, 2)), bool(r.integers(0, 2))
+    dps = int(r.choice([1, 2, 3, 5, 16, 32])) if dst_tm else 16
+    return dict(G=G, W=W, Hkv=Hkv, batch=batch, S=S, N=N, ks=ks, lens=lens, src_tm=src_tm, dst_tm=dst_tm,
+                dps=dps, shuffle=bool(r.integers(0, 2)))
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_snapkv(env, oracle, seed):
+    from helpers import assert_topk_within_band
+    from test_gpu_parity import ragged
+    torch, rk, dev = env
+    p = draw_snap(seed)
+    print("[case] random snapkv", seed, p, flush=True)
+    sys.stdout.flush()
+    S, N, W, B = p["S"], p["N"], p["W"], p["batch"]
+    w = small("mistral_snap_128k", batch=B, n_q_heads=p["G"] * p["Hkv"], n_kv_heads=p["Hkv"], context=S,
+              snap_keep=N, window=W, n_heavy=6, seed=100 + seed)
+    d = ragged(wl.generate(w, with_obs=True), p["lens"])
+    rng = np.random.default_rng(seed) if p["shuffle"] else None
+    src, _ = to_device_cache(rk, torch, d, w.n_q_heads, 16, dev, shuffle_rng=rng,
+                             v_layout=rk.V_TOKEN_MAJOR if p["src_tm"] else rk.V_CHANNEL_MAJOR)
+    dps = p["dps"]
+    dst = rk.alloc_cache(B, w.n_q_heads, w.n_kv_heads, 128, dps, (N + dps - 1) // dps, dev, zero=True,
+                         v_layout=rk.V_TOKEN_MAJOR if p["dst_tm"] else rk.V_CHANNEL_MAJOR)
+    kept = torch.full((B, w.n_kv_heads, N), -9, dtype=torch.int32, device=dev)
+    ws = rk.alloc_workspace(rk.OP_SNAPKV, src, W, N)
+    ws.fill_(0xEE)
+    rk.workspace_init(ws)
+    rk.snapkv_compress(wl.from_bits(d["qobs"], dev), src, W, p["ks"], N, dst, kept, ws)
+    torch.cuda.synchronize()
+    ref = oracle.snapkv(d["qobs"], d["K"], d["seq_lens"], p["ks"], N, want_votes=True)
+    gk = kept.cpu().numpy()
+    assert dst.seq_lens.cpu().numpy().tolist() == ref["n_kept"].tolist()
+    Kd, Vd = rk.unpack_cache(dst)
+    Kd, Vd = wl.to_bits(Kd), wl.to_bits(Vd)
+    for b in range(B):
+        Sb = int(d["seq_lens"][b])
+        cnt = int(ref["n_kept"][b])
+        for g in range(w.n_kv_heads):
+            row = gk[b, g]
+            if Sb <= N:
+                assert row[:Sb].tolist() == list(range(Sb)) and (row[Sb:] == -1).all()
+            else:
+                L = Sb - W
+                assert row[N - W:].tolist() == list(range(L, Sb))
+                assert_topk_within_band(ref["pooled"][b, g, :L], row[:N - W], N - W, f"kept b{b} g{g}")
+            assert np.array_equal(Kd[b, g, :cnt], d["K"][b, g, row[:cnt]])
+            assert np.array_equal(Vd[b, g, :cnt], d["V"][b, g, row[:cnt]])
