@@ -568,87 +568,122 @@ __global__ __launch_bounds__(kSelT) void snap_select_fast_kernel(CacheView c, Sn
   if (g == 0 && tid == 0) a.n_out[b] = a.keep;
 }
 
-// copy the kept tokens into the destination cache; one workgroup per 16 kept tokens.  K rows move
-// as 256-byte rows.  The V values of the 16 tokens are staged in LDS as [channel][token] whatever the
-// source layout, then leave as one contiguous channel-major tile (page size 16) or as token rows.
+// copy the kept tokens into the destination cache; one workgroup per kGatherBlocks x 16 kept tokens
+// (each workgroup is a chain of dependent round trips: index, rows, stores; several blocks per
+// workgroup put several times the loads in flight behind one such chain).  K rows move as 256-byte
+// rows.  The V values of 16 tokens are staged in LDS as [channel][token] whatever the source layout,
+// then leave as one contiguous channel-major tile (page size 16) or as token rows.
+constexpr int kGatherBlocks = 4;
 __global__ __launch_bounds__(256) void snap_gather_kernel(CacheView src, CacheView dst, SnapArgs a) {
-  __shared__ int s_tok[kAttnPage];
-  __shared__ bf16_t s_v[kHeadDim * kAttnPage];
+  constexpr int NB = kGatherBlocks, NTOK = NB * kAttnPage;
+  __shared__ int s_tok[NTOK];
+  __shared__ int64_t s_src[NTOK];  // element offset of the token's source tile (page and head), or -1
+  __shared__ __align__(16) bf16_t s_v[NB][kHeadDim * kAttnPage];
   const int tid = threadIdx.x;
-  const int unit = blockIdx.y, blk = blockIdx.x;
+  const int unit = blockIdx.y, blk0 = blockIdx.x * NB;
   const int b = unit / src.n_kv_heads, g = unit % src.n_kv_heads;
   const int S = src.seq_lens[b];
   const int cnt = S > src.pages_cap * kAttnPage ? 0 : min(S, a.keep);
-  if (blk * kAttnPage >= cnt) return;
-  if (tid < kAttnPage) {
-    const int t = blk * kAttnPage + tid;
-    s_tok[tid] = t < cnt ? a.kept[(int64_t)unit * a.keep + t] : -1;
+  if (blk0 * kAttnPage >= cnt) return;
+  const int64_t dhead = (int64_t)g * dst.stride_head, shead = (int64_t)g * src.stride_head;
+  if (tid < NTOK) {
+    const int t = blk0 * kAttnPage + tid;
+    const int tok = t < cnt ? a.kept[(int64_t)unit * a.keep + t] : -1;
+    const int64_t spp = tok >= 0 ? phys_page(src, b, tok / kAttnPage) : -1;
+    s_tok[tid] = spp >= 0 ? tok : -1;
+    s_src[tid] = spp >= 0 ? spp * src.stride_page + shead : -1;
   }
   __syncthreads();
   const int dps = dst.page_size;
-  const int64_t dhead = (int64_t)g * dst.stride_head, shead = (int64_t)g * src.stride_head;
-  // K: 16 rows of 256 B; thread -> (row = tid/16, 16-byte piece = tid%16)
+  // rows: thread -> (row = tid/16 of each block, 16-byte piece = tid%16)
   const int row = tid / 16, piece = tid % 16;
-  const int tok = s_tok[row];
-  const int dt = blk * kAttnPage + row;  // destination position of this thread's row
-  const int64_t spp = tok >= 0 ? phys_page(src, b, tok / kAttnPage) : -1;
-  const int64_t dpp = dt / dps < dst.pages_cap ? phys_page(dst, b, dt / dps) : -1;
-  const bool row_live = tok >= 0 && spp >= 0;
+  int tok[NB];
+  int64_t so[NB], dof[NB];  // source tile, destination row (-1: none)
+  bool in_cnt[NB];
+#pragma unroll
+  for (int i = 0; i < NB; ++i) {
+    tok[i] = s_tok[i * kAttnPage + row];
+    so[i] = s_src[i * kAttnPage + row];
+    const int dt = (blk0 + i) * kAttnPage + row;  // destination position of this thread's row
+    in_cnt[i] = (blk0 + i) * kAttnPage < cnt;     // the block exists at all
+    const int64_t dpp = (in_cnt[i] && dt / dps < dst.pages_cap) ? phys_page(dst, b, dt / dps) : -1;
+    dof[i] = dpp >= 0 ? dpp * dst.stride_page + dhead + (dt % dps) * kHeadDim + piece * 8 : -1;
+  }
   {
-    uint4 val = make_uint4(0, 0, 0, 0);
-    if (row_live)
-      val = ld16<false>(src.k_pool + spp * src.stride_page + shead + (tok % kAttnPage) * kHeadDim + piece * 8);
+    uint4 val[NB];
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+      val[i] = make_uint4(0, 0, 0, 0);
+      if (tok[i] >= 0) val[i] = ld16<false>(src.k_pool + so[i] + (tok[i] % kAttnPage) * kHeadDim + piece * 8);
+    }
     // a channel-major destination gets whole tiles (zero rows past the end); a token-major one only
     // the rows that exist, as later pages may belong to something else
-    if (dpp >= 0 && (tok >= 0 || !dst.v_token_major))
-      *reinterpret_cast<uint4*>(dst.k_pool + dpp * dst.stride_page + dhead + (dt % dps) * kHeadDim +
-                                piece * 8) = val;
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+      if (dof[i] >= 0 && (tok[i] >= 0 || !dst.v_token_major)) *reinterpret_cast<uint4*>(dst.k_pool + dof[i]) = val[i];
   }
   if (src.v_token_major && dst.v_token_major) {
-    if (row_live && dpp >= 0)
-      *reinterpret_cast<uint4*>(dst.v_pool + dpp * dst.stride_page + dhead + (dt % dps) * kHeadDim +
-                                piece * 8) =
-          ld16<false>(src.v_pool + spp * src.stride_page + shead + (tok % kAttnPage) * kHeadDim + piece * 8);
+    uint4 val[NB];
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+      if (tok[i] >= 0) val[i] = ld16<false>(src.v_pool + so[i] + (tok[i] % kAttnPage) * kHeadDim + piece * 8);
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+      if (tok[i] >= 0 && dof[i] >= 0) *reinterpret_cast<uint4*>(dst.v_pool + dof[i]) = val[i];
     return;
   }
-  // stage V as s_v[channel][token]
+  // stage V as s_v[block][channel][token]
   if (src.v_token_major) {
-    uint4 val = make_uint4(0, 0, 0, 0);
-    if (row_live)
-      val = ld16<false>(src.v_pool + spp * src.stride_page + shead + (tok % kAttnPage) * kHeadDim + piece * 8);
-    const uint32_t w[4] = {val.x, val.y, val.z, val.w};
+    uint4 val[NB];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      s_v[(piece * 8 + 2 * i) * kAttnPage + row] = (bf16_t)(w[i] & 0xffffu);
-      s_v[(piece * 8 + 2 * i + 1) * kAttnPage + row] = (bf16_t)(w[i] >> 16);
+    for (int i = 0; i < NB; ++i) {
+      val[i] = make_uint4(0, 0, 0, 0);
+      if (tok[i] >= 0) val[i] = ld16<false>(src.v_pool + so[i] + (tok[i] % kAttnPage) * kHeadDim + piece * 8);
+    }
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+      const uint32_t w[4] = {val[i].x, val[i].y, val[i].z, val[i].w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        s_v[i][(piece * 8 + 2 * e) * kAttnPage + row] = (bf16_t)(w[e] & 0xffffu);
+        s_v[i][(piece * 8 + 2 * e + 1) * kAttnPage + row] = (bf16_t)(w[e] >> 16);
+      }
     }
   } else {
-    for (int idx = tid; idx < kHeadDim * kAttnPage; idx += 256) {
-      const int slot = idx % kAttnPage, ch = idx / kAttnPage;
-      const int tk = s_tok[slot];
-      bf16_t val = 0;
-      if (tk >= 0) {
-        const int64_t sp2 = phys_page(src, b, tk / kAttnPage);
-        if (sp2 >= 0)
-          val = src.v_pool[sp2 * src.stride_page + shead + ch * kAttnPage + tk % kAttnPage];
+    // thread -> (slot = tid%16, channels tid/16 + 16 j): all of a block's loads go out before the LDS stores
+    const int slot = tid % kAttnPage, ch0 = tid / kAttnPage;
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+      const int tk = s_tok[i * kAttnPage + slot];
+      const int64_t sv = s_src[i * kAttnPage + slot];
+      bf16_t val[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        val[j] = 0;
+        if (tk >= 0) val[j] = src.v_pool[sv + (ch0 + 16 * j) * kAttnPage + tk % kAttnPage];
       }
-      s_v[idx] = val;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) s_v[i][(ch0 + 16 * j) * kAttnPage + slot] = val[j];
     }
   }
   __syncthreads();
-  if (!dst.v_token_major) {
-    // page size 16: the staged block is the destination tile
-    if (dpp >= 0)
-      reinterpret_cast<uint4*>(dst.v_pool + dpp * dst.stride_page + dhead)[tid] =
-          reinterpret_cast<const uint4*>(s_v)[tid];
-  } else if (tok >= 0 && dpp >= 0) {
-    uint32_t w[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-      w[i] = (uint32_t)s_v[(piece * 8 + 2 * i) * kAttnPage + row] |
-             ((uint32_t)s_v[(piece * 8 + 2 * i + 1) * kAttnPage + row] << 16);
-    *reinterpret_cast<uint4*>(dst.v_pool + dpp * dst.stride_page + dhead + (dt % dps) * kHeadDim +
-                              piece * 8) = make_uint4(w[0], w[1], w[2], w[3]);
+  for (int i = 0; i < NB; ++i) {
+    if (!dst.v_token_major) {
+      // page size 16: the staged block is the destination tile
+      const int dt0 = (blk0 + i) * kAttnPage;
+      const int64_t dpp = (in_cnt[i] && dt0 / kAttnPage < dst.pages_cap) ? phys_page(dst, b, dt0 / kAttnPage) : -1;
+      if (dpp >= 0)
+        reinterpret_cast<uint4*>(dst.v_pool + dpp * dst.stride_page + dhead)[tid] =
+            reinterpret_cast<const uint4*>(s_v[i])[tid];
+    } else if (tok[i] >= 0 && dof[i] >= 0) {
+      uint32_t w[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        w[e] = (uint32_t)s_v[i][(piece * 8 + 2 * e) * kAttnPage + row] |
+               ((uint32_t)s_v[i][(piece * 8 + 2 * e + 1) * kAttnPage + row] << 16);
+      *reinterpret_cast<uint4*>(dst.v_pool + dof[i]) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
   }
 }
 
@@ -726,7 +761,7 @@ hipError_t launch_snapkv(const bf16_t* q_obs, const CacheView& src, int window, 
   else
     hipLaunchKernelGGL(snap_select_kernel, dim3(units), dim3(kSelT), 0, st, src, a);
   if (!dst) return hipGetLastError();  // filter only: the indices are the result
-  const dim3 ggrid((keep + kAttnPage - 1) / kAttnPage, units);
+  const dim3 ggrid((keep + kGatherBlocks * kAttnPage - 1) / (kGatherBlocks * kAttnPage), units);
   hipLaunchKernelGGL(snap_gather_kernel, ggrid, dim3(256), 0, st, src, *dst, a);
   return hipGetLastError();
 }
