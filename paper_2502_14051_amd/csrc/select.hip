@@ -48,7 +48,6 @@ struct ScoreLds {
 template <int NT, bool APPEND, bool PICK>
 __global__ __launch_bounds__(NT) void hsa_score_kernel(CacheView c, SelectArgs a, AppendArgs ap,
                                                        uint32_t* unit_counters, uint32_t* seq_counters) {
-  constexpr int kRuns = NT / 4;  // eight-page runs per workgroup
   __shared__ __align__(16) unsigned char lds[ScoreLds<NT, PICK>::kBytes];  // selection state, then the pick's
   __shared__ int s_n0, s_last;
   __shared__ bf16_t s_knew[kHeadDim];
@@ -90,8 +89,10 @@ __global__ __launch_bounds__(NT) void hsa_score_kernel(CacheView c, SelectArgs a
   }
   int P = (n + c.page_size - 1) / c.page_size;
   if (P > c.pages_cap) P = c.pages_cap;
-  const int o_begin = blockIdx.x * kRuns;
-  const int n_runs = min(kRuns, (P + 7) / 8 - o_begin);
+  // the runs of the cache (not just of the sequence: the split must not depend on data) in equal shares
+  const int share = ((c.pages_cap + 7) / 8 + gridDim.x - 1) / gridDim.x;  // <= NT / 4 by the launch's grid
+  const int o_begin = blockIdx.x * share;
+  const int n_runs = min(share, (P + 7) / 8 - o_begin);
   if (n_runs > 0)
     score_chunk<NT, PICK>(c, a, unit, P, sh, o_begin, n_runs, a.out_scores + (int64_t)unit * c.pages_cap, tp);
   if (writer) {
