@@ -407,15 +407,18 @@ def main():
     big = None
     if not args.no_decomposed and not args.batch and not args.layers:
         big = []
-        for Bb in (4 * B, 8 * B):
+        w70 = wl.CONFIGS["llama70b_step_b16"]  # 64 query / 8 KV heads (G = 8), same cache per layer
+        for Bb, wbase, label in ((4 * B, w, "same shape and budgets"), (8 * B, w, "same shape and budgets"),
+                                 (w70.batch, w70, "llama70b_step_b16 shape (G = 8), same budgets")):
             nlb = 8
-            wb = wl.scaled(w, batch=Bb, n_layers=nlb)
+            wb = wl.scaled(wbase, batch=Bb, n_layers=nlb)
+            Hq_b, G_b = wb.n_q_heads, wb.group
             bl = []
             snapb_ws = None
             for layer in range(nlb):
                 d = wl.generate_device(wb, layer, dev, with_obs=True)
-                srcb = rk.pack_cache(d["K"], d["V"], d["seq_lens"].cpu().numpy(), Hq, ps)
-                dstb = rk.alloc_cache(Bb, Hq, Hkv, D, ps, pages_cap, dev, zero=True)
+                srcb = rk.pack_cache(d["K"], d["V"], d["seq_lens"].cpu().numpy(), Hq_b, ps)
+                dstb = rk.alloc_cache(Bb, Hq_b, Hkv, D, ps, pages_cap, dev, zero=True)
                 if snapb_ws is None:
                     snapb_ws = rk.alloc_workspace(rk.OP_SNAPKV, srcb, W, N)
                 rk.snapkv_compress(d["qobs"], srcb, W, w.pool_kernel, N, dstb, None, snapb_ws)
@@ -427,7 +430,7 @@ def main():
                 bl.append(dict(cache=dstb, kmax=kmb, kmin=knb, q=d["q"].contiguous(),
                                new_k=torch.randn((Bb, Hkv, D), generator=gen, device=dev).bfloat16(),
                                new_v=torch.randn((Bb, Hkv, D), generator=gen, device=dev).bfloat16(),
-                               out=torch.empty((Bb, Hq, D), dtype=torch.bfloat16, device=dev),
+                               out=torch.empty((Bb, Hq_b, D), dtype=torch.bfloat16, device=dev),
                                ws=rk.alloc_workspace(rk.OP_HSA_DECODE, dstb, T)))
                 del d, srcb
             del snapb_ws
@@ -439,13 +442,17 @@ def main():
 
             big_us = timed_graph(big_all, max(2, args.kernel_reps // 2)) * 1e3 / nlb
             nb_now = int(bl[0]["cache"].seq_lens[0].item())
-            big_bytes = hsa_bytes_at((nb_now + ps - 1) // ps, ps, k1, T) * (Bb // B)
+            Pb = (nb_now + ps - 1) // ps
+            kpb = min(Pb, max(1, T // ps))
+            big_bytes = Bb * Hkv * ((kpb * ps * D * 2 * 2 + 2 * G_b * D * 2)
+                                    + (k1 * ((Pb + 7) // 8 * 8) * 2 + G_b * D * 2 + kpb * 4)
+                                    + (2 * D * 2 + 2 * D * 2 * 2))
             big_gbs = big_bytes / (big_us * 1e-6) / 1e9
-            big.append({"workload": f"same shape and budgets, batch {Bb}, {nlb} layers",
+            big.append({"workload": f"{label}, batch {Bb}, {nlb} layers",
                         "us_per_layer_step": round(big_us, 3), "bytes_per_layer_step": big_bytes,
                         "achieved_GBs": round(big_gbs, 1), "frac_of_hbm_peak": round(big_gbs / HBM_PEAK_GBS, 4),
-                        "decode_tokens_per_s_attention_only_32_layers":
-                            round(Bb / (big_us * 1e-6 * w.n_layers), 1)})
+                        "decode_tokens_per_s_attention_only_all_layers":
+                            round(Bb / (big_us * 1e-6 * wbase.n_layers), 1)})
             del bl
             torch.cuda.empty_cache()
 
@@ -532,7 +539,7 @@ def main():
         "decomposed_operating_point": dec_pt,
         "multi_turn_variant": mt_pt,
         "single_layer_batch1": single,
-        "larger_batches_same_shape": big,
+        "other_shapes_and_batches": big,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))
