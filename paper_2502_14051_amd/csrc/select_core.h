@@ -134,11 +134,13 @@ __device__ __forceinline__ void select_channels(const CacheView& c, const Select
     sh.s_sum[tid] = ss;
   }
   __syncthreads();
-  // ---- i1: rank by counting, compact ascending --------------------------------------------------
-  // every thread ranks channel (tid mod 128) against one slice of the channels, 4 at a time
+  // ---- i1: rank by counting ---------------------------------------------------------------------
+  // kParts neighbouring lanes rank one channel against a slice of the channels each (4 LDS values per
+  // read) and add up; ranks are unique (ties go to the lower channel), so the k1 picked channels go
+  // straight to slot `rank`: no compaction, and the order of the score sums stays fixed.
+  constexpr int kParts = NT / kHeadDim, kSlice = kHeadDim / kParts;
   {
-    constexpr int kParts = NT / kHeadDim, kSlice = kHeadDim / kParts;
-    const int ch = tid & (kHeadDim - 1), part = tid / kHeadDim;
+    const int ch = tid / kParts, part = tid % kParts;
     const float mine = sh.s_abs[ch];
     const float4* v4 = reinterpret_cast<const float4*>(sh.s_abs + part * kSlice);
     int rank = 0;
@@ -151,26 +153,29 @@ __device__ __forceinline__ void select_channels(const CacheView& c, const Select
       rank += (v.z > mine) || (v.z == mine && o + 2 < ch);
       rank += (v.w > mine) || (v.w == mine && o + 3 < ch);
     }
-    sh.s_rank[tid] = rank;
-  }
-  __syncthreads();
-  bool sel = false;
-  if (tid < kHeadDim) {
-    int rank = 0;
 #pragma unroll
-    for (int part = 0; part < NT / kHeadDim; ++part) rank += sh.s_rank[tid + part * kHeadDim];
-    sel = rank < a.k1;
-  }
-  const unsigned long long bal = __ballot(sel);
-  if (tid == 0) sh.cnt0 = (uint32_t)__popcll(bal);
-  __syncthreads();
-  if (sel) {
-    const int pos = __popcll(bal & ((1ull << lane) - 1ull)) + (wave == 1 ? (int)sh.cnt0 : 0);
-    sh.s_chan[pos] = tid;
-    sh.s_wgt[pos] = sh.s_sum[tid];
-    if (write_global && a.out_channels) a.out_channels[(int64_t)unit * a.k1 + pos] = tid;
+    for (int off = 1; off < kParts; off <<= 1) rank += __shfl_xor(rank, off);
+    if (part == 0) {
+      sh.s_rank[ch] = rank;
+      if (rank < a.k1) {
+        sh.s_chan[rank] = ch;
+        sh.s_wgt[rank] = sh.s_sum[ch];
+      }
+    }
   }
   __syncthreads();
+  // the caller's copy of i1 is ascending by channel: compacted here, only when it is asked for
+  if (write_global && a.out_channels) {
+    bool sel = false;
+    if (tid < kHeadDim) sel = sh.s_rank[tid] < a.k1;
+    const unsigned long long bal = __ballot(sel);
+    if (tid == 0) sh.cnt0 = (uint32_t)__popcll(bal);
+    __syncthreads();
+    if (sel) {
+      const int pos = __popcll(bal & ((1ull << lane) - 1ull)) + (wave == 1 ? (int)sh.cnt0 : 0);
+      a.out_channels[(int64_t)unit * a.k1 + pos] = tid;
+    }
+  }
 }
 
 // The kp-th largest of the P order keys in `keys` (LDS) by four 8-bit radix passes, as (tau, need_eq):
