@@ -181,18 +181,21 @@ __device__ __forceinline__ void select_channels(const CacheView& c, const Select
 // The kp-th largest of the P order keys in `keys` (LDS) by four 8-bit radix passes, as (tau, need_eq):
 // the selection is every key above tau plus the first need_eq keys equal to it.  Needs kp < P and
 // `hist` (LDS, 4 x 256 counters, 16-byte aligned) zeroed; every thread gets the result.
-template <int NT>
+// FIRST_DONE: the caller has already counted every key's top digit into hist[0] (and synchronised).
+template <int NT, bool FIRST_DONE = false>
 __device__ __forceinline__ void radix_threshold(const uint32_t* keys, int P, int kp, uint32_t (*hist)[256],
                                                 uint32_t& tau, uint32_t& need_eq) {
   const int tid = threadIdx.x, lane = tid % kWave;
   uint32_t prefix = 0, mask = 0, k = (uint32_t)kp;
   for (int pass = 0; pass < 4; ++pass) {
     const int shift = 24 - 8 * pass;
-    for (int p = tid; p < P; p += NT) {
-      const uint32_t key = keys[p];
-      if ((key & mask) == prefix) atomicAdd(&hist[pass][(key >> shift) & 255u], 1u);
+    if (!(FIRST_DONE && pass == 0)) {
+      for (int p = tid; p < P; p += NT) {
+        const uint32_t key = keys[p];
+        if ((key & mask) == prefix) atomicAdd(&hist[pass][(key >> shift) & 255u], 1u);
+      }
+      __syncthreads();
     }
-    __syncthreads();
     // every wavefront finds the bucket holding the k-th largest on its own (no broadcast needed):
     // lane L owns bins 4(63-L)..4(63-L)+3, so a prefix sum over lanes counts the keys in higher bins
     const int b0 = 4 * (kWave - 1 - lane);
@@ -276,7 +279,9 @@ __device__ __forceinline__ int select_pages(const CacheView& c, const SelectArgs
         if (p < P && out_scores) out_scores[(int64_t)unit * c.pages_cap + p] = s;
         if (p >= P) s = -INFINITY;
         else if (p >= P - n_rec) s = INFINITY;
-        keys[p] = f32_order_key(s);
+        const uint32_t key = f32_order_key(s);
+        keys[p] = key;
+        if (p < P) atomicAdd(&sh.hist[0][key >> 24], 1u);  // the first radix pass, counted on the way
       }
     }
   } else {
@@ -295,7 +300,9 @@ __device__ __forceinline__ int select_pages(const CacheView& c, const SelectArgs
         if (p < P && out_scores) out_scores[(int64_t)unit * c.pages_cap + p] = s;
         if (p >= P) s = -INFINITY;
         else if (p >= P - n_rec) s = INFINITY;
-        keys[p] = f32_order_key(s);
+        const uint32_t key = f32_order_key(s);
+        keys[p] = key;
+        if (p < P) atomicAdd(&sh.hist[0][key >> 24], 1u);  // the first radix pass, counted on the way
       }
     }
   }
@@ -303,7 +310,7 @@ __device__ __forceinline__ int select_pages(const CacheView& c, const SelectArgs
 
   // ---- i2: exact kp-th largest key by 4 x 8-bit radix passes -------------------------------------
   uint32_t tau = 0, need_eq = (uint32_t)P;  // defaults select everything (kp == P)
-  if (kp < P) radix_threshold<NT>(keys, P, kp, sh.hist, tau, need_eq);
+  if (kp < P) radix_threshold<NT, true>(keys, P, kp, sh.hist, tau, need_eq);
 
   // ---- emit ascending: every key > tau, plus the first need_eq keys == tau -----------------------
   const int ipt = (P + NT - 1) / NT;
