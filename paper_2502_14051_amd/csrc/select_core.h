@@ -33,8 +33,9 @@ struct SelectShared {
   uint32_t cnt0;
 };
 
-// exclusive prefix sum of one uint32 per thread over the NT-thread workgroup
-template <int NT>
+// exclusive prefix sum of one uint32 per thread over the NT-thread workgroup.  REUSE = false leaves
+// out the trailing barrier, for a caller that does not touch `wsum` again before its next barrier.
+template <int NT, bool REUSE = true>
 __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* wsum) {
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
   const uint32_t inc = wave_incl_scan(v);
@@ -42,7 +43,7 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* wsum) 
   __syncthreads();
   uint32_t base = 0;
   for (int w = 0; w < wave; ++w) base += wsum[w];
-  __syncthreads();
+  if (REUSE) __syncthreads();
   return base + inc - v;
 }
 
@@ -321,7 +322,7 @@ __device__ __forceinline__ int select_pages(const CacheView& c, const SelectArgs
     cnt += (key > tau) ? 1u : 0u;
     cnt += (key == tau) ? 0x10000u : 0u;
   }
-  const uint32_t before = block_excl_scan<NT>(cnt, sh.wsum);
+  const uint32_t before = block_excl_scan<NT, false>(cnt, sh.wsum);  // the caller's barrier follows
   uint32_t gt = before & 0xffffu, eq = before >> 16;
   for (int p = lo; p < hi; ++p) {
     const uint32_t key = keys[p];
