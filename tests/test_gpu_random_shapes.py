@@ -159,3 +159,67 @@ def test_random_snapkv(env, oracle, seed):
                 assert_topk_within_band(ref["pooled"][b, g, :L], row[:N - W], N - W, f"kept b{b} g{g}")
             assert np.array_equal(Kd[b, g, :cnt], d["K"][b, g, row[:cnt]])
             assert np.array_equal(Vd[b, g, :cnt], d["V"][b, g, row[:cnt]])
+
+
+@pytest.mark.parametrize("token_major,ps", [(False, 16), (True, 16), (True, 4)])
+def test_absent_pages_are_skipped(env, oracle, token_major, ps):
+    """Block-table entries outside the pool mark absent pages: attention leaves their tokens out (here
+    checked as the oracle's attention over the list of the pages that are present), the summary build
+    writes neutral zeros for them, and the decode step still runs (its attention equals the oracle's on
+    the pages it reports, minus the absent ones)."""
+    torch, rk, dev = env
+    w = small("tiny", batch=2, n_q_heads=8, n_kv_heads=2, context=900, page_size=ps, token_budget=256, n_heavy=4)
+    print("[case] absent pages", token_major, ps, flush=True)
+    sys.stdout.flush()
+    d = wl.generate(w)
+    layout = rk.V_TOKEN_MAJOR if token_major else rk.V_CHANNEL_MAJOR
+    cache, q = to_device_cache(rk, torch, d, w.n_q_heads, ps, dev, shuffle_rng=np.random.default_rng(3),
+                               v_layout=layout)
+    P = (w.context + ps - 1) // ps
+    rng = np.random.default_rng(17)
+    gone = [sorted(rng.choice(P, size=5, replace=False).tolist()) for _ in range(w.batch)]
+    bt = cache.block_table.cpu().numpy().copy()
+    for b in range(w.batch):
+        for i, p in enumerate(gone[b]):
+            bt[b, p] = -1 if i % 2 == 0 else int(cache.k_pool.shape[0]) + 7  # below and above the pool
+    cache.block_table.copy_(torch.from_numpy(bt).to(dev))
+    present = np.full((w.batch, w.n_kv_heads, P), -1, dtype=np.int32)
+    for b in range(w.batch):
+        keep = [p for p in range(P) if p not in gone[b]]
+        present[b, :, :len(keep)] = keep
+    # dense decode == attention over the present pages
+    out = torch.empty((w.batch, w.n_q_heads, 128), dtype=torch.bfloat16, device=dev)
+    lse = torch.empty((w.batch, w.n_q_heads), dtype=torch.float32, device=dev)
+    ws = rk.alloc_workspace(rk.OP_DENSE_DECODE, cache)
+    rk.dense_decode(cache, q, out, lse, ws)
+    torch.cuda.synchronize()
+    want_y, want_lse = oracle.attend_given(d["q"], d["K"], d["V"], d["seq_lens"], ps, present)
+    assert_attention_close(wl.to_bits(out), want_y, "dense with absent pages")
+    np.testing.assert_allclose(lse.cpu().numpy(), want_lse, rtol=1e-3, atol=1e-3)
+    # summaries: zeros in the absent columns, the oracle's values elsewhere
+    kmax, kmin = rk.alloc_summaries(cache)
+    rk.build_page_summaries(cache, kmax, kmin)
+    torch.cuda.synchronize()
+    want_max, want_min = oracle.build_summaries(d["K"], d["seq_lens"], ps, cache.pages_cap)
+    gmax, gmin = wl.bf16_bits_to_f64(wl.to_bits(kmax)), wl.bf16_bits_to_f64(wl.to_bits(kmin))
+    for b in range(w.batch):
+        for p in range(P):
+            if p in gone[b]:
+                assert (gmax[b, :, :, p] == 0).all() and (gmin[b, :, :, p] == 0).all()
+            else:
+                assert np.array_equal(gmax[b, :, :, p], want_max[b, :, :, p])
+                assert np.array_equal(gmin[b, :, :, p], want_min[b, :, :, p])
+    # the decode step: whatever it picks, absent pages contribute nothing
+    row = rk.pages_row_len(cache, w.token_budget)
+    pages = torch.empty((w.batch, w.n_kv_heads, row), dtype=torch.int32, device=dev)
+    wsd = rk.alloc_workspace(rk.OP_HSA_DECODE, cache, w.token_budget)
+    rk.hsa_decode(cache, q, kmax, kmin, w.channel_budget, w.token_budget, 0, out, None, pages, None, wsd)
+    torch.cuda.synchronize()
+    gp = pages.cpu().numpy()
+    eff = np.full_like(gp, -1)
+    for b in range(w.batch):
+        for g in range(w.n_kv_heads):
+            v = [p for p in gp[b, g] if p >= 0 and p not in gone[b]]
+            eff[b, g, :len(v)] = v
+    want_y, _ = oracle.attend_given(d["q"], d["K"], d["V"], d["seq_lens"], ps, eff)
+    assert_attention_close(wl.to_bits(out), want_y, "decode with absent pages")
