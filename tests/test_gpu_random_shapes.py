@@ -223,3 +223,72 @@ def test_absent_pages_are_skipped(env, oracle, token_major, ps):
             eff[b, g, :len(v)] = v
     want_y, _ = oracle.attend_given(d["q"], d["K"], d["V"], d["seq_lens"], ps, eff)
     assert_attention_close(wl.to_bits(out), want_y, "decode with absent pages")
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_multi_turn_decode(env, oracle, seed):
+    """RocketKV-MT decode over a random index (random subset per (sequence, KV head), random logical
+    page size, cache paged independently), a few decode-with-append steps, then the decode checked
+    against the oracle on the arrays gathered through the index."""
+    from test_gpu_multi_turn import decode_check
+    torch, rk, dev = env
+    r = np.random.default_rng(9000 + seed)
+    lps = int(r.choice([1, 2, 3, 4, 8, 16]))
+    cache_ps = int(r.choice([4, 5, 16, 32]))
+    G, Hkv, B = int(r.choice([1, 2, 4])), int(r.choice([1, 2, 3])), int(r.integers(1, 4))
+    S = int(r.integers(200, 1800))
+    k1 = int(r.choice([8, 32, 70, 128]))
+    n_idx0 = int(r.integers(20, min(S, 600)))
+    T = int(r.integers(lps, max(lps + 1, n_idx0)))
+    steps = int(r.integers(2, 9))
+    print("[case] random multi-turn", seed, dict(lps=lps, cache_ps=cache_ps, G=G, Hkv=Hkv, B=B, S=S, k1=k1,
+                                                 n_idx0=n_idx0, T=T, steps=steps), flush=True)
+    sys.stdout.flush()
+    w = small("tiny", batch=B, n_q_heads=G * Hkv, n_kv_heads=Hkv, context=S + steps, page_size=lps,
+              channel_budget=k1, token_budget=T, n_heavy=4, seed=300 + seed)
+    full = wl.generate(w)
+    lens = np.array([S] + [int(r.integers(n_idx0, S + 1)) for _ in range(B - 1)], dtype=np.int32)
+    d0 = dict(q=full["q"], K=np.ascontiguousarray(full["K"][:, :, :S]), V=np.ascontiguousarray(full["V"][:, :, :S]),
+              seq_lens=lens.copy())
+    cap_tokens = S + steps + 3
+    cache, q = to_device_cache(rk, torch, d0, w.n_q_heads, cache_ps, dev,
+                               pages_cap=(cap_tokens + cache_ps - 1) // cache_ps,
+                               shuffle_rng=np.random.default_rng(seed), v_layout=rk.V_TOKEN_MAJOR)
+    index = rk.alloc_index(cache, lps, n_idx0 + steps + 5)
+    cap = index.pages_cap * lps
+    idx = np.full((B, Hkv, cap), -1, dtype=np.int32)
+    n_idx = np.array([n_idx0] + [int(r.integers(0, n_idx0 + 1)) for _ in range(B - 1)], dtype=np.int32)
+    for b in range(B):
+        for g in range(Hkv):
+            idx[b, g, :n_idx[b]] = np.sort(r.choice(int(lens[b]), size=n_idx[b], replace=False))
+    index.token_index.copy_(torch.from_numpy(idx).to(dev))
+    index.n_indexed.copy_(torch.from_numpy(n_idx).to(dev))
+    kmax, kmin = rk.alloc_index_summaries(cache, index)
+    rk.mt_build_page_summaries(cache, index, kmax, kmin)
+    ws = rk.mt_alloc_workspace(cache, index, T)
+    Kfull = np.zeros((B, Hkv, cache.pages_cap * cache_ps, 128), dtype=np.uint16)
+    Vfull = np.zeros_like(Kfull)
+    for b in range(B):
+        Kfull[b, :, :lens[b]] = full["K"][b, :, :lens[b]]
+        Vfull[b, :, :lens[b]] = full["V"][b, :, :lens[b]]
+    objs = (cache, index, kmax, kmin, ws)
+    wlog = wl.scaled(w, page_size=lps)
+    decode_check(env, oracle, objs, wlog, full["q"], Kfull, Vfull, n_recent=int(r.integers(0, 2)))
+    out = torch.empty((B, w.n_q_heads, 128), dtype=torch.bfloat16, device=dev)
+    lens_now = lens.copy()
+    for s in range(steps):
+        kn, vn = full["K"][:, :, S + s], full["V"][:, :, S + s]
+        for b in range(B):
+            Kfull[b, :, lens_now[b]] = kn[b]
+            Vfull[b, :, lens_now[b]] = vn[b]
+        rk.mt_hsa_decode_append(cache, index, q, wl.from_bits(kn, dev), wl.from_bits(vn, dev), kmax, kmin, k1, T,
+                                1, out, None, None, None, ws)
+        lens_now += 1
+    torch.cuda.synchronize()
+    assert cache.seq_lens.cpu().numpy().tolist() == lens_now.tolist()
+    assert index.n_indexed.cpu().numpy().tolist() == (n_idx + steps).tolist()
+    Kc, nl = decode_check(env, oracle, objs, wlog, full["q"], Kfull, Vfull, n_recent=1)
+    want_max, want_min = oracle.build_summaries(Kc, nl.astype(np.int32), lps, index.pages_cap)
+    valid = ~np.isnan(want_max)
+    assert np.array_equal(wl.bf16_bits_to_f64(wl.to_bits(kmax))[valid], want_max[valid])
+    assert np.array_equal(wl.bf16_bits_to_f64(wl.to_bits(kmin))[valid], want_min[valid])
