@@ -113,3 +113,72 @@ def test_graph_replay_equals_eager(env, name, ps, k1, T, ctx, layout, mt):
     assert torch.equal(A["kmax"], B["kmax"]) and torch.equal(A["kmin"], B["kmin"])
     if mt:
         assert torch.equal(A["index"].token_index, B["index"].token_index)
+
+
+def test_long_decode_256_graph_replays(env, oracle):
+    """The long-decode configuration (a cache of 8192 kept tokens, budget 2048, 256 generated tokens)
+    driven by one captured step replayed 256 times: every replay equals the eager step on a twin
+    cache, pages are crossed 16 times, and the end state agrees with the oracle."""
+    from helpers import assert_attention_close
+    from test_gpu_parity import check_selection
+    torch, rk, dev = env
+    steps, n0, T, k1 = 256, 8192, 2048, 32
+    w = small("mistral_snap_128k", context=n0 + steps, token_budget=T, channel_budget=k1, n_heavy=32)
+    say("256 graph replays", w.name, n0, T)
+    full = wl.generate(w)
+    Hq, Hkv = w.n_q_heads, w.n_kv_heads
+    d0 = dict(q=full["q"], K=np.ascontiguousarray(full["K"][:, :, :n0]), V=np.ascontiguousarray(full["V"][:, :, :n0]),
+              seq_lens=np.array([n0], dtype=np.int32))
+
+    def make():
+        cache, _ = to_device_cache(rk, torch, d0, Hq, 16, dev, pages_cap=(n0 + steps) // 16 + 1,
+                                   shuffle_rng=np.random.default_rng(5))
+        kmax, kmin = rk.alloc_summaries(cache)
+        rk.build_page_summaries(cache, kmax, kmin)
+        row = rk.pages_row_len(cache, T)
+        return dict(cache=cache, kmax=kmax, kmin=kmin, ws=rk.alloc_workspace(rk.OP_HSA_DECODE, cache, T),
+                    out=torch.zeros((1, Hq, 128), dtype=torch.bfloat16, device=dev),
+                    pages=torch.zeros((1, Hkv, row), dtype=torch.int32, device=dev))
+
+    A, B = make(), make()
+    q = wl.from_bits(full["q"], dev)
+    kn = torch.zeros((1, Hkv, 128), dtype=torch.bfloat16, device=dev)
+    vn = torch.zeros((1, Hkv, 128), dtype=torch.bfloat16, device=dev)
+
+    def step(S, stream):
+        rk.hsa_decode_append(S["cache"], q, kn, vn, S["kmax"], S["kmin"], k1, T, 1, S["out"], None, S["pages"],
+                             None, S["ws"], stream)
+
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step(A, side)
+    torch.cuda.synchronize()
+    Kall, Vall = wl.from_bits(full["K"], dev), wl.from_bits(full["V"], dev)
+    for s in range(steps):
+        kn.copy_(Kall[:, :, n0 + s])
+        vn.copy_(Vall[:, :, n0 + s])
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            graph.replay()
+        side.synchronize()
+        step(B, None)
+        torch.cuda.synchronize()
+        assert torch.equal(A["out"], B["out"]), f"replay {s}: outputs differ"
+        assert torch.equal(A["pages"], B["pages"]), f"replay {s}: page lists differ"
+    assert A["cache"].seq_lens.cpu().numpy().tolist() == [n0 + steps]
+    assert torch.equal(A["cache"].k_pool, B["cache"].k_pool) and torch.equal(A["cache"].v_pool, B["cache"].v_pool)
+    assert torch.equal(A["kmax"], B["kmax"]) and torch.equal(A["kmin"], B["kmin"])
+    # the end state against the oracle
+    lens = np.array([n0 + steps], dtype=np.int32)
+    want_max, want_min = oracle.build_summaries(full["K"], lens, 16, A["cache"].pages_cap)
+    valid = ~np.isnan(want_max)
+    assert np.array_equal(wl.bf16_bits_to_f64(wl.to_bits(A["kmax"]))[valid], want_max[valid])
+    assert np.array_equal(wl.bf16_bits_to_f64(wl.to_bits(A["kmin"]))[valid], want_min[valid])
+    ds = dict(q=full["q"], K=full["K"], V=full["V"], seq_lens=lens)
+    gp = A["pages"].cpu().numpy()
+    check_selection(oracle, ds, wl.scaled(w, context=n0 + steps), A["cache"].pages_cap, gp, None, None, 1)
+    want_y, _ = oracle.attend_given(full["q"], full["K"], full["V"], lens, 16, gp)
+    assert_attention_close(wl.to_bits(A["out"]), want_y, "last replay")
