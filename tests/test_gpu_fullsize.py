@@ -251,3 +251,22 @@ def test_decomposed_point_full_shape_sampled(env, oracle):
         want_max, want_min = oracle.page_summaries(Ku, ps)
         assert np.array_equal(wl.bf16_bits_to_f64(wl.to_bits(kmax[b, g, :, :P])), want_max)
         assert np.array_equal(wl.bf16_bits_to_f64(wl.to_bits(kmin[b, g, :, :P])), want_min)
+
+
+def test_recall_curve_diagnostic(env, capsys, monkeypatch):
+    """The recall-against-budget diagnostic runs through the library and shows what Section 4.1 reports:
+    token-granular selection finds every planted token at a budget where 16-token pages cannot, and
+    recall does not fall as the budget grows."""
+    import json
+    import sys as _sys
+    from paper_2502_14051_amd import recall_curve
+    monkeypatch.setattr(_sys, "argv", ["recall_curve", "--budgets", "128,512,2048", "--context", "8192", "--json"])
+    recall_curve.main()
+    rows = json.loads(capsys.readouterr().out.strip().splitlines()[-1])
+    by = {(r["setting"], r["token_budget"]): r for r in rows}
+    assert by[("exact-topk", 128)]["recall"] == 1.0
+    assert by[("hsa", 128)]["recall"] < 1.0
+    for s in ("hsa", "quest-like", "exact-topk", "decomposed"):
+        rec = [by[(s, t)]["recall"] for t in (128, 512, 2048)]
+        assert rec == sorted(rec)
+        assert by[(s, 2048)]["recall"] == 1.0 and by[(s, 2048)]["rel_err"] < 0.01
