@@ -408,17 +408,19 @@ def main():
     if not args.no_decomposed and not args.batch and not args.layers:
         big = []
         w70 = wl.CONFIGS["llama70b_step_b16"]  # 64 query / 8 KV heads (G = 8), same cache per layer
+        wmha = wl.scaled(w, n_kv_heads=w.n_q_heads)  # LongChat-7B-like: 32 heads, no grouping
         for Bb, wbase, label in ((4 * B, w, "same shape and budgets"), (8 * B, w, "same shape and budgets"),
-                                 (w70.batch, w70, "llama70b_step_b16 shape (G = 8), same budgets")):
+                                 (w70.batch, w70, "llama70b_step_b16 shape (G = 8), same budgets"),
+                                 (B, wmha, "multi-head shape (32 KV heads, G = 1), same budgets")):
             nlb = 8
             wb = wl.scaled(wbase, batch=Bb, n_layers=nlb)
-            Hq_b, G_b = wb.n_q_heads, wb.group
+            Hq_b, G_b, Hkv_b = wb.n_q_heads, wb.group, wb.n_kv_heads
             bl = []
             snapb_ws = None
             for layer in range(nlb):
                 d = wl.generate_device(wb, layer, dev, with_obs=True)
                 srcb = rk.pack_cache(d["K"], d["V"], d["seq_lens"].cpu().numpy(), Hq_b, ps)
-                dstb = rk.alloc_cache(Bb, Hq_b, Hkv, D, ps, pages_cap, dev, zero=True)
+                dstb = rk.alloc_cache(Bb, Hq_b, Hkv_b, D, ps, pages_cap, dev, zero=True)
                 if snapb_ws is None:
                     snapb_ws = rk.alloc_workspace(rk.OP_SNAPKV, srcb, W, N)
                 rk.snapkv_compress(d["qobs"], srcb, W, w.pool_kernel, N, dstb, None, snapb_ws)
@@ -428,8 +430,8 @@ def main():
                 gen = torch.Generator(device=dev)
                 gen.manual_seed(88_000 + layer)
                 bl.append(dict(cache=dstb, kmax=kmb, kmin=knb, q=d["q"].contiguous(),
-                               new_k=torch.randn((Bb, Hkv, D), generator=gen, device=dev).bfloat16(),
-                               new_v=torch.randn((Bb, Hkv, D), generator=gen, device=dev).bfloat16(),
+                               new_k=torch.randn((Bb, Hkv_b, D), generator=gen, device=dev).bfloat16(),
+                               new_v=torch.randn((Bb, Hkv_b, D), generator=gen, device=dev).bfloat16(),
                                out=torch.empty((Bb, Hq_b, D), dtype=torch.bfloat16, device=dev),
                                ws=rk.alloc_workspace(rk.OP_HSA_DECODE, dstb, T)))
                 del d, srcb
@@ -444,7 +446,7 @@ def main():
             nb_now = int(bl[0]["cache"].seq_lens[0].item())
             Pb = (nb_now + ps - 1) // ps
             kpb = min(Pb, max(1, T // ps))
-            big_bytes = Bb * Hkv * ((kpb * ps * D * 2 * 2 + 2 * G_b * D * 2)
+            big_bytes = Bb * Hkv_b * ((kpb * ps * D * 2 * 2 + 2 * G_b * D * 2)
                                     + (k1 * ((Pb + 7) // 8 * 8) * 2 + G_b * D * 2 + kpb * 4)
                                     + (2 * D * 2 + 2 * D * 2 * 2))
             big_gbs = big_bytes / (big_us * 1e-6) / 1e9
