@@ -195,6 +195,7 @@ def test_layouts_agree_at_page_16(env, oracle):
     (3, 62, 96, 400),      # small summaries: append launch, one selection launch, attention
     (2, 128, 96, 1100),    # large summaries: the score launch takes the token in, then top-k, attention
     (1, 128, 64, 700),     # Exact-TopK setting, every step opens a new page
+    (1, 40, 500, 9000),    # more than 8192 pages: the scores go through memory, with the token taken in
 ])
 def test_decode_append_token_major(env, oracle, ps, k1, T, ctx):
     """A run of decode steps with the new token folded in, small pages."""
