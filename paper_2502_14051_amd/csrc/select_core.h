@@ -351,6 +351,25 @@ __device__ __forceinline__ float f32_from_order_key(uint32_t k) {
   return __uint_as_float((k & 0x80000000u) ? (k ^ 0x80000000u) : ~k);
 }
 
+// One count into `hist[bin]` for every lane with `on`, where many lanes of a wavefront may share a
+// bin: up to two rounds in which the first pending lane's bin is counted once for all lanes that
+// hold it, then plain atomics for whatever is left.
+__device__ __forceinline__ void hist_add_grouped(uint32_t* hist, uint32_t bin, bool on) {
+  const int lane = threadIdx.x % kWave;
+  unsigned long long todo = __ballot(on);
+#pragma unroll
+  for (int it = 0; it < 2; ++it) {
+    if (todo == 0) break;  // the same for the whole wavefront
+    const int leader = __ffsll((long long)todo) - 1;
+    const uint32_t b = (uint32_t)__builtin_amdgcn_readlane((int)bin, leader);
+    const unsigned long long same = __ballot(on && bin == b);
+    if (lane == leader) atomicAdd(&hist[b], (uint32_t)__popcll(same));
+    on = on && bin != b;
+    todo &= ~same;
+  }
+  if (on) atomicAdd(&hist[bin], 1u);
+}
+
 // Step 2's top-k (Algorithm 1, i2) on page scores that an earlier launch left in a.in_scores: the
 // pick of the large-summary path.  A thread keeps its contiguous run of a few scores in registers
 // from the one batch of loads to the ordered emission, so no pass waits on LDS reads.
@@ -377,7 +396,10 @@ struct PickShared {
 // write-through stores): they are read with device-scope loads, which do not trust this XCD's L2.
 // kVec: float4 loads per thread, i.e. NT * kVec * 4 >= pages_cap (the wrapper below picks it).
 // sh.hist must be all zero on entry (the caller clears it, and synchronises, before the call).
-template <int NT, bool COHERENT, int kVec>
+// SKEWED: for values that pile up in a few exponents with a long tail above them (attention votes),
+// where equal-width value bins would put nearly everything into the lowest one: the bins are laid
+// on the ordered bit pattern instead, and the radix fallback counts with hist_add_grouped.
+template <int NT, bool COHERENT, int kVec, bool SKEWED = false>
 __device__ __forceinline__ void pick_from_scores_n(const CacheView& c, const SelectArgs& a, int unit, int n,
                                                    PickShared<NT>& sh) {
   constexpr int NB = 1024, BPT = NB / NT, CAP = 1024;
@@ -459,13 +481,17 @@ __device__ __forceinline__ void pick_from_scores_n(const CacheView& c, const Sel
       lo = fminf(lo, sh.wmin[w]);
       hi = fmaxf(hi, sh.wmax[w]);
     }
-    const float scale = (float)(NB - 1) / (hi - lo);
+    // SKEWED: equal-width bins on the ordered bit pattern instead of the value, i.e. roughly on its
+    // logarithm, which is just as monotone
+    const uint32_t klo = f32_order_key(lo);
+    const float scale = SKEWED ? (float)(NB - 1) / (float)(f32_order_key(hi) - klo) : (float)(NB - 1) / (hi - lo);
     bool decided = (hi > lo) && (scale < 3.0e38f);  // same for every thread
     if (decided) {
       const auto bin_of = [&](uint32_t k) -> int {
         const float f = f32_from_order_key(k);
         if (f == INFINITY) return NB - 1;
-        const int b = (int)((f - lo) * scale);
+        // (a masked-out entry lies below klo: the difference wraps, the clamp catches it)
+        const int b = SKEWED ? (int)fminf((float)(k - klo) * scale, (float)(NB - 2)) : (int)((f - lo) * scale);
         return min(max(b, 0), NB - 2);
       };
       int bin[kVec * 4];
@@ -527,8 +553,12 @@ __device__ __forceinline__ void pick_from_scores_n(const CacheView& c, const Sel
       for (int pass = 0; pass < 4; ++pass) {
         const int shift = 24 - 8 * pass;
 #pragma unroll
-        for (int r = 0; r < kVec * 4; ++r)
-          if (is_live(r) && (key[r] & mask) == prefix) atomicAdd(&sh.hist[pass][(key[r] >> shift) & 255u], 1u);
+        for (int r = 0; r < kVec * 4; ++r) {
+          const bool on = is_live(r) && (key[r] & mask) == prefix;
+          const uint32_t digit = (key[r] >> shift) & 255u;
+          if (SKEWED) hist_add_grouped(sh.hist[pass], digit, on);
+          else if (on) atomicAdd(&sh.hist[pass][digit], 1u);
+        }
         __syncthreads();
         const int b0 = 4 * (kWave - 1 - lane);
         const uint4 h = *reinterpret_cast<const uint4*>(&sh.hist[pass][b0]);
@@ -594,16 +624,16 @@ __device__ __forceinline__ void pick_from_scores_n(const CacheView& c, const Sel
 
 // The pick with the per-thread run sized to the cache (instruction count follows the unrolled run
 // length, so a short cache must not pay for the longest one).
-template <int NT, bool COHERENT = false>
+template <int NT, bool COHERENT = false, bool SKEWED = false>
 __device__ __forceinline__ void pick_from_scores(const CacheView& c, const SelectArgs& a, int unit, int n,
                                                  PickShared<NT>& sh) {
   constexpr int kMaxVec = ROCKETKV_MAX_PAGES / 4 / NT;
   static_assert(kMaxVec >= 1, "thread count does not fit the pick");
   const int per = (c.pages_cap / 4 + NT - 1) / NT;  // same for every thread
-  if (per <= 1) pick_from_scores_n<NT, COHERENT, 1>(c, a, unit, n, sh);
-  else if (per <= 2 || kMaxVec < 4) pick_from_scores_n<NT, COHERENT, (kMaxVec < 2 ? kMaxVec : 2)>(c, a, unit, n, sh);
-  else if (per <= 4 || kMaxVec < 8) pick_from_scores_n<NT, COHERENT, (kMaxVec < 4 ? kMaxVec : 4)>(c, a, unit, n, sh);
-  else pick_from_scores_n<NT, COHERENT, kMaxVec>(c, a, unit, n, sh);
+  if (per <= 1) pick_from_scores_n<NT, COHERENT, 1, SKEWED>(c, a, unit, n, sh);
+  else if (per <= 2 || kMaxVec < 4) pick_from_scores_n<NT, COHERENT, (kMaxVec < 2 ? kMaxVec : 2), SKEWED>(c, a, unit, n, sh);
+  else if (per <= 4 || kMaxVec < 8) pick_from_scores_n<NT, COHERENT, (kMaxVec < 4 ? kMaxVec : 4), SKEWED>(c, a, unit, n, sh);
+  else pick_from_scores_n<NT, COHERENT, kMaxVec, SKEWED>(c, a, unit, n, sh);
 }
 
 // Page scores of the eight-page runs [o_begin, o_begin + n_runs) of one unit, n_runs <= NT, written as

@@ -560,7 +560,7 @@ __global__ __launch_bounds__(kSelT) void snap_select_fast_kernel(CacheView c, Sn
   pa.row_len = k_pref;
   pa.out_pages2 = kept2;
   pa.row_len2 = k_pref;
-  pick_from_scores<kSelT>(row, pa, 0, L, sh);
+  pick_from_scores<kSelT, false, true>(row, pa, 0, L, sh);
   for (int w = tid; w < a.W; w += kSelT) {
     kept[k_pref + w] = L + w;
     if (kept2) kept2[k_pref + w] = L + w;

@@ -161,6 +161,33 @@ def test_random_snapkv(env, oracle, seed):
             assert np.array_equal(Vd[b, g, :cnt], d["V"][b, g, row[:cnt]])
 
 
+@pytest.mark.parametrize("S,N", [(3000, 512), (20000, 4096)])
+def test_snapkv_equal_votes_keep_the_lowest_positions(env, oracle, S, N):
+    """Every key of the prompt is the same vector: all prefix tokens get exactly the same vote, the
+    pooled votes have no finite range to bin, and the tie rule alone decides: the lowest positions
+    stay.  (On the GPU this is the top-k's fallback to radix passes with most of a wavefront in one
+    counter.)"""
+    torch, rk, dev = env
+    W, ks = 32, 63
+    w = small("mistral_snap_128k", batch=1, n_q_heads=8, n_kv_heads=2, context=S, snap_keep=N, window=W,
+              n_heavy=0, seed=5)
+    print("[case] snapkv equal votes", S, N, flush=True)
+    sys.stdout.flush()
+    d = wl.generate(w, with_obs=True)
+    d["K"][:] = d["K"][:, :, :1, :]  # one key per head, repeated
+    src, _ = to_device_cache(rk, torch, d, w.n_q_heads, 16, dev)
+    dst = rk.alloc_cache(1, w.n_q_heads, w.n_kv_heads, 128, 16, (N + 15) // 16, dev, zero=True)
+    kept = torch.full((1, w.n_kv_heads, N), -9, dtype=torch.int32, device=dev)
+    ws = rk.alloc_workspace(rk.OP_SNAPKV, src, W, N)
+    rk.snapkv_compress(wl.from_bits(d["qobs"], dev), src, W, ks, N, dst, kept, ws)
+    torch.cuda.synchronize()
+    ref = oracle.snapkv(d["qobs"], d["K"], d["seq_lens"], ks, N)
+    want = list(range(N - W)) + list(range(S - W, S))
+    for g in range(w.n_kv_heads):
+        assert ref["kept"][0, g].tolist() == want
+        assert kept[0, g].cpu().numpy().tolist() == want
+
+
 @pytest.mark.parametrize("token_major,ps", [(False, 16), (True, 16), (True, 4)])
 def test_absent_pages_are_skipped(env, oracle, token_major, ps):
     """Block-table entries outside the pool mark absent pages: attention leaves their tokens out (here
