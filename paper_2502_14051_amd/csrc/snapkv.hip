@@ -623,24 +623,26 @@ __global__ __launch_bounds__(256) void snap_gather_kernel(CacheView src, CacheVi
     const int64_t dpp = (in_cnt[i] && dt / dps < dst.pages_cap) ? phys_page(dst, b, dt / dps) : -1;
     dof[i] = dpp >= 0 ? dpp * dst.stride_page + dhead + (dt % dps) * kHeadDim + piece * 8 : -1;
   }
-  {
-    uint4 val[NB];
+  // the K rows: loaded now, stored after the V loads have gone out as well (one wait for both)
+  uint4 kval[NB];
 #pragma unroll
-    for (int i = 0; i < NB; ++i) {
-      val[i] = make_uint4(0, 0, 0, 0);
-      if (tok[i] >= 0) val[i] = ld16<false>(src.k_pool + so[i] + (tok[i] % kAttnPage) * kHeadDim + piece * 8);
-    }
-    // a channel-major destination gets whole tiles (zero rows past the end); a token-major one only
-    // the rows that exist, as later pages may belong to something else
+  for (int i = 0; i < NB; ++i) {
+    kval[i] = make_uint4(0, 0, 0, 0);
+    if (tok[i] >= 0) kval[i] = ld16<false>(src.k_pool + so[i] + (tok[i] % kAttnPage) * kHeadDim + piece * 8);
+  }
+  // a channel-major destination gets whole tiles (zero rows past the end); a token-major one only
+  // the rows that exist, as later pages may belong to something else
+  const auto store_k = [&]() {
 #pragma unroll
     for (int i = 0; i < NB; ++i)
-      if (dof[i] >= 0 && (tok[i] >= 0 || !dst.v_token_major)) *reinterpret_cast<uint4*>(dst.k_pool + dof[i]) = val[i];
-  }
+      if (dof[i] >= 0 && (tok[i] >= 0 || !dst.v_token_major)) *reinterpret_cast<uint4*>(dst.k_pool + dof[i]) = kval[i];
+  };
   if (src.v_token_major && dst.v_token_major) {
     uint4 val[NB];
 #pragma unroll
     for (int i = 0; i < NB; ++i)
       if (tok[i] >= 0) val[i] = ld16<false>(src.v_pool + so[i] + (tok[i] % kAttnPage) * kHeadDim + piece * 8);
+    store_k();
 #pragma unroll
     for (int i = 0; i < NB; ++i)
       if (tok[i] >= 0 && dof[i] >= 0) *reinterpret_cast<uint4*>(dst.v_pool + dof[i]) = val[i];
@@ -654,6 +656,7 @@ __global__ __launch_bounds__(256) void snap_gather_kernel(CacheView src, CacheVi
       val[i] = make_uint4(0, 0, 0, 0);
       if (tok[i] >= 0) val[i] = ld16<false>(src.v_pool + so[i] + (tok[i] % kAttnPage) * kHeadDim + piece * 8);
     }
+    store_k();
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
       const uint32_t w[4] = {val[i].x, val[i].y, val[i].z, val[i].w};
@@ -664,21 +667,24 @@ __global__ __launch_bounds__(256) void snap_gather_kernel(CacheView src, CacheVi
       }
     }
   } else {
-    // thread -> (slot = tid%16, channels tid/16 + 16 j): all of a block's loads go out before the LDS stores
+    // thread -> (slot = tid%16, channels tid/16 + 16 j): the loads of all blocks go out before the first LDS store
     const int slot = tid % kAttnPage, ch0 = tid / kAttnPage;
+    bf16_t val[NB][8];
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
       const int tk = s_tok[i * kAttnPage + slot];
       const int64_t sv = s_src[i * kAttnPage + slot];
-      bf16_t val[8];
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
-        val[j] = 0;
-        if (tk >= 0) val[j] = src.v_pool[sv + (ch0 + 16 * j) * kAttnPage + tk % kAttnPage];
+        val[i][j] = 0;
+        if (tk >= 0) val[i][j] = src.v_pool[sv + (ch0 + 16 * j) * kAttnPage + tk % kAttnPage];
       }
-#pragma unroll
-      for (int j = 0; j < 8; ++j) s_v[i][(ch0 + 16 * j) * kAttnPage + slot] = val[j];
     }
+    store_k();
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) s_v[i][(ch0 + 16 * j) * kAttnPage + slot] = val[i][j];
   }
   __syncthreads();
 #pragma unroll
