@@ -458,6 +458,58 @@ def main():
             del bl
             torch.cuda.empty_cache()
 
+    # ------------------------------------------------------------------ one long prompt, batch 1
+    # BASELINE configs[3]: a single 131072-token prompt (32 query / 8 KV heads), SnapKV to 8192 tokens,
+    # then decode steps with append at token budget 2048, against full-KV dense attention over the
+    # 131072 tokens.  Eight layers (4.3 GB of uncompressed cache), eight units per launch.
+    long_pt = None
+    if not args.no_decomposed and not args.batch and not args.layers:
+        wm = wl.CONFIGS["mistral_snap_128k"]
+        nlm = 8
+        ll, snapm_ws, snapm_ms = [], None, []
+        for layer in range(nlm):
+            d = wl.generate_device(wm, layer, dev, with_obs=True)
+            srcm = rk.pack_cache(d["K"], d["V"], d["seq_lens"].cpu().numpy(), wm.n_q_heads, 16)
+            dstm = rk.alloc_cache(1, wm.n_q_heads, wm.n_kv_heads, D, 16, (wm.snap_keep + 512) // 16, dev, zero=True)
+            if snapm_ws is None:
+                snapm_ws = rk.alloc_workspace(rk.OP_SNAPKV, srcm, wm.window, wm.snap_keep)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            with torch.cuda.stream(stream):
+                e0.record(stream)
+                rk.snapkv_compress(d["qobs"], srcm, wm.window, wm.pool_kernel, wm.snap_keep, dstm, None, snapm_ws, stream)
+                e1.record(stream)
+                stream.synchronize()
+            snapm_ms.append(e0.elapsed_time(e1))
+            kmm, knm = rk.alloc_summaries(dstm)
+            rk.build_page_summaries(dstm, kmm, knm)
+            torch.cuda.synchronize()
+            ll.append(dict(src=srcm, cache=dstm, kmax=kmm, kmin=knm, q=d["q"].contiguous(),
+                           out=torch.empty((1, wm.n_q_heads, D), dtype=torch.bfloat16, device=dev),
+                           ws=rk.alloc_workspace(rk.OP_HSA_DECODE, dstm, wm.token_budget),
+                           wsd=rk.alloc_workspace(rk.OP_DENSE_DECODE, srcm)))
+            del d
+        nkm = layers[0]["new_k"][:1].contiguous()
+        nvm = layers[0]["new_v"][:1].contiguous()
+
+        def long_all():
+            for L in ll:
+                rk.hsa_decode_append(L["cache"], L["q"], nkm, nvm, L["kmax"], L["kmin"], wm.channel_budget,
+                                     wm.token_budget, 0, L["out"], None, None, None, L["ws"], stream)
+
+        def long_dense():
+            for L in ll:
+                rk.dense_decode(L["src"], L["q"], L["out"], None, L["wsd"], stream)
+
+        long_us = timed_graph(long_all, 6) * 1e3 / nlm
+        long_dense_us = timed_graph(long_dense, 6) * 1e3 / nlm
+        long_pt = {"workload": f"mistral_snap_128k: batch 1, 32q/8kv heads, prompt {wm.context} -> SnapKV {wm.snap_keep}, "
+                               f"budget {wm.token_budget}, page 16, k1 {wm.channel_budget}, {nlm} layers",
+                   "us_per_layer_step": round(long_us, 2), "dense_full_kv_us": round(long_dense_us, 2),
+                   "speedup_vs_dense_full_kv": round(long_dense_us / long_us, 2),
+                   "snapkv_ms_per_layer": round(float(np.median(snapm_ms)), 3)}
+        del ll, snapm_ws
+        torch.cuda.empty_cache()
+
     # ------------------------------------------------------------------ bytes
     kp = min(P_now, T // ps)
     attend_bytes = units * (kp * ps * D * 2 * 2 + 2 * G * D * 2)
@@ -539,6 +591,7 @@ def main():
                      "measured_read_GBs": None if read_gbs is None else round(read_gbs, 1),
                      "frac_of_measured_read": None if read_gbs is None else round(hsa_gbs / read_gbs, 4)},
         "decomposed_operating_point": dec_pt,
+        "long_prompt_batch1": long_pt,
         "multi_turn_variant": mt_pt,
         "single_layer_batch1": single,
         "other_shapes_and_batches": big,

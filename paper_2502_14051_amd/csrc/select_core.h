@@ -351,10 +351,10 @@ __device__ __forceinline__ float f32_from_order_key(uint32_t k) {
   return __uint_as_float((k & 0x80000000u) ? (k ^ 0x80000000u) : ~k);
 }
 
-// One count into `hist[bin]` for every lane with `on`, where many lanes of a wavefront may share a
-// bin: up to two rounds in which the first pending lane's bin is counted once for all lanes that
-// hold it, then plain atomics for whatever is left.
-__device__ __forceinline__ void hist_add_grouped(uint32_t* hist, uint32_t bin, bool on) {
+// `weight` counts into `hist[bin]` for every lane with `on`, where many lanes of a wavefront may
+// share a bin: up to two rounds in which the first pending lane's bin is counted once for all lanes
+// that hold it, then plain atomics for whatever is left.
+__device__ __forceinline__ void hist_add_grouped(uint32_t* hist, uint32_t bin, bool on, uint32_t weight = 1u) {
   const int lane = threadIdx.x % kWave;
   unsigned long long todo = __ballot(on);
 #pragma unroll
@@ -363,11 +363,11 @@ __device__ __forceinline__ void hist_add_grouped(uint32_t* hist, uint32_t bin, b
     const int leader = __ffsll((long long)todo) - 1;
     const uint32_t b = (uint32_t)__builtin_amdgcn_readlane((int)bin, leader);
     const unsigned long long same = __ballot(on && bin == b);
-    if (lane == leader) atomicAdd(&hist[b], (uint32_t)__popcll(same));
+    if (lane == leader) atomicAdd(&hist[b], weight * (uint32_t)__popcll(same));
     on = on && bin != b;
     todo &= ~same;
   }
-  if (on) atomicAdd(&hist[bin], 1u);
+  if (on) atomicAdd(&hist[bin], weight);
 }
 
 // Step 2's top-k (Algorithm 1, i2) on page scores that an earlier launch left in a.in_scores: the

@@ -340,24 +340,50 @@ void snap_score_kernel(CacheView c, SnapArgs a) {
   }
 }
 
-// merge the per-chunk statistics of one unit: one thread per softmax row
-__global__ __launch_bounds__(256) void snap_stats_kernel(CacheView c, SnapArgs a) {
+// merge the per-chunk statistics of one unit.  A long prompt has hundreds of chunks: the chunks of a
+// softmax row are dealt to 1024 / ncp threads (ncp = the row count rounded up to a power of two),
+// each merges its share with eight loads in flight, and one thread per row merges the partial
+// results in a fixed order.
+constexpr int kStatsT = 1024;
+__global__ __launch_bounds__(kStatsT) void snap_stats_kernel(CacheView c, SnapArgs a) {
+  __shared__ float pm[kStatsT], pz[kStatsT];
+  const int tid = threadIdx.x;
   const int unit = blockIdx.x;
   const int b = unit / c.n_kv_heads;
   const int S = c.seq_lens[b];
   if (S <= a.keep || S > c.pages_cap * kAttnPage) return;
   const int chunks = ((S + kAttnPage - 1) / kAttnPage + a.chunk_pages - 1) / a.chunk_pages;
-  for (int col = threadIdx.x; col < a.NC; col += 256) {
-    float mm = kNegBigS, zz = 0.f;
-    for (int ch = 0; ch < chunks; ++ch) {
-      const float* o = a.stats_part + (((int64_t)unit * a.n_chunks + ch) * a.NC + col) * 2;
-      const float mo = o[0], zo = o[1];
-      const float mn = fmaxf(mm, mo);
-      zz = zz * exp2_fast(mm - mn) + zo * exp2_fast(mo - mn);
-      mm = mn;
+  int ncp = 64;
+  while (ncp < a.NC) ncp <<= 1;  // NC <= 256 (host)
+  const int col = tid % ncp, part = tid / ncp, parts = kStatsT / ncp;
+  const auto merge = [](float& mm, float& zz, float mo, float zo) {
+    const float mn = fmaxf(mm, mo);
+    zz = zz * exp2_fast(mm - mn) + zo * exp2_fast(mo - mn);
+    mm = mn;
+  };
+  float mm = kNegBigS, zz = 0.f;
+  if (col < a.NC) {
+    const float2* row = reinterpret_cast<const float2*>(a.stats_part) + (int64_t)unit * a.n_chunks * a.NC + col;
+    for (int ch0 = part; ch0 < chunks; ch0 += parts * 8) {
+      float2 o[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int ch = ch0 + u * parts;
+        o[u] = ch < chunks ? row[(int64_t)ch * a.NC] : make_float2(kNegBigS, 0.f);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) merge(mm, zz, o[u].x, o[u].y);
     }
-    a.stats[((int64_t)unit * a.NC + col) * 2] = mm;
-    a.stats[((int64_t)unit * a.NC + col) * 2 + 1] = zz > 0.f ? 1.f / zz : 0.f;
+  }
+  pm[tid] = mm;
+  pz[tid] = zz;
+  __syncthreads();
+  if (tid < a.NC) {
+    mm = kNegBigS;
+    zz = 0.f;
+    for (int p = 0; p < parts; ++p) merge(mm, zz, pm[p * ncp + tid], pz[p * ncp + tid]);
+    a.stats[((int64_t)unit * a.NC + tid) * 2] = mm;
+    a.stats[((int64_t)unit * a.NC + tid) * 2 + 1] = zz > 0.f ? 1.f / zz : 0.f;
   }
 }
 
@@ -406,11 +432,17 @@ __device__ __forceinline__ uint32_t order_key(float f) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-// exact top-(keep-W) of pooled[0, L) + the window, ascending; one 1024-thread workgroup per unit
+// exact top-(keep-W) of pooled[0, L) + the window, ascending; one 1024-thread workgroup per unit.
+// Six passes over the row (four radix digits, a count, the ordered emission), all of them as
+// coalesced 16-byte loads with eight in flight per thread; the top digit (sign and exponent, which
+// votes share) is counted once per group of lanes that hold the same one.  For the emission a
+// wavefront owns a contiguous stretch of the row and walks it in 256-position steps, with a prefix
+// sum over its lanes per step.
 constexpr int kSelT = 1024;
+constexpr int kSelBatch = 8;
 __global__ __launch_bounds__(kSelT) void snap_select_kernel(CacheView c, SnapArgs a) {
   __shared__ uint32_t hist[256];
-  __shared__ uint32_t wsum[kSelT / kWave];
+  __shared__ uint32_t wsum[kSelT / kWave], wsum_eq[kSelT / kWave];
   __shared__ uint32_t sh_bucket, sh_k;
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
   const int unit = blockIdx.x;
@@ -432,16 +464,45 @@ __global__ __launch_bounds__(kSelT) void snap_select_kernel(CacheView c, SnapArg
   }
   const int L = S - a.W;
   const int k_pref = a.keep - a.W;
-  const float* pv = a.pooled + (int64_t)unit * a.s_cap;
+  // the row holds s_cap >= L + W floats and starts 16-byte aligned: the last group of four is in bounds
+  const float4* pv4 = reinterpret_cast<const float4*>(a.pooled + (int64_t)unit * a.s_cap);
+  const int n4 = (L + 3) / 4;
 
   uint32_t prefix = 0, mask = 0, k = (uint32_t)k_pref;
   for (int pass = 0; pass < 4; ++pass) {
     const int shift = 24 - 8 * pass;
     if (tid < 256) hist[tid] = 0;
     __syncthreads();
-    for (int j = tid; j < L; j += kSelT) {
-      const uint32_t key = order_key(pv[j]);
-      if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+    for (int base = 0; base < n4; base += kSelT * kSelBatch) {  // the same trip count for every thread
+      float4 v[kSelBatch];
+#pragma unroll
+      for (int u = 0; u < kSelBatch; ++u) {
+        const int q = base + u * kSelT + tid;
+        v[u] = q < n4 ? pv4[q] : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+#pragma unroll
+      for (int u = 0; u < kSelBatch; ++u) {
+        const int q = base + u * kSelT + tid;
+        const float x[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+        bool on[4];
+        uint32_t digit[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const uint32_t key = order_key(x[e]);
+          on[e] = q < n4 && 4 * q + e < L && (key & mask) == prefix;
+          digit[e] = (key >> shift) & 255u;
+        }
+        // the top digit: four neighbours mostly share it (pooling repeats a maximum 2r+1 times), and
+        // so do most lanes; such a group of four is counted in one step for all lanes that agree
+        const bool four = pass == 0 && on[0] && on[1] && on[2] && on[3] && digit[0] == digit[1] &&
+                          digit[1] == digit[2] && digit[2] == digit[3];
+        if (pass == 0) hist_add_grouped(hist, digit[0], four, 4u);
+        if (!four) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (on[e]) atomicAdd(&hist[digit[e]], 1u);
+        }
+      }
     }
     __syncthreads();
     uint32_t v = 0, inc = 0;
@@ -472,60 +533,89 @@ __global__ __launch_bounds__(kSelT) void snap_select_kernel(CacheView c, SnapArg
   }
   const uint32_t tau = prefix, need_eq = k;
 
-  // ordered emission: thread t owns a contiguous range of positions
-  const int ipt = (L + kSelT - 1) / kSelT;
-  const int lo = min(L, tid * ipt), hi = min(L, lo + ipt);
+  // ordered emission: wavefront w owns groups [w * gpw, (w + 1) * gpw), gpw a multiple of 64
+  const int gpw = ((n4 + kSelT / kWave - 1) / (kSelT / kWave) + kWave - 1) / kWave * kWave;
+  const int wbeg = wave * gpw, wend = min(wbeg + gpw, n4);
   uint32_t cgt = 0, ceq = 0;
-  for (int j = lo; j < hi; ++j) {
-    const uint32_t key = order_key(pv[j]);
-    cgt += key > tau;
-    ceq += key == tau;
-  }
-  // two block scans (counts can exceed 16 bits here)
-  uint32_t before_gt, before_eq;
-  {
-    uint32_t inc = cgt;
+  for (int base = wbeg; base < wend; base += kWave * kSelBatch) {
+    float4 v[kSelBatch];
 #pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-      const uint32_t y = __shfl_up(inc, off);
-      if (lane >= off) inc += y;
+    for (int u = 0; u < kSelBatch; ++u) {
+      const int q = base + u * kWave + lane;
+      v[u] = q < wend ? pv4[q] : make_float4(0.f, 0.f, 0.f, 0.f);
     }
-    if (lane == kWave - 1) wsum[wave] = inc;
-    __syncthreads();
-    uint32_t base = 0;
-    for (int w = 0; w < wave; ++w) base += wsum[w];
-    before_gt = base + inc - cgt;
-    __syncthreads();
-    inc = ceq;
 #pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-      const uint32_t y = __shfl_up(inc, off);
-      if (lane >= off) inc += y;
-    }
-    if (lane == kWave - 1) wsum[wave] = inc;
-    __syncthreads();
-    base = 0;
-    for (int w = 0; w < wave; ++w) base += wsum[w];
-    before_eq = base + inc - ceq;
-  }
-  uint32_t gt = before_gt, eq = before_eq;
-  for (int j = lo; j < hi; ++j) {
-    const uint32_t key = order_key(pv[j]);
-    bool take = key > tau;
-    uint32_t eq_taken = min(eq, need_eq);
-    if (key == tau) {
-      take = eq < need_eq;
-      eq_taken = eq;
-      ++eq;
-    }
-    if (take) {
-      const uint32_t pos = gt + eq_taken;
-      if ((int)pos < k_pref) {
-        kept[pos] = j;
-        if (kept2) kept2[pos] = j;
+    for (int u = 0; u < kSelBatch; ++u) {
+      const int q = base + u * kWave + lane;
+      const float x[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const uint32_t key = order_key(x[e]);
+        const bool in = q < wend && 4 * q + e < L;
+        cgt += in && key > tau;
+        ceq += in && key == tau;
       }
     }
-    if (key > tau) ++gt;
+  }
+  // keys above / equal to the threshold in the wavefronts before this one
+  {
+    const uint32_t tg = wave_incl_scan(cgt), te = wave_incl_scan(ceq);
+    if (lane == kWave - 1) {
+      wsum[wave] = tg;
+      wsum_eq[wave] = te;
+    }
+  }
+  __syncthreads();
+  uint32_t gt = 0, eq = 0;  // the same for every lane of the wavefront
+  for (int w = 0; w < wave; ++w) {
+    gt += wsum[w];
+    eq += wsum_eq[w];
+  }
+  for (int base = wbeg; base < wend; base += kWave * kSelBatch) {
+    float4 v[kSelBatch];
+#pragma unroll
+    for (int u = 0; u < kSelBatch; ++u) {
+      const int q = base + u * kWave + lane;
+      v[u] = q < wend ? pv4[q] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int u = 0; u < kSelBatch; ++u) {
+      const int q = base + u * kWave + lane;
+      const float x[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+      uint32_t key[4];
+      uint32_t ng = 0, ne = 0;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        key[e] = order_key(x[e]);
+        const bool in = q < wend && 4 * q + e < L;
+        if (!in) key[e] = 0;  // below every threshold that is reached here (kp < L)
+        ng += in && key[e] > tau;
+        ne += in && key[e] == tau;
+      }
+      const uint32_t sg = wave_incl_scan(ng), se = wave_incl_scan(ne);
+      uint32_t mgt = gt + sg - ng, meq = eq + se - ne;  // before this lane's four positions
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const bool in = q < wend && 4 * q + e < L;
+        bool take = in && key[e] > tau;
+        uint32_t eq_taken = min(meq, need_eq);
+        if (in && key[e] == tau) {
+          take = meq < need_eq;
+          eq_taken = meq;
+          ++meq;
+        }
+        if (take) {
+          const uint32_t pos = mgt + eq_taken;
+          if ((int)pos < k_pref) {
+            kept[pos] = 4 * q + e;
+            if (kept2) kept2[pos] = 4 * q + e;
+          }
+        }
+        if (in && key[e] > tau) ++mgt;
+      }
+      gt += (uint32_t)__builtin_amdgcn_readlane((int)sg, kWave - 1);
+      eq += (uint32_t)__builtin_amdgcn_readlane((int)se, kWave - 1);
+    }
   }
   for (int w = tid; w < a.W; w += kSelT) {
     kept[k_pref + w] = L + w;
@@ -767,7 +857,7 @@ hipError_t launch_snapkv(const bf16_t* q_obs, const CacheView& src, int window, 
     hipLaunchKernelGGL((snap_score_kernel<false, 2>), sgrid, dim3(256), kSnapRingBytes, st, src, a);
   else
     hipLaunchKernelGGL((snap_score_kernel<false, 1>), sgrid, dim3(256), kSnapRingBytes, st, src, a);
-  hipLaunchKernelGGL(snap_stats_kernel, dim3(units), dim3(256), 0, st, src, a);
+  hipLaunchKernelGGL(snap_stats_kernel, dim3(units), dim3(kStatsT), 0, st, src, a);
 
   if (two_groups)
     hipLaunchKernelGGL((snap_score_kernel<true, 2>), sgrid, dim3(256), kSnapRingBytes + vote_bytes, st, src, a);

@@ -161,12 +161,12 @@ def test_random_snapkv(env, oracle, seed):
             assert np.array_equal(Vd[b, g, :cnt], d["V"][b, g, row[:cnt]])
 
 
-@pytest.mark.parametrize("S,N", [(3000, 512), (20000, 4096)])
+@pytest.mark.parametrize("S,N", [(3000, 512), (20000, 4096), (40000, 4096)])
 def test_snapkv_equal_votes_keep_the_lowest_positions(env, oracle, S, N):
     """Every key of the prompt is the same vector: all prefix tokens get exactly the same vote, the
     pooled votes have no finite range to bin, and the tie rule alone decides: the lowest positions
     stay.  (On the GPU this is the top-k's fallback to radix passes with most of a wavefront in one
-    counter.)"""
+    counter; the 40000-token prompt goes through the select kernel for long prompts.)"""
     torch, rk, dev = env
     W, ks = 32, 63
     w = small("mistral_snap_128k", batch=1, n_q_heads=8, n_kv_heads=2, context=S, snap_keep=N, window=W,
