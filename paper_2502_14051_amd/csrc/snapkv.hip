@@ -803,10 +803,11 @@ SnapPlan plan_snapkv(const CacheView& src, int window, int keep) {
   const int NC = src.group * window;
   // Pages per workgroup in the score passes.  Every wavefront loads the whole observation-window
   // query block before its first page, so long chunks amortise that; short ones keep the chip full
-  // when there are few (sequence, KV head) units.  Aim for about 2048 workgroups.
+  // when there are few (sequence, KV head) units.  Aim for 512 workgroups or more (two per compute
+  // unit): eight units of a 131072-token prompt ran a third slower in chunks of 32 pages than of 128.
   static_assert(kSnapMaxChunkPages / 2 <= kSnapMaxIters, "a wavefront's share of the longest chunk must fit its page-offset lanes");
   int chunk_pages = 32;
-  while (chunk_pages < kSnapMaxChunkPages && units * ((src.pages_cap + chunk_pages - 1) / chunk_pages) > 2048) chunk_pages *= 2;
+  while (chunk_pages < kSnapMaxChunkPages && units * ((src.pages_cap + chunk_pages - 1) / chunk_pages) > 512) chunk_pages *= 2;
   p.chunk_pages = chunk_pages;
   p.n_chunks = (src.pages_cap + chunk_pages - 1) / chunk_pages;
   const size_t s_cap = (size_t)src.pages_cap * kAttnPage;
