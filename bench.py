@@ -33,7 +33,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0  # MI355X published peak
 # HBM bytes per launch of the fused kernel on this workload from rocprofv3 FETCH_SIZE / WRITE_SIZE
 # (profiles/bench_llama8b_step_b16_pmc.txt): (FETCH_SIZE x 2.0 + WRITE_SIZE) KiB.
-TRAFFIC_BYTES_PER_LAUNCH = 75153306
+TRAFFIC_BYTES_PER_LAUNCH = 75157197
 
 
 def parse():
