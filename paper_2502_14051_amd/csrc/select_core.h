@@ -352,7 +352,7 @@ __device__ __forceinline__ float f32_from_order_key(uint32_t k) {
 }
 
 // `weight` counts into `hist[bin]` for every lane with `on`, where many lanes of a wavefront may
-// share a bin: up to two rounds in which the first pending lane's bin is counted once for all lanes
+// share a bin: up to two steps in which the first pending lane's bin is counted once for all lanes
 // that hold it, then plain atomics for whatever is left.
 __device__ __forceinline__ void hist_add_grouped(uint32_t* hist, uint32_t bin, bool on, uint32_t weight = 1u) {
   const int lane = threadIdx.x % kWave;
