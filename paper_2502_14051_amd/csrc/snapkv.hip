@@ -78,7 +78,7 @@ __device__ __forceinline__ int64_t readlane64(int64_t v, int l) {
 constexpr int kSnapMaxIters = 2 * kWave;  // pages one wavefront walks in a chunk, at most
 constexpr int kSnapRing = 3;              // key tiles a wavefront keeps in flight (4 KiB of LDS each)
 constexpr size_t kSnapRingBytes = (size_t)4 * kSnapRing * 4 * kWave * 16;  // four wavefronts
-constexpr int kSnapMaxChunkPages = 128;  // pages per workgroup; pass 2 stages their votes in LDS (8 KiB)
+constexpr int kSnapMaxChunkPages = 128;  // pages per workgroup; pass 2 stages their votes in LDS (8 KiB per column group)
 
 // QD: groups of four column blocks every wavefront works through (2 when some wavefront owns more
 // than four blocks with real softmax rows; blocks without any hold zero queries and are discarded).
@@ -86,7 +86,6 @@ template <bool PASS2, int QD>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2)))
 void snap_score_kernel(CacheView c, SnapArgs a) {
   __shared__ float sM[4][kSnapColBlocks * 16], sZ[4][kSnapColBlocks * 16];
-  __shared__ float sV[4][16];
   const int tid = threadIdx.x, lane = tid % kWave;
   const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);  // scalar: page indices stay in SGPRs
   const int hn = lane % 16, kg = lane / 16;
@@ -136,7 +135,7 @@ void snap_score_kernel(CacheView c, SnapArgs a) {
   typedef uint32_t ring_u32x4 __attribute__((ext_vector_type(4)));
   extern __shared__ __align__(16) unsigned char snap_dyn[];
   ring_u32x4* ring = reinterpret_cast<ring_u32x4*>(snap_dyn) + wave * (kSnapRing * 4 * kWave);
-  float* s_votes = reinterpret_cast<float*>(snap_dyn + kSnapRingBytes);  // pass 2: [chunk_pages][16]
+  float* s_votes = reinterpret_cast<float*>(snap_dyn + kSnapRingBytes);  // pass 2: [column group][chunk_pages][16]
   const auto tile_off = [&](int it) -> int64_t {  // `it` is wave-uniform; branch-free
     const int l = it & (kWave - 1);
     const int64_t lo = readlane64(off_lo, l), hi = readlane64(off_hi, l);
@@ -206,25 +205,15 @@ void snap_score_kernel(CacheView c, SnapArgs a) {
       }
     }
   };
-  // votes of one page (already summed over the 16 columns a token group's lanes hold): add the column
-  // groups, stage the result
+  // votes of one page (already summed over the 16 columns a token group's lanes hold): staged in LDS,
+  // one copy per column group, and written out once per chunk (a global store per page would sit among
+  // the tile loads the wait above counts, and make it wait for more of them than it needs; adding the
+  // column groups per page would cost two workgroup barriers per page)
+  const int chunk_tokens = a.chunk_pages * kAttnPage;
   const auto emit_votes = [&](float* v, bool live, int tok0) {
-    if (a.CG == 2) {
-      if (cgi == 1 && hn == 0) {
-#pragma unroll
-        for (int r = 0; r < 4; ++r) sV[pw][kg * 4 + r] = v[r];
-      }
-      __syncthreads();
-      if (cgi == 0) {
-#pragma unroll
-        for (int r = 0; r < 4; ++r) v[r] += sV[pw][kg * 4 + r];
-      }
-      __syncthreads();
-    }
-    // staged in LDS and written out once per chunk: a global store per page would sit among the
-    // tile loads the wait above counts, and make it wait for more of them than it needs
-    if (live && cgi == 0 && hn == 0)
-      *reinterpret_cast<float4*>(s_votes + (tok0 - p_begin * kAttnPage)) = make_float4(v[0], v[1], v[2], v[3]);
+    if (live && hn == 0)
+      *reinterpret_cast<float4*>(s_votes + cgi * chunk_tokens + (tok0 - p_begin * kAttnPage)) =
+          make_float4(v[0], v[1], v[2], v[3]);
   };
   int slot = 0;
   // One page: its tile out of the ring, then per group of four column blocks the products and the
@@ -297,14 +286,15 @@ void snap_score_kernel(CacheView c, SnapArgs a) {
     }
   }
   int it = 0;
-  for (; it < n_fast; ++it) page(std::false_type{}, it);  // n_it is the same for wavefronts that share a barrier
+  for (; it < n_fast; ++it) page(std::false_type{}, it);
   for (; it < n_it; ++it) page(std::true_type{}, it);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the last refills (unused) land before LDS is reused
   if (PASS2) {
     __syncthreads();
     const int tok_begin = p_begin * kAttnPage;
     const int n_tok = min(p_end * kAttnPage, L) - tok_begin;
-    for (int i = tid; i < n_tok; i += 256) a.votes[(int64_t)unit * a.s_cap + tok_begin + i] = s_votes[i];
+    for (int i = tid; i < n_tok; i += 256)
+      a.votes[(int64_t)unit * a.s_cap + tok_begin + i] = a.CG == 2 ? s_votes[i] + s_votes[chunk_tokens + i] : s_votes[i];
     return;
   }
   // ---- pass 1: merge statistics over token groups, waves, and hand the chunk's partial out -------
@@ -852,7 +842,7 @@ hipError_t launch_snapkv(const bf16_t* q_obs, const CacheView& src, int window, 
   a.n_out = n_out;
 
   const dim3 sgrid(plan.n_chunks, units);
-  const size_t vote_bytes = (size_t)a.chunk_pages * kAttnPage * sizeof(float);
+  const size_t vote_bytes = (size_t)a.CG * a.chunk_pages * kAttnPage * sizeof(float);
   const bool two_groups = a.NC > 4 * 16;  // some wavefront owns more than four blocks of real rows
   if (two_groups)
     hipLaunchKernelGGL((snap_score_kernel<false, 2>), sgrid, dim3(256), kSnapRingBytes, st, src, a);
