@@ -411,6 +411,9 @@ SNAP_CASES = [
                                n_q_heads=4, n_kv_heads=2), None, 63, False),  # multi-turn window size
     # a prompt beyond 32768 tokens: the radix-select kernel instead of the register-resident top-k
     ("mistral_snap_128k", dict(context=40000, snap_keep=2048, n_heavy=16, n_q_heads=4, n_kv_heads=2), None, 63, False),
+    # the same kernel on ragged lengths (a row that ends inside a 16-byte group, a prompt below the keep budget)
+    ("mistral_snap_128k", dict(batch=3, context=50003, snap_keep=1000, n_heavy=12, n_q_heads=2, n_kv_heads=1),
+     (50003, 33001, 700), 31, True),
 ]
 
 
