@@ -182,7 +182,8 @@ hipError_t launch_append(const CacheView& c, const bf16_t* k_new, const bf16_t* 
                          bf16_t* kmin, hipStream_t st);
 
 struct SnapPlan {
-  size_t stats_off, votes_off, pooled_off, kept_off, total_bytes;
+  size_t stats_off, votes_off, pooled_off, kept_off, sel_off, total_bytes;
+  int sel_split;  // workgroups per unit in the select of a long prompt (0: one, in a single launch)
   int n_chunks;  // key-axis chunks per (sequence, head group) in the two score passes
   int chunk_pages;
 };

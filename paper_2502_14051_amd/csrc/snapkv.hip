@@ -42,6 +42,8 @@ struct SnapArgs {
   int32_t* kept_user; // optional copy for the caller, rows of kept_stride entries
   int kept_stride;
   int32_t* n_out;     // [batch]: number of tokens kept per sequence
+  uint32_t* sel_hist; // split select: [units][4][256] digit counts, then [units][sel_split][2] slice counts
+  int sel_split;
 };
 
 __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -614,6 +616,262 @@ __global__ __launch_bounds__(kSelT) void snap_select_kernel(CacheView c, SnapArg
   if (g == 0 && tid == 0) a.n_out[b] = a.keep;
 }
 
+// ---- the same selection with several workgroups per unit ------------------------------------------
+// One long prompt is eight units: one workgroup each leaves the chip idle for the six passes above.
+// Here a unit's row is cut into `sel_split` slices, and every pass is a launch of its own: four
+// launches add their slice's digit counts to the unit's histograms in memory (each workgroup first
+// re-derives the digits fixed so far from the earlier histograms, which is 256 counters per digit),
+// one counts the keys above / equal to the threshold per slice, and the last emits in order from the
+// slice counts before it.  Same result as the single-launch kernel.
+constexpr int kSplitT = 256;
+
+// (prefix, remaining k) after the first `passes` radix digits, from the unit's histograms; every
+// wavefront computes it for itself
+__device__ __forceinline__ void split_threshold(const uint32_t* ghist, int passes, uint32_t k_pref,
+                                                uint32_t& prefix, uint32_t& mask, uint32_t& k) {
+  const int lane = threadIdx.x % kWave;
+  prefix = 0;
+  mask = 0;
+  k = k_pref;
+  for (int pass = 0; pass < passes; ++pass) {
+    const int shift = 24 - 8 * pass;
+    const int b0 = 4 * (kWave - 1 - lane);  // lane 0 owns the four highest bins
+    const uint4 h = *reinterpret_cast<const uint4*>(ghist + pass * 256 + b0);
+    const uint32_t s3 = h.w, s2 = h.z + s3, s1 = h.y + s2, s0 = h.x + s1;
+    const uint32_t above = wave_incl_scan(s0) - s0;
+    const uint32_t in[4] = {above + s0, above + s1, above + s2, above + s3};
+    const uint32_t hc[4] = {h.x, h.y, h.z, h.w};
+    int found = -1;
+    uint32_t newk = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint32_t exc = in[j] - hc[j];
+      if (exc < k && k <= in[j]) {
+        found = b0 + j;
+        newk = k - exc;
+      }
+    }
+    const unsigned long long who = __ballot(found >= 0);
+    const int src = __ffsll((long long)who) - 1;
+    const uint32_t bucket = (uint32_t)__builtin_amdgcn_readlane(found, src);
+    k = (uint32_t)__builtin_amdgcn_readlane((int)newk, src);
+    prefix |= bucket << shift;
+    mask |= 0xffu << shift;
+  }
+}
+
+// the slice of float4 groups of workgroup `wg`: a multiple of 64 groups, so wavefront steps stay whole
+__device__ __forceinline__ void split_slice(int n4, int split, int wg, int& gbeg, int& gend) {
+  const int per = ((n4 + split - 1) / split + kWave - 1) / kWave * kWave;
+  gbeg = min(wg * per, n4);
+  gend = min(gbeg + per, n4);
+}
+
+__global__ __launch_bounds__(kSplitT) void snap_split_hist_kernel(CacheView c, SnapArgs a, int pass) {
+  __shared__ uint32_t hist[256];
+  const int tid = threadIdx.x;
+  const int unit = blockIdx.y, wg = blockIdx.x;
+  const int b = unit / c.n_kv_heads;
+  const int S = c.seq_lens[b];
+  if (S <= a.keep || S > c.pages_cap * kAttnPage) return;
+  const int L = S - a.W;
+  const float4* pv4 = reinterpret_cast<const float4*>(a.pooled + (int64_t)unit * a.s_cap);
+  const int n4 = (L + 3) / 4;
+  int gbeg, gend;
+  split_slice(n4, a.sel_split, wg, gbeg, gend);
+  uint32_t* ghist = a.sel_hist + (int64_t)unit * 4 * 256;
+  uint32_t prefix, mask, k;
+  split_threshold(ghist, pass, (uint32_t)(a.keep - a.W), prefix, mask, k);
+  const int shift = 24 - 8 * pass;
+  hist[tid] = 0;
+  __syncthreads();
+  for (int base = gbeg; base < gend; base += kSplitT * 4) {  // the same trip count for every thread
+    float4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int q = base + u * kSplitT + tid;
+      v[u] = q < gend ? pv4[q] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int q = base + u * kSplitT + tid;
+      const float x[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+      bool on[4];
+      uint32_t digit[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const uint32_t key = order_key(x[e]);
+        on[e] = q < gend && 4 * q + e < L && (key & mask) == prefix;
+        digit[e] = (key >> shift) & 255u;
+      }
+      const bool four = pass == 0 && on[0] && on[1] && on[2] && on[3] && digit[0] == digit[1] &&
+                        digit[1] == digit[2] && digit[2] == digit[3];
+      if (pass == 0) hist_add_grouped(hist, digit[0], four, 4u);
+      if (!four) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (on[e]) atomicAdd(&hist[digit[e]], 1u);
+      }
+    }
+  }
+  __syncthreads();
+  if (hist[tid] != 0) atomicAdd(&ghist[pass * 256 + tid], hist[tid]);
+}
+
+// EMIT = false: the slice's counts of keys above / equal to the threshold, to sel_hist's second part.
+// EMIT = true: the ordered emission of the slice (and, by slice 0, the window and the short prompts).
+template <bool EMIT>
+__global__ __launch_bounds__(kSplitT) void snap_split_emit_kernel(CacheView c, SnapArgs a) {
+  __shared__ uint32_t wsum[kSplitT / kWave], wsum_eq[kSplitT / kWave];
+  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+  const int unit = blockIdx.y, wg = blockIdx.x;
+  const int units = gridDim.y;
+  const int b = unit / c.n_kv_heads, g = unit % c.n_kv_heads;
+  const int S = c.seq_lens[b];
+  int32_t* kept = a.kept + (int64_t)unit * a.keep;
+  int32_t* kept2 = a.kept_user ? a.kept_user + (int64_t)unit * a.kept_stride : nullptr;
+  const bool small = S <= a.keep;
+  const bool bad = S > c.pages_cap * kAttnPage;
+  if (small || bad) {
+    if (EMIT && wg == 0) {
+      const int cnt = bad ? 0 : S;
+      for (int i = tid; i < a.keep; i += kSplitT) {
+        const int v = i < cnt ? i : -1;
+        kept[i] = v;
+        if (kept2) kept2[i] = v;
+      }
+      if (g == 0 && tid == 0) a.n_out[b] = cnt;
+    }
+    return;
+  }
+  const int L = S - a.W;
+  const int k_pref = a.keep - a.W;
+  const float4* pv4 = reinterpret_cast<const float4*>(a.pooled + (int64_t)unit * a.s_cap);
+  const int n4 = (L + 3) / 4;
+  int gbeg, gend;
+  split_slice(n4, a.sel_split, wg, gbeg, gend);
+  uint32_t tau, mask, need_eq;
+  split_threshold(a.sel_hist + (int64_t)unit * 4 * 256, 4, (uint32_t)k_pref, tau, mask, need_eq);
+  uint32_t* slice_cnt = a.sel_hist + (int64_t)units * 4 * 256 + (int64_t)unit * a.sel_split * 2;
+
+  // wavefront w of the workgroup owns groups [wbeg, wend) of the slice, a multiple of 64 long
+  const int gpw = ((gend - gbeg + kSplitT / kWave - 1) / (kSplitT / kWave) + kWave - 1) / kWave * kWave;
+  const int wbeg = min(gbeg + wave * gpw, gend), wend = min(wbeg + gpw, gend);
+  uint32_t cgt = 0, ceq = 0;
+  for (int base = wbeg; base < wend; base += kWave * 4) {
+    float4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int q = base + u * kWave + lane;
+      v[u] = q < wend ? pv4[q] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int q = base + u * kWave + lane;
+      const float x[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const uint32_t key = order_key(x[e]);
+        const bool in = q < wend && 4 * q + e < L;
+        cgt += in && key > tau;
+        ceq += in && key == tau;
+      }
+    }
+  }
+  {
+    const uint32_t tg = wave_incl_scan(cgt), te = wave_incl_scan(ceq);
+    if (lane == kWave - 1) {
+      wsum[wave] = tg;
+      wsum_eq[wave] = te;
+    }
+  }
+  __syncthreads();
+  if (!EMIT) {
+    if (tid == 0) {
+      uint32_t tg = 0, te = 0;
+      for (int w = 0; w < kSplitT / kWave; ++w) {
+        tg += wsum[w];
+        te += wsum_eq[w];
+      }
+      slice_cnt[wg * 2] = tg;
+      slice_cnt[wg * 2 + 1] = te;
+    }
+    return;
+  }
+  // keys above / equal to the threshold before this wavefront: earlier slices, earlier wavefronts
+  uint32_t gt = 0, eq = 0;
+  {
+    uint32_t pg = 0, pe = 0;
+    if (lane < wg) {  // sel_split <= 64 (host)
+      pg = slice_cnt[lane * 2];
+      pe = slice_cnt[lane * 2 + 1];
+    }
+    gt = (uint32_t)__builtin_amdgcn_readlane((int)wave_incl_scan(pg), kWave - 1);
+    eq = (uint32_t)__builtin_amdgcn_readlane((int)wave_incl_scan(pe), kWave - 1);
+  }
+  for (int w = 0; w < wave; ++w) {
+    gt += wsum[w];
+    eq += wsum_eq[w];
+  }
+  for (int base = wbeg; base < wend; base += kWave * 4) {
+    float4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int q = base + u * kWave + lane;
+      v[u] = q < wend ? pv4[q] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int q = base + u * kWave + lane;
+      const float x[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+      uint32_t key[4];
+      uint32_t ng = 0, ne = 0;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        key[e] = order_key(x[e]);
+        const bool in = q < wend && 4 * q + e < L;
+        ng += in && key[e] > tau;
+        ne += in && key[e] == tau;
+      }
+      const uint32_t sg = wave_incl_scan(ng), se = wave_incl_scan(ne);
+      uint32_t mgt = gt + sg - ng, meq = eq + se - ne;  // before this lane's four positions
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const bool in = q < wend && 4 * q + e < L;
+        bool take = in && key[e] > tau;
+        uint32_t eq_taken = min(meq, need_eq);
+        if (in && key[e] == tau) {
+          take = meq < need_eq;
+          eq_taken = meq;
+          ++meq;
+        }
+        if (take) {
+          const uint32_t pos = mgt + eq_taken;
+          if ((int)pos < k_pref) {
+            kept[pos] = 4 * q + e;
+            if (kept2) kept2[pos] = 4 * q + e;
+          }
+        }
+        if (in && key[e] > tau) ++mgt;
+      }
+      gt += (uint32_t)__builtin_amdgcn_readlane((int)sg, kWave - 1);
+      eq += (uint32_t)__builtin_amdgcn_readlane((int)se, kWave - 1);
+    }
+  }
+  if (wg == 0) {
+    for (int w = tid; w < a.W; w += kSplitT) {
+      kept[k_pref + w] = L + w;
+      if (kept2) kept2[k_pref + w] = L + w;
+    }
+    if (g == 0 && tid == 0) a.n_out[b] = a.keep;
+  }
+}
+
+__global__ __launch_bounds__(256) void snap_split_zero_kernel(uint32_t* p, int n) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
+
 // The same selection for prompts of up to ROCKETKV_MAX_PAGES tokens, through the register-resident
 // top-k that Step 2 of the decode path uses for its page scores (one token = one page of size 1,
 // budget = the prefix share of the keep budget): every pooled vote is read once, where the radix
@@ -811,6 +1069,14 @@ SnapPlan plan_snapkv(const CacheView& src, int window, int keep) {
   off += up(units * s_cap * sizeof(float));
   p.kept_off = off;
   off += up(units * (size_t)keep * sizeof(int32_t));
+  // long prompts of few units: the select runs as several workgroups per unit over several launches
+  p.sel_split = 0;
+  if (s_cap > ROCKETKV_MAX_PAGES && units <= 64) {
+    int split = (int)(256 / units);
+    p.sel_split = split > 32 ? 32 : split;
+  }
+  p.sel_off = off;
+  off += up(units * (size_t)(4 * 256 + 2 * 64) * sizeof(uint32_t));
   p.total_bytes = off;
   return p;
 }
@@ -840,6 +1106,8 @@ hipError_t launch_snapkv(const bf16_t* q_obs, const CacheView& src, int window, 
   a.kept_user = kept_idx;
   a.kept_stride = kept_stride;
   a.n_out = n_out;
+  a.sel_hist = reinterpret_cast<uint32_t*>(base + plan.sel_off);
+  a.sel_split = plan.sel_split;
 
   const dim3 sgrid(plan.n_chunks, units);
   const size_t vote_bytes = (size_t)a.CG * a.chunk_pages * kAttnPage * sizeof(float);
@@ -857,10 +1125,19 @@ hipError_t launch_snapkv(const bf16_t* q_obs, const CacheView& src, int window, 
   const dim3 pgrid((a.s_cap + kPoolTile - 1) / kPoolTile, units);
   hipLaunchKernelGGL(snap_pool_kernel, pgrid, dim3(256), 2 * (kPoolTile + 2 * a.pool_r) * sizeof(float), st,
                      src, a);
-  if (a.s_cap <= ROCKETKV_MAX_PAGES)
+  if (a.s_cap <= ROCKETKV_MAX_PAGES) {
     hipLaunchKernelGGL(snap_select_fast_kernel, dim3(units), dim3(kSelT), 0, st, src, a);
-  else
+  } else if (plan.sel_split > 0) {
+    const int n_clear = units * (4 * 256 + 2 * plan.sel_split);
+    hipLaunchKernelGGL(snap_split_zero_kernel, dim3((n_clear + 255) / 256), dim3(256), 0, st, a.sel_hist, n_clear);
+    const dim3 hgrid(plan.sel_split, units);
+    for (int pass = 0; pass < 4; ++pass)
+      hipLaunchKernelGGL(snap_split_hist_kernel, hgrid, dim3(kSplitT), 0, st, src, a, pass);
+    hipLaunchKernelGGL(snap_split_emit_kernel<false>, hgrid, dim3(kSplitT), 0, st, src, a);
+    hipLaunchKernelGGL(snap_split_emit_kernel<true>, hgrid, dim3(kSplitT), 0, st, src, a);
+  } else {
     hipLaunchKernelGGL(snap_select_kernel, dim3(units), dim3(kSelT), 0, st, src, a);
+  }
   if (!dst) return hipGetLastError();  // filter only: the indices are the result
   const dim3 ggrid((keep + kGatherBlocks * kAttnPage - 1) / (kGatherBlocks * kAttnPage), units);
   hipLaunchKernelGGL(snap_gather_kernel, ggrid, dim3(256), 0, st, src, *dst, a);

@@ -414,6 +414,10 @@ SNAP_CASES = [
     # the same kernel on ragged lengths (a row that ends inside a 16-byte group, a prompt below the keep budget)
     ("mistral_snap_128k", dict(batch=3, context=50003, snap_keep=1000, n_heavy=12, n_q_heads=2, n_kv_heads=1),
      (50003, 33001, 700), 31, True),
+    # more than 64 units of such prompts: one workgroup per unit and a single launch (fewer units take
+    # several workgroups per unit over several launches, as in the two cases above)
+    ("mistral_snap_128k", dict(batch=13, context=33000, snap_keep=512, window=16, n_heavy=6, n_q_heads=5, n_kv_heads=5),
+     None, 15, False),
 ]
 
 
