@@ -33,8 +33,12 @@ def build(force: bool = False) -> str:
 def _load():
     global _lib
     if _lib is None:
-        build()
-        _lib = C.CDLL(_LIB)
+        # ROCKETKV_ORACLE_LIB: a library built elsewhere from a copy of the source (the tests that plant
+        # mistakes in the oracle and check that the pins notice use it); otherwise the one beside this file
+        other = os.environ.get("ROCKETKV_ORACLE_LIB")
+        if not other:
+            build()
+        _lib = C.CDLL(other or _LIB)
         _lib.okv_num_threads.restype = C.c_int
         _lib.okv_pages_to_pick.restype = C.c_int
         _lib.okv_snapkv_unit.restype = C.c_int
