@@ -190,3 +190,28 @@ def test_multi_turn_argument_checks(L):
     small_ix = rk.IndexStruct(0x3000, 0x4000, 4, 8)  # 32 entries per row < keep budget
     r = L.rocketkv_snapkv_filter(0x5000, C.byref(tm), 32, 63, 1024, C.byref(small_ix), 0x10000, 1 << 30, None)
     assert r == rk.INVALID_ARG and "keep_budget" in rk.last_error()
+
+
+def test_product_and_oracle_do_not_know_each_other():
+    """The HIP path and the oracle share no code: nothing under the package imports, includes or opens
+    anything of ``oracle/``, and the oracle includes none of the package's headers and imports none of its
+    modules (the seeded input generators are handed to it as data by the tests)."""
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    pkg = os.path.join(root, "paper_2502_14051_amd")
+    for base, _, files in os.walk(pkg):
+        if "_build" in base or "__pycache__" in base:
+            continue
+        for f in files:
+            if not f.endswith((".py", ".hip", ".h", ".c", ".cpp")):
+                continue
+            text = open(os.path.join(base, f), encoding="utf-8").read()
+            assert not re.search(r"^\s*(import|from)\s+oracle\b", text, re.M), f
+            assert "rocketkv_oracle" not in text and "oracle/" not in text, f
+    for f in os.listdir(os.path.join(root, "oracle")):
+        if not f.endswith((".py", ".c", ".h")):
+            continue
+        text = open(os.path.join(root, "oracle", f), encoding="utf-8").read()
+        assert "paper_2502_14051_amd" not in text and "csrc" not in text, f
+        assert '#include "' not in text or "rocketkv.h" not in text, f
+    entry = open(os.path.join(root, "include", "rocketkv.h"), encoding="utf-8").read()
+    assert "oracle" not in entry.lower()
