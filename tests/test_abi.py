@@ -215,3 +215,15 @@ def test_product_and_oracle_do_not_know_each_other():
         assert '#include "' not in text or "rocketkv.h" not in text, f
     entry = open(os.path.join(root, "include", "rocketkv.h"), encoding="utf-8").read()
     assert "oracle" not in entry.lower()
+
+
+def test_missing_library_is_an_error_not_a_fallback(monkeypatch, tmp_path):
+    """Without the built library every entry point of the binding raises: there is no CPU path behind it."""
+    from paper_2502_14051_amd import rocketkv as rk
+
+    monkeypatch.setattr(rk, "_lib", None)
+    monkeypatch.setattr(rk, "LIB_PATH", str(tmp_path / "librocketkv.so"))
+    with pytest.raises(ImportError, match="no fallback"):
+        rk.lib()
+    with pytest.raises(ImportError, match="no fallback"):
+        rk.decompose(32768, 2048, 128)
