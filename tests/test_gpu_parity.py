@@ -283,6 +283,8 @@ DECODE_CASES = [
     ("tiny", dict(batch=2, n_q_heads=12, n_kv_heads=2, context=2222, token_budget=300), None, 0, True),   # G = 6
     ("tiny", dict(batch=2, n_q_heads=21, n_kv_heads=3, context=1500, token_budget=128), None, 1, False),  # G = 7
     ("tiny", dict(n_q_heads=8, n_kv_heads=2, context=140000, token_budget=2048, n_heavy=32), None, 0, False),  # > 8192 pages
+    # the largest cache the selection takes: 32768 pages, a ragged last page
+    ("tiny", dict(n_q_heads=2, n_kv_heads=1, context=32768 * 16 - 5, token_budget=4096, n_heavy=32), None, 1, False),
     # more (sequence, KV head) units than compute units: the four-wavefront launch geometry
     ("tiny", dict(batch=40, n_q_heads=32, n_kv_heads=8, context=1100, token_budget=512, n_heavy=4), None, 0, True),
 ]
@@ -414,6 +416,9 @@ SNAP_CASES = [
     # the same kernel on ragged lengths (a row that ends inside a 16-byte group, a prompt below the keep budget)
     ("mistral_snap_128k", dict(batch=3, context=50003, snap_keep=1000, n_heavy=12, n_q_heads=2, n_kv_heads=1),
      (50003, 33001, 700), 31, True),
+    # the longest prompt a source cache can hold (32768 pages), ending inside a page
+    ("mistral_snap_128k", dict(context=32768 * 16 - 3, snap_keep=2048, n_heavy=16, n_q_heads=1, n_kv_heads=1),
+     None, 63, False),
     # more than 64 units of such prompts: one workgroup per unit and a single launch (fewer units take
     # several workgroups per unit over several launches, as in the two cases above)
     ("mistral_snap_128k", dict(batch=13, context=33000, snap_keep=512, window=16, n_heavy=6, n_q_heads=5, n_kv_heads=5),
