@@ -277,10 +277,6 @@ __device__ __forceinline__ int select_pages(const CacheView& c, const SelectArgs
   float* out_scores = write_global ? a.out_scores : nullptr;
   float* tail2 = sh.s_abs;  // free since the channel pick ended; [0..1]: the two halves of tp.page's score
   tail_page_score<NT>(a, sh.s_chan, sh.s_wgt, rows, c.pages_cap, tp, tail2);
-  // Page scores share their sign and most of their exponent, so the top digit of nearly every key
-  // lands in two or three counters: from about a thousand pages on, the one-address LDS atomics
-  // cost more than grouping the lanes that share a digit (2.5 against 0.6 us at 2048 pages).
-  const bool grouped = P >= 1024;
   if (n_oct < NT) {
     int npow = 1;
     while (npow < n_oct) npow <<= 1;
@@ -305,9 +301,7 @@ __device__ __forceinline__ int select_pages(const CacheView& c, const SelectArgs
         else if (p >= P - n_rec) s = INFINITY;
         const uint32_t key = f32_order_key(s);
         keys[p] = key;
-        // the first radix pass, counted on the way
-        if (grouped) hist_add_grouped(sh.hist[0], key >> 24, p < P);
-        else if (p < P) atomicAdd(&sh.hist[0][key >> 24], 1u);
+        if (p < P) atomicAdd(&sh.hist[0][key >> 24], 1u);  // the first radix pass, counted on the way
       }
     }
   } else {
@@ -328,8 +322,7 @@ __device__ __forceinline__ int select_pages(const CacheView& c, const SelectArgs
         else if (p >= P - n_rec) s = INFINITY;
         const uint32_t key = f32_order_key(s);
         keys[p] = key;
-        if (grouped) hist_add_grouped(sh.hist[0], key >> 24, p < P);
-        else if (p < P) atomicAdd(&sh.hist[0][key >> 24], 1u);
+        if (p < P) atomicAdd(&sh.hist[0][key >> 24], 1u);  // the first radix pass, counted on the way
       }
     }
   }

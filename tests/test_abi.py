@@ -227,3 +227,20 @@ def test_missing_library_is_an_error_not_a_fallback(monkeypatch, tmp_path):
         rk.lib()
     with pytest.raises(ImportError, match="no fallback"):
         rk.decompose(32768, 2048, 128)
+
+
+def test_no_kernel_spills_registers():
+    """The build writes what the compiler reports per kernel.  No kernel of the library may use scratch
+    memory: a spill costs HBM traffic on every launch (12 bytes per lane in the fused decode kernel were
+    1.5 % of its time and 2 MB per launch) and no numerical test would ever notice."""
+    from paper_2502_14051_amd import build as b
+
+    if not os.path.exists(b.RESOURCES):
+        pytest.skip("no kernel_resources.txt: build the library first")
+    rows = [l.split() for l in open(b.RESOURCES) if l.strip() and not l.startswith("#")]
+    assert len(rows) >= 40, "the report lists fewer kernels than the library has"
+    names = " ".join(r[1] for r in rows)
+    for must in ("hsa_decode_kernel", "hsa_decode_tok_kernel", "attend_mfma_kernel", "snap_score_kernel"):
+        assert must in names, must
+    spilling = [(r[0], r[1], r[5]) for r in rows if r[5] != "0"]
+    assert not spilling, spilling
