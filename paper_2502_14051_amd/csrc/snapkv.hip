@@ -874,9 +874,9 @@ __global__ __launch_bounds__(256) void snap_split_zero_kernel(uint32_t* p, int n
 
 // The same selection for prompts of up to ROCKETKV_MAX_PAGES tokens, through the register-resident
 // top-k that Step 2 of the decode path uses for its page scores (one token = one page of size 1,
-// budget = the prefix share of the keep budget): every pooled vote is read once, where the radix
-// kernel above walks the row five times, twice of them with a stride that defeats coalescing.  Same
-// result: the k largest, ties to the lower position, ascending.
+// budget = the prefix share of the keep budget): every pooled vote is read once and stays in
+// registers, where the radix kernels above walk the row six times.  Same result: the k largest, ties
+// to the lower position, ascending.
 __global__ __launch_bounds__(kSelT) void snap_select_fast_kernel(CacheView c, SnapArgs a) {
   __shared__ PickShared<kSelT> sh;
   const int tid = threadIdx.x;
