@@ -182,3 +182,48 @@ def test_long_decode_256_graph_replays(env, oracle):
     check_selection(oracle, ds, wl.scaled(w, context=n0 + steps), A["cache"].pages_cap, gp, None, None, 1)
     want_y, _ = oracle.attend_given(full["q"], full["K"], full["V"], lens, 16, gp)
     assert_attention_close(wl.to_bits(A["out"]), want_y, "last replay")
+
+
+@pytest.mark.parametrize("S,N", [(3000, 512), (40000, 1024)])
+def test_snapkv_graph_replays(env, S, N):
+    """The SnapKV stage captured once and replayed: every replay over changed inputs must equal the eager
+    call on the same inputs, bit for bit.  The 40000-token prompt takes the select of several launches,
+    whose histograms in the workspace are cleared by a kernel (a captured memset would not do)."""
+    torch, rk, dev = env
+    W = 32
+    w = small("mistral_snap_128k", batch=2, n_q_heads=4, n_kv_heads=2, context=S, snap_keep=N, window=W, n_heavy=8)
+    say("snapkv graph", S, N)
+    d = wl.generate(w, with_obs=True)
+    src, _ = to_device_cache(rk, torch, d, w.n_q_heads, 16, dev)
+    qobs = wl.from_bits(d["qobs"], dev)
+    P = (N + 15) // 16
+
+    def fresh():
+        return (rk.alloc_cache(w.batch, w.n_q_heads, w.n_kv_heads, 128, 16, P, dev, zero=True),
+                torch.full((w.batch, w.n_kv_heads, N), -7, dtype=torch.int32, device=dev),
+                rk.alloc_workspace(rk.OP_SNAPKV, src, W, N))
+
+    dst_g, kept_g, ws_g = fresh()
+    dst_e, kept_e, ws_e = fresh()
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        rk.snapkv_compress(qobs, src, W, 63, N, dst_g, kept_g, ws_g, stream)  # warm
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            rk.snapkv_compress(qobs, src, W, 63, N, dst_g, kept_g, ws_g, stream)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(5)
+    for rep in range(3):
+        # new queries in place: the captured launches read the same buffers
+        qobs.copy_((torch.randn(qobs.shape, generator=gen, device=dev) * (1.0 + rep)).to(torch.bfloat16))
+        kept_g.fill_(-7)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        rk.snapkv_compress(qobs, src, W, 63, N, dst_e, kept_e, ws_e)
+        torch.cuda.synchronize()
+        assert torch.equal(kept_g, kept_e), f"replay {rep}: kept indices differ"
+        assert torch.equal(dst_g.k_pool, dst_e.k_pool) and torch.equal(dst_g.v_pool, dst_e.v_pool), f"replay {rep}"
+        assert torch.equal(dst_g.seq_lens, dst_e.seq_lens)
+        assert int((kept_g >= 0).sum()) == w.batch * w.n_kv_heads * N
