@@ -35,7 +35,8 @@ def _load():
     if _lib is None:
         # ROCKETKV_ORACLE_LIB: a library built elsewhere from a copy of the source (the tests that plant
         # mistakes in the oracle and check that the pins notice use it); otherwise the one beside this file
-        other = os.environ.get("ROCKETKV_ORACLE_LIB")
+        # (honoured only when ROCKETKV_ORACLE_MUTANT_RUN=1 is set as well, which only that test does)
+        other = os.environ.get("ROCKETKV_ORACLE_LIB") if os.environ.get("ROCKETKV_ORACLE_MUTANT_RUN") == "1" else None
         if not other:
             build()
         _lib = C.CDLL(other or _LIB)

@@ -65,6 +65,8 @@ int check_cache(const rocketkv_cache_t* c, bool need_pools, const char* who) {
                   "%s: strides must be multiples of 8 elements with stride_head >= page_size*head_dim "
                   "and stride_page >= n_kv_heads*page_size*head_dim", who);
     if (c->n_phys_pages < 1) return fail(ROCKETKV_INVALID_ARG, "%s: n_phys_pages must be positive", who);
+    if (c->n_phys_pages > 2147483647ll)
+      return fail(ROCKETKV_UNSUPPORTED, "%s: n_phys_pages %lld exceeds 2^31 - 1", who, (long long)c->n_phys_pages);
     if (!c->block_table && c->n_phys_pages < (int64_t)c->batch * c->pages_cap)
       return fail(ROCKETKV_INVALID_ARG,
                   "%s: identity block table needs n_phys_pages >= batch * pages_cap", who);

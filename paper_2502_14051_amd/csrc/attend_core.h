@@ -16,9 +16,10 @@
 // 4kg..4kg+3 of each, which is exactly how the S tiles come out of the first product.
 //
 // Latency matters as much as bandwidth here (a layer moves only tens of MB): a wavefront reads the
-// page ids of its whole share with one load, keeps the next page pair's 16 KiB in flight while it
-// works on the current one, and the split partials are handed over with write-through stores and a
-// relaxed device-scope counter instead of cache-flushing fences.
+// page ids of its whole share with one load and requests a page pair's 16 KiB in one go (one pair in
+// flight per wavefront, the other wavefronts of the SIMD cover its softmax step), and the split
+// partials are handed over with write-through stores, an explicit wait for their acknowledgement and
+// a relaxed device-scope counter instead of cache-flushing fences.
 #pragma once
 
 #include "common.h"
@@ -244,6 +245,7 @@ __device__ __forceinline__ void attend_merge(const CacheView& c, const AttendArg
     }
   }
   __syncthreads();
+  RKV_STAMP(8);
   const int64_t out_base = ((int64_t)b * c.n_q_heads + (int64_t)g * G) * kHeadDim;
   for (int idx = tid; idx < G * kHeadDim; idx += kThreads) {
     const int h = idx / kHeadDim, ch = idx % kHeadDim;
@@ -274,13 +276,16 @@ __device__ __forceinline__ void attend_merge(const CacheView& c, const AttendArg
   if (a.n_split == 1) return;
 
   // ---- last workgroup of the unit merges the split partials --------------------------------------
-  __syncthreads();  // every store of this workgroup has been acknowledged
+  RKV_STAMP(9);
+  drain_stores();   // this thread's partials (and whatever else it stored) have been acknowledged ...
+  __syncthreads();  // ... and so have every other thread's, before thread 0 reports
   if (tid == 0) {
     const uint32_t old = __hip_atomic_fetch_add(&a.counters[unit], 1u, __ATOMIC_RELAXED,
                                                 __HIP_MEMORY_SCOPE_AGENT);
     *s_last = (old == (uint32_t)a.n_split - 1u);
   }
   __syncthreads();
+  RKV_STAMP(10);
   if (!*s_last) return;
   for (int idx = tid; idx < G * kHeadDim; idx += kThreads) {
     const int h = idx / kHeadDim, ch = idx % kHeadDim;
@@ -318,6 +323,7 @@ __device__ __forceinline__ void attend_merge(const CacheView& c, const AttendArg
       a.out_lse[(int64_t)b * c.n_q_heads + g * G + h] = den > 0.f ? (M + log2f(den)) * kLn2 : -INFINITY;
   }
   if (tid == 0) __hip_atomic_store(&a.counters[unit], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  RKV_STAMP(11);
 }
 
 // The attention of one workgroup: its share (`split`) of the page list of `unit`, then the merges.
@@ -421,11 +427,13 @@ __device__ __forceinline__ void attend_block(const CacheView& c, const AttendArg
         softmax_round<NP, false>(kf, vf, ids, qf, O, m, l, have_acc, n, hn, kg, sc, tp);
       else
         softmax_round<NP, true>(kf, vf, ids, qf, O, m, l, have_acc, n, hn, kg, sc, tp);
+      if (!have_acc) RKV_STAMP(6);
       have_acc = true;
     }
   }
   l += __shfl_xor(l, 16);
   l += __shfl_xor(l, 32);
+  RKV_STAMP(7);
   after_stream();
   attend_merge<WAVES>(c, a, unit, split, O, m, l, smem, s_last, b, g);
 }

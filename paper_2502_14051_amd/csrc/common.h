@@ -42,6 +42,32 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
   return (bf16_t)(u >> 16);
 }
 
+// Hand-off of data between workgroups of one launch, as used by every last-arriver scheme here:
+//   producer: device-scope (write-through) stores; drain_stores() in EVERY storing thread; a workgroup
+//             barrier; one thread adds to a device-scope counter.
+//   consumer: the workgroup whose add returns the last count reads the data with device-scope loads
+//             (issued after a barrier that follows the add, hence after its answer).
+// drain_stores() is what orders the stores before the counter: it holds the wavefront until the
+// memory system has acknowledged every vector store (and load) it has issued, so once the barrier
+// has let the adding thread through, all of the workgroup's data is visible device-wide.  A barrier
+// alone does not wait for stores in flight.
+__device__ __forceinline__ void drain_stores() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// Diagnostic build only (-DRKV_STAMPS, never the shipped library): lane 0 of every wavefront of a few
+// workgroups of the fused decode kernel notes the 100 MHz clock at phase boundaries.
+#ifdef RKV_STAMPS
+constexpr int kStampSlots = 64, kStampWaves = 8, kStampMarks = 16;
+static __device__ unsigned long long g_stamps[kStampSlots * 2 * kStampWaves * kStampMarks];
+#define RKV_STAMP(k)                                                                                          \
+  do {                                                                                                        \
+    if (threadIdx.x % 64 == 0 && blockIdx.x % 16 == 3 && blockIdx.x / 16 < rkv::kStampSlots && blockIdx.y < 2) \
+      rkv::g_stamps[(((blockIdx.x / 16) * 2 + blockIdx.y) * rkv::kStampWaves + threadIdx.x / 64) *            \
+                        rkv::kStampMarks + (k)] = __builtin_amdgcn_s_memrealtime();                          \
+  } while (0)
+#else
+#define RKV_STAMP(k) do { } while (0)
+#endif
+
 // Inclusive prefix sum over the 64 lanes of a wavefront with data-parallel-primitive moves (four
 // shifts inside each row of 16 lanes, then two row broadcasts): six adds and no LDS round trips.
 __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t x) {

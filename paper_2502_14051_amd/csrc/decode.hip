@@ -27,7 +27,6 @@ void hsa_decode_kernel(CacheView c, SelectArgs sa, AttendArgs aa, AppendArgs ap,
   constexpr int NT = WAVES * kWave;
   extern __shared__ __align__(16) unsigned char dsm[];  // [staged k,v][list][selection scratch | merge buffer]
   __shared__ int s_last;
-  __shared__ int s_n0;
   const int tid = threadIdx.x;
   const int unit = blockIdx.x, split = blockIdx.y;
   const int b = unit / c.n_kv_heads, g = unit % c.n_kv_heads;
@@ -38,19 +37,25 @@ void hsa_decode_kernel(CacheView c, SelectArgs sa, AttendArgs aa, AppendArgs ap,
   SelectShared<NT>& sh = *reinterpret_cast<SelectShared<NT>*>(region);
   uint32_t* keys = reinterpret_cast<uint32_t*>(region + round16(sizeof(SelectShared<NT>)));
 
+  RKV_STAMP(0);
   TailPatch tp = {-1, 0, s_knew, s_vnew};
   for (int i = tid; i < sa.row_len; i += NT) list[i] = -1;
+  // Everything the selection starts from is requested before anything is used, so that q, the new
+  // key / value and the length cost one memory round trip together.
+  uint32_t qv[kMaxGroup];  // one bf16 each, kept in a register of its own (no packing, hence no early use)
+  load_q_column(c, sa, unit, qv);
   int n = 0;
   uint32_t arrivals = 0;
   bf16_t kb = 0, vb = 0;
   if (!APPEND) {
     n = c.seq_lens[b];  // in flight during the channel pick, which does not need it
   } else {
-    // One thread reads the old length for the whole workgroup; later the workgroup reports that read
-    // to the per-sequence counter, and the one that finds every other workgroup of the sequence has
-    // reported stores the new length at the very end: no thread anywhere sees the length change
-    // under it.
-    if (tid == 0) s_n0 = c.seq_lens[b];
+    // Every thread reads the old length itself (a vector load that travels with the others; a scalar
+    // load here would be waited for before the loads behind it are even issued).  After its K/V
+    // stream the workgroup reports that read to the per-sequence counter, and the one that finds every
+    // other workgroup of the sequence has reported stores the new length at its very end: no thread
+    // anywhere sees the length change under it.
+    n = __hip_atomic_load(&c.seq_lens[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (tid < kHeadDim) {
       const int64_t src = ((int64_t)b * c.n_kv_heads + g) * kHeadDim + tid;
       kb = ap.k_new[src];
@@ -59,11 +64,11 @@ void hsa_decode_kernel(CacheView c, SelectArgs sa, AttendArgs aa, AppendArgs ap,
       s_vnew[tid] = vb;
     }
   }
-  select_channels<NT>(c, sa, unit, sh, split == 0);  // ends with a barrier: s_n0 and the staging are visible
+  select_channels<NT>(c, sa, unit, sh, split == 0, qv);  // ends with a barrier: the staging is visible
+  RKV_STAMP(1);
   bool room = false;
   if (APPEND) {
-    const int n0 = s_n0;
-    n = n0;
+    const int n0 = n;
     room = n0 < c.pages_cap * kAttnPage;
     if (room) {
       tp.page = n0 / kAttnPage;
@@ -73,27 +78,30 @@ void hsa_decode_kernel(CacheView c, SelectArgs sa, AttendArgs aa, AppendArgs ap,
   }
   // the summary column the new key goes into, fetched now (beside the row loads) and stored at the end
   bf16_t old_max = 0, old_min = 0;
-  const int64_t sum_off = ((int64_t)unit * kHeadDim + (tid & (kHeadDim - 1))) * c.pages_cap + (room ? tp.page : 0);
-  int64_t pp_new = -1;  // where the new token's page lives: looked up now, needed at the end
+  const auto summary_slot = [&]() {
+    return ((int64_t)unit * kHeadDim + (tid & (kHeadDim - 1))) * c.pages_cap + (room ? tp.page : 0);
+  };
+  int32_t pp_new = -1;  // where the new token's page lives (pools hold fewer than 2^31 pages): looked up now, needed at the end
   if (APPEND && room && split == 0 && tid < kHeadDim) {
-    pp_new = phys_page(c, b, tp.page);
+    pp_new = (int32_t)phys_page(c, b, tp.page);
     if (tp.slot != 0) {
-      old_max = ap.kmax[sum_off];
-      old_min = ap.kmin[sum_off];
+      old_max = ap.kmax[summary_slot()];
+      old_min = ap.kmin[summary_slot()];
     }
   }
   select_pages<NT>(c, sa, unit, n, sh, keys, list, split == 0, tp);
   __syncthreads();  // list complete; the selection scratch is dead and becomes the merge buffer
-  // Runs after this thread's last K/V tile, so that the stores and the counter round trip drain under
-  // the merges: split 0 of the unit stores the key row, the value column and the updated summary
-  // column for later steps, and thread 0 reports this workgroup's read of the old length.
+  RKV_STAMP(5);
+  // Runs after this thread's last K/V tile, so that the stores drain under the merges: split 0 of the
+  // unit stores the key row, the value column and the updated summary column for later steps.
   auto write_back = [&]() {
     if (!APPEND) return;
-    if (tid == 0)
+    if (tid == 0)  // this workgroup's read of the old length, reported where the answer's latency hides under the merges
       arrivals = __hip_atomic_fetch_add(&seq_counters[b], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (room && split == 0 && tid < kHeadDim) {
+      const int64_t sum_off = summary_slot();
       if (pp_new >= 0) {
-        const int64_t base = pp_new * c.stride_page + (int64_t)g * c.stride_head;
+        const int64_t base = (int64_t)pp_new * c.stride_page + (int64_t)g * c.stride_head;
         c.k_pool[base + tp.slot * kHeadDim + tid] = kb;
         c.v_pool[base + tid * kAttnPage + tp.slot] = vb;
       }
@@ -104,6 +112,7 @@ void hsa_decode_kernel(CacheView c, SelectArgs sa, AttendArgs aa, AppendArgs ap,
   };
   attend_block<WAVES, 1, STREAM_K>(c, aa, unit, split, n, list, reinterpret_cast<float*>(region), &s_last, tp, write_back);
 
+  RKV_STAMP(12);
   if (APPEND) {
     // the last workgroup of the sequence to have read the old length stores the new one
     if (tid == 0 && arrivals == (uint32_t)c.n_kv_heads * gridDim.y - 1u) {
@@ -112,6 +121,17 @@ void hsa_decode_kernel(CacheView c, SelectArgs sa, AttendArgs aa, AppendArgs ap,
     }
   }
 }
+
+#ifdef RKV_STAMPS
+extern "C" int rocketkv_debug_stamps(void* host, size_t bytes, int clear) {
+  if (clear) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_stamps)) != hipSuccess) return -1;
+    return hipMemset(p, 0, sizeof(unsigned long long) * kStampSlots * 2 * kStampWaves * kStampMarks) == hipSuccess ? 0 : -1;
+  }
+  return hipMemcpyFromSymbol(host, HIP_SYMBOL(g_stamps), bytes) == hipSuccess ? 0 : -1;
+}
+#endif
 
 size_t fused_decode_lds_bytes(const CacheView& c, int row_len, const AttendPlan& plan) {
   const size_t sel = round16(plan.waves == 8 ? sizeof(SelectShared<512>) : sizeof(SelectShared<256>)) +

@@ -29,7 +29,6 @@ void hsa_decode_tok_kernel(CacheView c, CacheView lc, SelectArgs sa, AttendArgs 
   constexpr int NT = WAVES * kWave;
   extern __shared__ __align__(16) unsigned char dsm[];  // [staged k,v][list][selection scratch | merge buffer]
   __shared__ int s_last;
-  __shared__ int s_n0, s_pos0;
   const int tid = threadIdx.x;
   const int unit = blockIdx.x, split = blockIdx.y;
   const int b = unit / c.n_kv_heads, g = unit % c.n_kv_heads;
@@ -44,17 +43,20 @@ void hsa_decode_tok_kernel(CacheView c, CacheView lc, SelectArgs sa, AttendArgs 
   TailPatch tp = {-1, 0, s_knew, s_vnew};
   TokenPatch tokp = {-1, s_knew, s_vnew};
   for (int i = tid; i < sa.row_len; i += NT) list[i] = -1;
+  // q, the new key / value and the lengths: all requested before anything is used (one round trip)
+  uint32_t qv[kMaxGroup];  // one bf16 each, kept in a register of its own (no packing, hence no early use)
+  load_q_column(lc, sa, unit, qv);
   int n = 0;
+  int pos0 = 0;  // where the new token goes in the cache
   uint32_t arrivals = 0;
   bf16_t kb = 0, vb = 0;
   if (!APPEND) {
     n = lc.seq_lens[b];  // in flight during the channel pick, which does not need it
   } else {
-    // one thread reads the old lengths for the whole workgroup (see the header comment)
-    if (tid == 0) {
-      s_n0 = lc.seq_lens[b];
-      s_pos0 = INDEXED ? c.seq_lens[b] : 0;
-    }
+    // every thread reads the old lengths itself, with vector loads that travel with the others (see
+    // the header comment for how the workgroup reports these reads)
+    n = __hip_atomic_load(&lc.seq_lens[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (INDEXED) pos0 = __hip_atomic_load(&c.seq_lens[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (tid < kHeadDim) {
       const int64_t src = (int64_t)unit * kHeadDim + tid;
       kb = ap.k_new[src];
@@ -63,13 +65,11 @@ void hsa_decode_tok_kernel(CacheView c, CacheView lc, SelectArgs sa, AttendArgs 
       s_vnew[tid] = vb;
     }
   }
-  select_channels<NT>(lc, sa, unit, sh, split == 0);  // ends with a barrier: lengths and staging are visible
+  select_channels<NT>(lc, sa, unit, sh, split == 0, qv);  // ends with a barrier: the staging is visible
   bool room = false;
-  int pos0 = 0;  // where the new token goes in the cache
   if (APPEND) {
-    const int n0 = s_n0;
-    n = n0;
-    pos0 = INDEXED ? s_pos0 : n0;
+    const int n0 = n;
+    if (!INDEXED) pos0 = n0;
     room = n0 < lc.pages_cap * ps && pos0 < c.pages_cap * c.page_size;
     if (room) {
       tp.page = n0 / ps;
@@ -89,7 +89,7 @@ void hsa_decode_tok_kernel(CacheView c, CacheView lc, SelectArgs sa, AttendArgs 
   __syncthreads();  // list complete; the selection scratch is dead and becomes the merge buffer
   auto write_back = [&]() {
     if (!APPEND) return;
-    if (tid == 0)
+    if (tid == 0)  // this workgroup's read of the old length, reported where the answer's latency hides under the merges
       arrivals = __hip_atomic_fetch_add(&seq_counters[b], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (room && split == 0 && tid < kHeadDim) {
       const int sp = pos0 / c.page_size, ss = pos0 % c.page_size;

@@ -30,7 +30,7 @@ __global__ __launch_bounds__(kSelThreads) void hsa_select_kernel(CacheView c, Se
 //                         picks the top-k right there, a launch boundary and a round trip earlier.
 //
 // APPEND: the launch also takes in the token generated at this step (Section 3.4 Step 1, last
-// sentence).  Every workgroup reads the old length once, scores with the new key folded into the tail
+// sentence).  Every workgroup reads the old length at its start, scores with the new key folded into the tail
 // page's bound from an LDS copy (so it does not matter whether the write-back has landed), and reports
 // its read; workgroup 0 of each (sequence, KV head) writes the key row, the value row or column and
 // the summary column.  Reports go to two levels of counters so that none sees more than a handful of
@@ -49,29 +49,32 @@ template <int NT, bool APPEND, bool PICK>
 __global__ __launch_bounds__(NT) void hsa_score_kernel(CacheView c, SelectArgs a, AppendArgs ap,
                                                        uint32_t* unit_counters, uint32_t* seq_counters) {
   __shared__ __align__(16) unsigned char lds[ScoreLds<NT, PICK>::kBytes];  // selection state, then the pick's
-  __shared__ int s_n0, s_last;
+  __shared__ int s_last;
   __shared__ bf16_t s_knew[kHeadDim];
   SelectShared<NT>& sh = *reinterpret_cast<SelectShared<NT>*>(lds);
   const int tid = threadIdx.x;
   const int unit = blockIdx.y;
   const int b = unit / c.n_kv_heads, g = unit % c.n_kv_heads;
+  // q, the new key / value and the length: all requested before anything is used (one round trip)
+  uint32_t qv[kMaxGroup];  // one bf16 each, kept in a register of its own (no packing, hence no early use)
+  load_q_column(c, a, unit, qv);
   int n = 0;
   bf16_t kb = 0, vb = 0;
   if (!APPEND) {
     n = c.seq_lens[b];  // not needed until the channels are picked
   } else {
-    if (tid == 0) s_n0 = c.seq_lens[b];
+    // every thread reads the old length itself: a vector load that travels with the others
+    n = __hip_atomic_load(&c.seq_lens[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (tid < kHeadDim) {
       kb = ap.k_new[(int64_t)unit * kHeadDim + tid];
       if (blockIdx.x == 0) vb = ap.v_new[(int64_t)unit * kHeadDim + tid];
       s_knew[tid] = kb;
     }
   }
-  select_channels<NT>(c, a, unit, sh, blockIdx.x == 0);  // its barriers publish s_n0 / s_knew
+  select_channels<NT>(c, a, unit, sh, blockIdx.x == 0, qv);  // its barriers publish s_knew
   TailPatch tp = {-1, 0, s_knew, nullptr};
   bool room = false;
   if (APPEND) {
-    n = s_n0;
     room = n < c.pages_cap * c.page_size;
     if (room) {
       tp.page = n / c.page_size;
@@ -107,7 +110,8 @@ __global__ __launch_bounds__(NT) void hsa_score_kernel(CacheView c, SelectArgs a
     if (tp.slot == 0 || x < bf16_to_f32(old_min)) ap.kmin[sum_off] = kb;
   }
   if (!APPEND && !PICK) return;
-  // (score_chunk ended with a barrier: with PICK, this workgroup's scores have been acknowledged)
+  // (score_chunk ended with a wait for the stores' acknowledgement and a barrier: with PICK, this
+  // workgroup's scores are visible device-wide before thread 0 reports)
   if (tid == 0) {
     const bool last = __hip_atomic_fetch_add(&unit_counters[unit], 1u, __ATOMIC_RELAXED,
                                              __HIP_MEMORY_SCOPE_AGENT) == gridDim.x - 1u;

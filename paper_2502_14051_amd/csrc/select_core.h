@@ -47,22 +47,32 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* wsum) 
   return base + inc - v;
 }
 
-// accumulate eight rows' worth of eight-page runs; every load of the batch is issued before use
-// (the page that is receiving a token in the same launch gets its score from tail_page_score instead)
+// accumulate eight rows' worth of eight-page runs.  The rows are j0 + t * jstep, t = 0..7, with
+// `jbase` the smallest j0 of the workgroup in this batch: whether batch slot t holds a row at all is
+// then the same for every thread (a scalar branch), and a thread whose own row falls beyond k1 reads
+// the last picked row with weight zero.  The channel / weight lookups (LDS) all come first and the
+// eight 16-byte loads go out back to back, so the batch costs one LDS and one memory round trip.
+// (The page that is receiving a token in the same launch gets its score from the tail-page routines.)
 template <bool STREAM = false>
 __device__ __forceinline__ void score_rows8(const SelectArgs& a, const int* s_chan, const float* s_wgt,
-                                            int64_t rows, int pages_cap, int o, int j0, int jstep,
+                                            int64_t rows, int pages_cap, int o, int j0, int jbase, int jstep,
                                             float (&acc)[8]) {
   uint4 v[8];
   float w[8];
+  int ch[8];
 #pragma unroll
   for (int t = 0; t < 8; ++t) {
     const int j = j0 + t * jstep;
-    w[t] = 0.f;
+    const int jj = j < a.k1 ? j : a.k1 - 1;
+    ch[t] = s_chan[jj];
+    w[t] = s_wgt[jj];
+    if (j >= a.k1) w[t] = 0.f;
+  }
+#pragma unroll
+  for (int t = 0; t < 8; ++t) {
     v[t] = make_uint4(0, 0, 0, 0);
-    if (j < a.k1) {
-      w[t] = s_wgt[j];
-      const bf16_t* row = (w[t] >= 0.f ? a.kmax : a.kmin) + (rows + s_chan[j]) * pages_cap + o * 8;
+    if (jbase + t * jstep < a.k1) {  // uniform over the workgroup
+      const bf16_t* row = (w[t] >= 0.f ? a.kmax : a.kmin) + (rows + ch[t]) * pages_cap + o * 8;
       v[t] = ld16<STREAM>(row);
     }
   }
@@ -77,24 +87,34 @@ __device__ __forceinline__ void score_rows8(const SelectArgs& a, const int* s_ch
   }
 }
 
-// The score of the page that is receiving a token (tp.page), computed on its own by the first two
+// The score of the page that is receiving a token (tp.page) is computed on its own by the first two
 // wavefronts from the page's old bounds and the new key, one picked channel per thread: the bound of
 // a channel is the old one folded with the new key's value, or the new value alone when the token
-// opens the page (whatever memory holds for that column is then not looked at).  The two partial
-// sums go to out2[0..1]; the caller adds them (fixed order) where it turns scores into keys, after a
-// barrier.  Cheaper than patching the packed rows in every wavefront that scores them.
+// opens the page (whatever memory holds for that column is then not looked at).  Cheaper than
+// patching the packed rows in every wavefront that scores them.  In two parts, so that the lookup of
+// the old bound goes out before the caller's row loads and is used after them (one memory round trip
+// for both): tail_page_load returns the old bound's bits, tail_page_finish leaves the two wavefronts'
+// partial sums in out2[0..1]; the caller adds them (fixed order) after a barrier.
 template <int NT>
-__device__ __forceinline__ void tail_page_score(const SelectArgs& a, const int* s_chan, const float* s_wgt,
-                                                int64_t rows, int pages_cap, const TailPatch& tp, float* out2) {
+__device__ __forceinline__ bf16_t tail_page_load(const SelectArgs& a, const int* s_chan, const float* s_wgt,
+                                                 int64_t rows, int pages_cap, const TailPatch& tp) {
+  const int tid = threadIdx.x;
+  bf16_t old = 0;
+  if (tp.page >= 0 && tp.slot != 0 && tid < a.k1)
+    old = ((s_wgt[tid] >= 0.f) ? a.kmax : a.kmin)[(rows + s_chan[tid]) * pages_cap + tp.page];
+  return old;
+}
+template <int NT>
+__device__ __forceinline__ void tail_page_finish(const SelectArgs& a, const int* s_chan, const float* s_wgt,
+                                                 const TailPatch& tp, bf16_t old, float* out2) {
   const int tid = threadIdx.x;
   if (tp.page < 0 || tid >= 2 * kWave) return;
   float contrib = 0.f;
   if (tid < a.k1) {
     const float w = s_wgt[tid];
-    const int ch = s_chan[tid];
-    float f = bf16_to_f32(tp.knew[ch]);
+    float f = bf16_to_f32(tp.knew[s_chan[tid]]);
     if (tp.slot != 0) {
-      const float fo = bf16_to_f32(((w >= 0.f) ? a.kmax : a.kmin)[(rows + ch) * pages_cap + tp.page]);
+      const float fo = bf16_to_f32(old);
       f = (w >= 0.f) ? fmaxf(fo, f) : fminf(fo, f);
     }
     contrib = w * f;
@@ -123,13 +143,40 @@ __device__ __forceinline__ void hist_add_grouped(uint32_t* hist, uint32_t bin, b
   if (on) atomicAdd(&hist[bin], weight);
 }
 
+// The unit's q at channel `tid` for every head of the group (threads below 128), requested but not
+// used here: a caller can put its own loads behind these before anything waits, so that all of them
+// share one memory round trip.  Heads beyond the group re-read head 0 (and are ignored later); the
+// blocks of heads are skipped by branches that are the same for the whole workgroup.
+__device__ __forceinline__ void load_q_column(const CacheView& c, const SelectArgs& a, int unit,
+                                              uint32_t (&qv)[kMaxGroup]) {
+  const int tid = threadIdx.x;
+  const int b = unit / c.n_kv_heads, g = unit % c.n_kv_heads;
+  const int G = c.group;
+#pragma unroll
+  for (int h = 0; h < kMaxGroup; ++h) qv[h] = 0;
+  if (tid < kHeadDim) {
+    const bf16_t* qp = a.q + ((int64_t)b * c.n_q_heads + (int64_t)g * G) * kHeadDim + tid;
+#pragma unroll
+    for (int h = 0; h < 4; ++h) qv[h] = qp[(h < G ? h : 0) * kHeadDim];
+    if (G > 4) {
+#pragma unroll
+      for (int h = 4; h < 8; ++h) qv[h] = qp[(h < G ? h : 0) * kHeadDim];
+    }
+    if (G > 8) {
+#pragma unroll
+      for (int h = 8; h < kMaxGroup; ++h) qv[h] = qp[(h < G ? h : 0) * kHeadDim];
+    }
+  }
+}
+
 // Step 2, first half (needs only q): a = sum_h |q|, s = sum_h q, i1 = top-k1 channels of a, left in
-// sh.s_chan / sh.s_wgt.  All NT threads of the workgroup take part; ends with a barrier.
+// sh.s_chan / sh.s_wgt.  `qv` comes from load_q_column.  All NT threads of the workgroup take part;
+// ends with a barrier.
 template <int NT>
 __device__ __forceinline__ void select_channels(const CacheView& c, const SelectArgs& a, int unit,
-                                                SelectShared<NT>& sh, bool write_global) {
+                                                SelectShared<NT>& sh, bool write_global,
+                                                const uint32_t (&qv)[kMaxGroup]) {
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
-  const int b = unit / c.n_kv_heads, g = unit % c.n_kv_heads;
   const int G = c.group;
 
 #pragma unroll
@@ -138,17 +185,11 @@ __device__ __forceinline__ void select_channels(const CacheView& c, const Select
   // ---- a[c] = sum_h |q|, s[c] = sum_h q (fp32, head order) -----------------------------------
   if (tid < kHeadDim) {
     float sa = 0.f, ss = 0.f;
-    const bf16_t* qp = a.q + ((int64_t)b * c.n_q_heads + (int64_t)g * G) * kHeadDim + tid;
-    bf16_t qv[kMaxGroup];
-#pragma unroll
-    for (int h = 0; h < kMaxGroup; ++h) qv[h] = h < G ? qp[h * kHeadDim] : (bf16_t)0;
 #pragma unroll
     for (int h = 0; h < kMaxGroup; ++h) {
-      if (h < G) {
-        const float x = bf16_to_f32(qv[h]);
-        sa += fabsf(x);
-        ss += x;
-      }
+      const float x = h < G ? bf16_to_f32((bf16_t)qv[h]) : 0.f;
+      sa += fabsf(x);
+      ss += x;
     }
     sh.s_abs[tid] = sa;
     sh.s_sum[tid] = ss;
@@ -276,7 +317,8 @@ __device__ __forceinline__ int select_pages(const CacheView& c, const SelectArgs
   const int64_t rows = (int64_t)unit * kHeadDim;
   float* out_scores = write_global ? a.out_scores : nullptr;
   float* tail2 = sh.s_abs;  // free since the channel pick ended; [0..1]: the two halves of tp.page's score
-  tail_page_score<NT>(a, sh.s_chan, sh.s_wgt, rows, c.pages_cap, tp, tail2);
+  // the old bounds of tp.page: requested ahead of the row loads, used after them
+  const bf16_t tail_old = tail_page_load<NT>(a, sh.s_chan, sh.s_wgt, rows, c.pages_cap, tp);
   if (n_oct < NT) {
     int npow = 1;
     while (npow < n_oct) npow <<= 1;
@@ -286,8 +328,10 @@ __device__ __forceinline__ int select_pages(const CacheView& c, const SelectArgs
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i] = 0.f;
     if (o < n_oct)
-      for (int j0 = r; j0 < a.k1; j0 += 8 * R)
-        score_rows8(a, sh.s_chan, sh.s_wgt, rows, c.pages_cap, o, j0, R, acc);
+      for (int jb = 0; jb < a.k1; jb += 8 * R)
+        score_rows8(a, sh.s_chan, sh.s_wgt, rows, c.pages_cap, o, jb + r, jb, R, acc);
+    tail_page_finish<NT>(a, sh.s_chan, sh.s_wgt, tp, tail_old, tail2);
+    RKV_STAMP(2);
 #pragma unroll
     for (int i = 0; i < 8; ++i) sh.partial[(r * npow + o) * 8 + i] = acc[i];
     __syncthreads();
@@ -305,13 +349,14 @@ __device__ __forceinline__ int select_pages(const CacheView& c, const SelectArgs
       }
     }
   } else {
+    tail_page_finish<NT>(a, sh.s_chan, sh.s_wgt, tp, tail_old, tail2);
     __syncthreads();  // tail2 is read below
     for (int o = tid; o < n_oct; o += NT) {
       float acc[8];
 #pragma unroll
       for (int i = 0; i < 8; ++i) acc[i] = 0.f;
       for (int j0 = 0; j0 < a.k1; j0 += 8)
-        score_rows8(a, sh.s_chan, sh.s_wgt, rows, c.pages_cap, o, j0, 1, acc);
+        score_rows8(a, sh.s_chan, sh.s_wgt, rows, c.pages_cap, o, j0, j0, 1, acc);
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const int p = o * 8 + i;
@@ -329,8 +374,10 @@ __device__ __forceinline__ int select_pages(const CacheView& c, const SelectArgs
   __syncthreads();
 
   // ---- i2: exact kp-th largest key by 4 x 8-bit radix passes -------------------------------------
+  RKV_STAMP(3);
   uint32_t tau = 0, need_eq = (uint32_t)P;  // defaults select everything (kp == P)
   if (kp < P) radix_threshold<NT, true>(keys, P, kp, sh.hist, tau, need_eq);
+  RKV_STAMP(4);
 
   // ---- emit ascending: every key > tau, plus the first need_eq keys == tau -----------------------
   const int ipt = (P + NT - 1) / NT;
@@ -653,14 +700,17 @@ __device__ __forceinline__ void score_chunk(const CacheView& c, const SelectArgs
   float acc[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) acc[i] = 0.f;
-  // the page that is receiving a token, if it lies in this slice: scored on its own (see tail_page_score)
+  // the page that is receiving a token, if it lies in this slice: scored on its own (see tail_page_load)
   float* tail2 = sh.s_abs;  // free since the channel pick ended
   const int tail_local = tp.page >= 0 ? tp.page - o_begin * 8 : -1;
   const bool owns_tail = tail_local >= 0 && tail_local < n_runs * 8;  // same for the whole workgroup
-  if (owns_tail) tail_page_score<NT>(a, sh.s_chan, sh.s_wgt, rows, c.pages_cap, tp, tail2);
+  TailPatch mine = tp;
+  if (!owns_tail) mine.page = -1;
+  const bf16_t tail_old = tail_page_load<NT>(a, sh.s_chan, sh.s_wgt, rows, c.pages_cap, mine);
   if (o < n_runs)
-    for (int j0 = r; j0 < a.k1; j0 += 8 * R)  // each slice of the rows has this one reader: streamed
-      score_rows8<true>(a, sh.s_chan, sh.s_wgt, rows, c.pages_cap, o_begin + o, j0, R, acc);
+    for (int jb = 0; jb < a.k1; jb += 8 * R)  // each slice of the rows has this one reader: streamed
+      score_rows8<true>(a, sh.s_chan, sh.s_wgt, rows, c.pages_cap, o_begin + o, jb + r, jb, R, acc);
+  tail_page_finish<NT>(a, sh.s_chan, sh.s_wgt, mine, tail_old, tail2);
 #pragma unroll
   for (int i = 0; i < 8; ++i) sh.partial[(r * npow + o) * 8 + i] = acc[i];
   __syncthreads();
@@ -676,6 +726,7 @@ __device__ __forceinline__ void score_chunk(const CacheView& c, const SelectArgs
         scores_row[page] = s;
     }
   }
+  if (COHERENT) drain_stores();  // the scores are acknowledged before the barrier that the caller's report follows
   __syncthreads();
 }
 
@@ -684,7 +735,9 @@ template <int NT>
 __device__ __forceinline__ int select_block(const CacheView& c, const SelectArgs& a, int unit, int n,
                                             SelectShared<NT>& sh, uint32_t* keys, int32_t* list_lds,
                                             bool write_global, const TailPatch& tp) {
-  select_channels<NT>(c, a, unit, sh, write_global);
+  uint32_t qv[kMaxGroup];  // one bf16 each, kept in a register of its own (no packing, hence no early use)
+  load_q_column(c, a, unit, qv);
+  select_channels<NT>(c, a, unit, sh, write_global, qv);
   return select_pages<NT>(c, a, unit, n, sh, keys, list_lds, write_global, tp);
 }
 

@@ -4,7 +4,9 @@ Each case plants one plausible mistake in a COPY of the oracle's C source (a fli
 dropped term, a wrong index, a swapped operand ...), builds it beside the real one and runs the pin
 tests of ``test_oracle_pins.py`` against it in a child process.  The pins must fail.  A mistake that
 survives means a part of the oracle is tied to nothing but itself.  The real oracle is never touched:
-the copy lives in a temporary folder and is selected through ``ROCKETKV_ORACLE_LIB``.
+the copy lives in a temporary folder and is selected through ``ROCKETKV_ORACLE_LIB``, which the
+oracle's loader honours only together with ``ROCKETKV_ORACLE_MUTANT_RUN=1`` (set here and nowhere
+else), so no other environment can swap the checker under the GPU tests.
 """
 import os
 import subprocess
@@ -44,6 +46,21 @@ MUTANTS = [
     ("snapkv_pool_is_an_average", "if (gv[i] > mx) mx = gv[i];", "mx += gv[i] / (double)(hi - lo + 1);", 0),
     ("snapkv_window_not_kept", "kept[keep_prefix + w] = L + w;", "kept[keep_prefix + w] = w;", 0),
     ("snapkv_budget_excludes_the_window", "int keep_prefix = N - W;", "int keep_prefix = N - W - 1;", 0),
+    # the batch wrappers: offsets of a (sequence, KV head) unit, row strides, list termination
+    ("attend_given_query_offset_ignores_the_group", "okv_attend_pages(q + (u * G) * D, K + u * (size_t)n_cap * D, V + u * (size_t)n_cap * D,\n                       G, D, seq_lens[b], ps, pg, kp,",
+     "okv_attend_pages(q + u * D, K + u * (size_t)n_cap * D, V + u * (size_t)n_cap * D,\n                       G, D, seq_lens[b], ps, pg, kp,", 0),
+    ("attend_given_values_of_the_first_unit", "K + u * (size_t)n_cap * D, V + u * (size_t)n_cap * D,\n                       G, D, seq_lens[b], ps, pg, kp,",
+     "K + u * (size_t)n_cap * D, V,\n                       G, D, seq_lens[b], ps, pg, kp,", 0),
+    ("attend_given_list_row_stride", "const int* pg = pages + u * pages_cap;", "const int* pg = pages + u * (pages_cap - 1);", 0),
+    ("attend_given_walks_past_the_terminator", "while (kp < pages_cap && pg[kp] >= 0) ++kp;",
+     "while (kp < pages_cap && pg[kp] >= 0) ++kp;\n      while (kp < pages_cap && pg[kp] < 0) ++kp;\n      while (kp < pages_cap && pg[kp] >= 0) ++kp;", 0),
+    ("attend_given_length_of_the_first_sequence", "G, D, seq_lens[b], ps, pg, kp,", "G, D, seq_lens[0], ps, pg, kp,", 0),
+    ("build_summaries_column_stride", "kmax[(u * D + c) * pages_cap + p] = mx[(size_t)c * P + p];", "kmax[(u * D + c) * P + p] = mx[(size_t)c * P + p];", 0),
+    ("build_summaries_keys_of_the_first_unit", "okv_page_summaries(K + u * (size_t)n_cap * D, n, D, ps, mx, mn);", "okv_page_summaries(K, n, D, ps, mx, mn);", 0),
+    ("build_summaries_min_from_max", "kmin[(u * D + c) * pages_cap + p] = mn[(size_t)c * P + p];", "kmin[(u * D + c) * pages_cap + p] = mx[(size_t)c * P + p];", 0),
+    ("snapkv_batch_queries_of_the_first_group", "okv_snapkv_unit(qobs + u * G * (size_t)W * D,", "okv_snapkv_unit(qobs + (size_t)b * Hq * W * D,", 0),
+    ("snapkv_batch_key_stride", "K + u * (size_t)S_cap * D,\n                                G, W, D, S, ks, N,", "K + u * (size_t)S * D,\n                                G, W, D, S, ks, N,", 0),
+    ("snapkv_batch_length_of_the_first_sequence", "int S = seq_lens[b];\n      int* kp = kept + u * N;", "int S = seq_lens[0];\n      int* kp = kept + u * N;", 0),
 ]
 
 
@@ -64,7 +81,7 @@ def test_pins_notice_a_planted_mistake(tmp_path, name, old, new, which):
     c_file.write_text(mutated)
     subprocess.run(["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared", str(c_file), "-o", str(lib), "-lm"],
                    check=True)
-    env = dict(os.environ, ROCKETKV_ORACLE_LIB=str(lib))
+    env = dict(os.environ, ROCKETKV_ORACLE_LIB=str(lib), ROCKETKV_ORACLE_MUTANT_RUN="1")
     r = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_oracle_pins.py"), "-x", "-q",
                         "-p", "no:cacheprovider"], cwd=ROOT, env=env, capture_output=True, text=True, timeout=600)
     assert r.returncode == 1, f"the pins did not notice '{name}' (pytest exit {r.returncode}):\n" + r.stdout[-1500:]

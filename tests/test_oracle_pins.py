@@ -273,6 +273,104 @@ def test_planted_heavy_pages_are_recalled(oracle):
     assert np.abs(yd - r["y"]).max() < 1e-3
 
 
+# ---------------------------------------------------------------- batch wrappers
+def test_attend_given_batch_against_library(oracle):
+    """The batch re-evaluation of Step 3 on a supplied list (several sequences of different lengths,
+    several KV heads, a GQA group, rows cut short by -1) equals torch's fp64 softmax attention over
+    exactly the listed tokens of the right (sequence, KV head), head by head."""
+    rng = np.random.default_rng(101)
+    B, Hkv, G, D, ps, ncap, cap = 3, 2, 4, 16, 4, 40, 6
+    lens = [37, 18, 40]
+    q = rand_bits(rng, (B, Hkv * G, D))
+    K = rand_bits(rng, (B, Hkv, ncap, D))
+    V = rand_bits(rng, (B, Hkv, ncap, D))
+    pages = np.full((B, Hkv, cap), -1, dtype=np.int32)
+    rows = {(0, 0): [0, 3, 9], (0, 1): [1, 2, 4, 8, 9], (1, 0): [4], (1, 1): [0, 2, 3, 4],
+            (2, 0): [], (2, 1): [0, 1, 5, 6, 7, 9]}  # page 9 of 37 tokens / page 4 of 18 are partial tails
+    for (b, g), r in rows.items():
+        pages[b, g, :len(r)] = r
+    # what follows a -1 must be ignored, whatever it holds
+    pages[1, 0, 2] = 1
+    y, lse = oracle.attend_given(q, K, V, lens, ps, pages)
+    for (b, g), r in rows.items():
+        tok = [j for p_ in r for j in range(p_ * ps, min((p_ + 1) * ps, lens[b]))]
+        sl = slice(g * G, (g + 1) * G)
+        if not tok:
+            assert (y[b, sl] == 0).all() and np.isneginf(lse[b, sl]).all()
+            continue
+        want_y, want_lse = torch_dense(q[b:b + 1, sl], K[b, g][tok][None, None], V[b, g][tok][None, None], [len(tok)])
+        np.testing.assert_allclose(y[b, sl], want_y[0], rtol=1e-12, atol=1e-12)
+        np.testing.assert_allclose(lse[b, sl], want_lse[0], rtol=1e-12, atol=1e-12)
+
+
+def test_attend_given_on_the_full_list_is_dense_and_on_the_picked_list_is_hsa(oracle):
+    """Two fixed points of the wrapper: the list of every page gives full attention (torch), and the
+    list Algorithm 1 picked gives Algorithm 1's own y."""
+    rng = np.random.default_rng(103)
+    B, Hkv, G, D, ps, ncap = 2, 2, 4, 16, 8, 64
+    lens = [64, 41]
+    q = rand_bits(rng, (B, Hkv * G, D))
+    K = rand_bits(rng, (B, Hkv, ncap, D))
+    V = rand_bits(rng, (B, Hkv, ncap, D))
+    every = np.full((B, Hkv, ncap // ps), -1, dtype=np.int32)
+    for b, n in enumerate(lens):
+        P = (n + ps - 1) // ps
+        every[b, :, :P] = np.arange(P)
+    y, lse = oracle.attend_given(q, K, V, lens, ps, every)
+    want_y, want_lse = torch_dense(q, K, V, lens)
+    np.testing.assert_allclose(y, want_y, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(lse, want_lse, rtol=1e-12, atol=1e-12)
+    r = oracle.hsa_decode(q, K, V, lens, ps=ps, k1=6, T=24)
+    y2, lse2 = oracle.attend_given(q, K, V, lens, ps, r["pages"])
+    np.testing.assert_array_equal(y2, r["y"])
+    np.testing.assert_array_equal(lse2, r["lse"])
+
+
+def test_build_summaries_batch_against_numpy(oracle):
+    """Batch Step 1 into rows of pages_cap > P columns: every written column is numpy's max / min over
+    the page's valid tokens of the right (sequence, KV head); columns at and beyond P stay untouched."""
+    rng = np.random.default_rng(107)
+    B, Hkv, D, ps, ncap, cap = 3, 2, 8, 4, 30, 12
+    lens = [30, 9, 0]
+    K = rand_bits(rng, (B, Hkv, ncap, D))
+    kmax, kmin = oracle.build_summaries(K, lens, ps, pages_cap=cap)
+    Kf = wl.bf16_bits_to_f64(K)
+    for b, n in enumerate(lens):
+        P = (n + ps - 1) // ps
+        for g in range(Hkv):
+            for p_ in range(P):
+                blk = Kf[b, g, p_ * ps:min((p_ + 1) * ps, n)]  # [tokens][D]
+                np.testing.assert_array_equal(kmax[b, g, :, p_], blk.max(axis=0))
+                np.testing.assert_array_equal(kmin[b, g, :, p_], blk.min(axis=0))
+            assert np.isnan(kmax[b, g, :, P:]).all() and np.isnan(kmin[b, g, :, P:]).all()
+
+
+def test_snapkv_batch_ragged_against_library(oracle):
+    """Batch Stage 1 with several sequences of different lengths (one short enough to be kept whole),
+    two KV heads and a GQA group: each (sequence, KV head) equals the torch rebuild on its own slices
+    (Section 3.3: window-summed, group-summed causal softmax, max-pool, top-(N-W) plus the window)."""
+    rng = np.random.default_rng(109)
+    B, Hkv, G, W, D, Scap, N, ks = 3, 2, 2, 4, 16, 70, 20, 5
+    lens = [70, 18, 43]
+    qobs = rand_bits(rng, (B, Hkv * G, W, D), scale=2.0)
+    K = rand_bits(rng, (B, Hkv, Scap, D), scale=2.0)
+    r = oracle.snapkv(qobs, K, lens, ks=ks, N=N, want_votes=True)
+    assert r["n_kept"].tolist() == [N, 18, N]
+    for b, S in enumerate(lens):
+        for g in range(Hkv):
+            if S <= N:
+                assert r["kept"][b, g, :S].tolist() == list(range(S)) and (r["kept"][b, g, S:] == -1).all()
+                continue
+            L = S - W
+            probs = torch_window_probs(qobs[b, g * G:(g + 1) * G], K[b, g], S, W)
+            gv = probs[:, :, :L].sum(dim=(0, 1))
+            np.testing.assert_allclose(r["gv"][b, g, :L], gv.numpy(), rtol=1e-11, atol=1e-14)
+            gv_o = torch.from_numpy(r["gv"][b, g, :L].copy())
+            pooled = torch.nn.functional.max_pool1d(gv_o[None, None], ks, stride=1, padding=ks // 2)[0, 0]
+            np.testing.assert_array_equal(r["pooled"][b, g, :L], pooled.numpy())
+            assert r["kept"][b, g].tolist() == brute_topk(r["pooled"][b, g, :L].tolist(), N - W) + list(range(L, S))
+
+
 # ---------------------------------------------------------------- SnapKV
 def torch_window_probs(qobs, K, S, W):
     """Causal softmax rows of the last W positions, torch fp64.  qobs: [H][W][D], K: [S][D]."""
