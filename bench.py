@@ -49,7 +49,6 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--kernel-reps", type=int, default=20)
-    ap.add_argument("--tune", type=str, default="", help="waves,pairs_per_wave override of the attention split")
     ap.add_argument("--no-decomposed", action="store_true",
                     help="skip the secondary measurement at the operating point of the adaptive decomposition")
     ap.add_argument("--q-variants", type=int, default=4,
@@ -75,9 +74,6 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
     rk.lib()
-    if args.tune:
-        wv, ppw = (int(x) for x in args.tune.split(","))
-        rk.tune_attend(wv, ppw, 0)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 

@@ -342,16 +342,6 @@ int32_t rocketkv_decompose(int64_t seq_len, int32_t token_budget, int32_t head_d
                            rocketkv_split_t* out);
 
 /*
- * Tuning hook for experiments with the attention launch geometry: wavefronts per workgroup (4 or 8;
- * negative = back to the default, which picks 8 up to 256 (sequence, KV head) units and 4 beyond),
- * page pairs a wavefront aims to own, and the cap on workgroups per launch; 0 keeps a value.
- * Process-wide, not thread-safe, affects later calls (and the workspace sizes they need, so query
- * rocketkv_workspace_bytes again after changing it).  The defaults (automatic, 2, 2048) are what the
- * benchmark and the tests run with.
- */
-void rocketkv_tune_attend(int32_t waves, int32_t pairs_per_wave, int32_t max_wgs);
-
-/*
  * Measurement aid (no step of the method): read `bytes` (a multiple of 16) of device memory at
  * `src` (16-byte aligned) once, front to back, with plain streaming loads, and write one checksum
  * word per wavefront to `sink` (device, at least rocketkv_stream_read_sink_bytes() bytes).  Timed

@@ -7,10 +7,6 @@
 
 #include "common.h"
 
-namespace rkv {
-void tune_attend(int waves, int pairs_per_wave, int max_wgs);
-}
-
 using namespace rkv;
 
 namespace {
@@ -125,11 +121,12 @@ int check_attend_shape(const rocketkv_cache_t* c, const char* who) {
 
 // Launch geometry of Step 3 over `row_len` list entries.  The plan counts 16-token entries; a
 // token-major cache of another page size is planned on the token slots its entries add up to.
-AttendPlan attend_plan_for(const CacheView& v, int row_len) {
-  if (!v.v_token_major) return plan_attend(v, row_len);
+// `gather`: a page list drives the launch (false: the identity list of the Full-KV baseline).
+AttendPlan attend_plan_for(const CacheView& v, int row_len, bool gather) {
+  if (!v.v_token_major) return plan_attend(v, row_len, gather);
   // whole entries only: the kernel's last wavefront absorbs a remainder of fewer than 16 slots
   const int64_t slots = (int64_t)row_len * v.page_size;
-  return plan_attend(v, slots >= kAttnPage ? (int)(slots / kAttnPage) : 1);
+  return plan_attend(v, slots >= kAttnPage ? (int)(slots / kAttnPage) : 1, gather);
 }
 
 hipError_t launch_attend_any(const CacheView& v, const bf16_t* q, const int32_t* pages, int row_len,
@@ -170,7 +167,7 @@ DecodePlan plan_decode(const rocketkv_cache_t* c, int T) {
   DecodePlan d;
   const CacheView v = view_of(c);
   d.row_len = list_len_for_budget(c, T);
-  d.attend = attend_plan_for(v, d.row_len);
+  d.attend = attend_plan_for(v, d.row_len, true);
   size_t off = 0;
   d.attend_off = off;  // first, so that the counters sit in the header workspace_init clears
   off += d.attend.total_bytes;
@@ -190,10 +187,6 @@ const char* rocketkv_last_error(void) { return g_err; }
 
 int32_t rocketkv_version(void) { return 100; }
 
-void rocketkv_tune_attend(int32_t waves, int32_t pairs_per_wave, int32_t max_wgs) {
-  tune_attend(waves, pairs_per_wave, max_wgs);
-}
-
 size_t rocketkv_workspace_bytes(int32_t op, const rocketkv_cache_t* cache, int32_t a, int32_t b) {
   g_err[0] = 0;
   if (check_cache(cache, false, "rocketkv_workspace_bytes")) return 0;
@@ -203,10 +196,10 @@ size_t rocketkv_workspace_bytes(int32_t op, const rocketkv_cache_t* cache, int32
       if (a < 1) { fail(ROCKETKV_INVALID_ARG, "rocketkv_workspace_bytes: token_budget must be >= 1"); return 0; }
       return plan_decode(cache, a).total;
     case ROCKETKV_OP_DENSE_DECODE:
-      return attend_plan_for(v, cache->pages_cap).total_bytes;
+      return attend_plan_for(v, cache->pages_cap, false).total_bytes;
     case ROCKETKV_OP_ATTEND:
       if (a < 0) { fail(ROCKETKV_INVALID_ARG, "rocketkv_workspace_bytes: pages_row_len must be >= 0"); return 0; }
-      return attend_plan_for(v, a > 0 ? a : cache->pages_cap).total_bytes;
+      return attend_plan_for(v, a > 0 ? a : cache->pages_cap, a > 0).total_bytes;
     case ROCKETKV_OP_SNAPKV:
       if (a < 1 || b <= a) { fail(ROCKETKV_INVALID_ARG, "rocketkv_workspace_bytes: need 1 <= window < keep_budget"); return 0; }
       return plan_snapkv(v, a, b).total_bytes;
@@ -285,7 +278,7 @@ int32_t rocketkv_attend(const rocketkv_cache_t* cache, const void* q, const int3
   if (pages && pages_row_len < 1) return fail(ROCKETKV_INVALID_ARG, "%s: pages_row_len must be >= 1", who);
   const int row_len = pages ? pages_row_len : cache->pages_cap;
   const CacheView v = view_of(cache);
-  const AttendPlan plan = attend_plan_for(v, row_len);
+  const AttendPlan plan = attend_plan_for(v, row_len, pages != nullptr);
   if (plan.total_bytes && (!workspace || workspace_bytes < plan.total_bytes))
     return fail(ROCKETKV_WORKSPACE_TOO_SMALL, "%s: workspace %zu bytes < %zu needed", who,
                 workspace ? workspace_bytes : (size_t)0, plan.total_bytes);

@@ -68,9 +68,10 @@ struct AttendArgs {
   int row_len;           // entries per unit in `pages` (or pages_cap for identity)
   bf16_t* out;
   float* out_lse;
-  float* partial;        // [units][n_split][G][kPartialStride]
-  uint32_t* counters;    // [units]
+  float* partial;        // [units][n_csplit][n_split][G][kPartialStride]
+  uint32_t* counters;    // [units][n_csplit]
   int n_split, chunk, per_wave;
+  int n_csplit;          // workgroups a unit's output channels are divided between (1 or 2)
 };
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -96,9 +97,9 @@ __device__ __forceinline__ float ld_agent(const float* p) {
 // logits S[token][head] (masked entries -inf), `vf` the V operand (lane: channel cb*16+hn, tokens
 // 4kg..4kg+3 of each page).  One max / rescale per round, the logit scale folded into the exponent's
 // FMA, hardware bf16 packing.
-template <int NP>
-__device__ __forceinline__ void softmax_pv(f32x4 (&acc)[NP][2], u32x2 (&vf)[NP][2][8],
-                                           f32x4 (&O)[8], float& m, float& l, bool have_acc, float sc) {
+template <int NP, int CB>
+__device__ __forceinline__ void softmax_pv(f32x4 (&acc)[NP][2], u32x2 (&vf)[NP][2][CB],
+                                           f32x4 (&O)[CB], float& m, float& l, bool have_acc, float sc) {
   float mx = -INFINITY;
 #pragma unroll
   for (int u = 0; u < NP; ++u)
@@ -113,7 +114,7 @@ __device__ __forceinline__ void softmax_pv(f32x4 (&acc)[NP][2], u32x2 (&vf)[NP][
     l *= alpha;
     if (__any(alpha != 1.f)) {
 #pragma unroll
-      for (int cb = 0; cb < 8; ++cb) O[cb] *= alpha;
+      for (int cb = 0; cb < CB; ++cb) O[cb] *= alpha;
     }
   }
   m = m_new;
@@ -136,7 +137,7 @@ __device__ __forceinline__ void softmax_pv(f32x4 (&acc)[NP][2], u32x2 (&vf)[NP][
 #pragma unroll
   for (int u = 0; u < NP; ++u)
 #pragma unroll
-    for (int cb = 0; cb < 8; ++cb) {
+    for (int cb = 0; cb < CB; ++cb) {
       const u32x4 vv = {vf[u][0][cb].x, vf[u][0][cb].y, vf[u][1][cb].x, vf[u][1][cb].y};
       O[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vv), as_bf16x8(pf[u]), O[cb], 0, 0, 0);
     }
@@ -147,11 +148,12 @@ __device__ __forceinline__ void softmax_pv(f32x4 (&acc)[NP][2], u32x2 (&vf)[NP][
 // this step is built around: one max / rescale per round instead of per page, the logit scale folded
 // into the exponent's FMA, hardware bf16 packing, and the per-token masks compiled only into the
 // MASK variant, which a round takes when it holds an absent page or the sequence's partial tail page.
-template <int NP, bool MASK>
-__device__ __forceinline__ void softmax_round(u32x4 (&kf)[NP][2][4], u32x2 (&vf)[NP][2][8],
+// `cs`: which share of the output channels this workgroup computes (channel blocks cs*CB .. cs*CB+CB-1).
+template <int NP, bool MASK, int CB>
+__device__ __forceinline__ void softmax_round(u32x4 (&kf)[NP][2][4], u32x2 (&vf)[NP][2][CB],
                                               const int (&ids)[NP][2], const u32x4 (&qf)[4],
-                                              f32x4 (&O)[8], float& m, float& l, bool have_acc, int n,
-                                              int hn, int kg, float sc, const TailPatch& tp) {
+                                              f32x4 (&O)[CB], float& m, float& l, bool have_acc, int n,
+                                              int hn, int kg, float sc, const TailPatch& tp, int cs) {
   if (MASK && tp.page >= 0) {
     // the page receiving a token in this launch: take that token's key row and value column from the
     // staged copies rather than from memory
@@ -167,8 +169,8 @@ __device__ __forceinline__ void softmax_round(u32x4 (&kf)[NP][2][4], u32x2 (&vf)
           if (kg == (tp.slot >> 2)) {
             const int e = tp.slot & 3;
 #pragma unroll
-            for (int cb = 0; cb < 8; ++cb) {
-              const uint32_t val = tp.vnew[cb * 16 + hn];
+            for (int cb = 0; cb < CB; ++cb) {
+              const uint32_t val = tp.vnew[(cs * CB + cb) * 16 + hn];
               uint32_t w0 = vf[u][x][cb].x, w1 = vf[u][x][cb].y;
               if (e == 0) w0 = (w0 & 0xffff0000u) | val;
               if (e == 1) w0 = (w0 & 0x0000ffffu) | (val << 16);
@@ -204,7 +206,7 @@ __device__ __forceinline__ void softmax_round(u32x4 (&kf)[NP][2][4], u32x2 (&vf)
         // what lies in an absent page, or beyond the sequence end in the tail page, may be anything:
         // its probability is zero, but 0 x NaN is not, so it is cleared out of the V operand too
 #pragma unroll
-        for (int cb = 0; cb < 8; ++cb) {
+        for (int cb = 0; cb < CB; ++cb) {
           uint32_t w0 = vf[u][x][cb].x, w1 = vf[u][x][cb].y;
           if (gone || tok0 + 0 >= n) w0 &= 0xffff0000u;
           if (gone || tok0 + 1 >= n) w0 &= 0x0000ffffu;
@@ -214,30 +216,32 @@ __device__ __forceinline__ void softmax_round(u32x4 (&kf)[NP][2][4], u32x2 (&vf)
         }
       }
   }
-  softmax_pv<NP>(acc, vf, O, m, l, have_acc, sc);
+  softmax_pv<NP, CB>(acc, vf, O, m, l, have_acc, sc);
 }
 
-// Merges of one workgroup's result: the wavefronts' (O, max, sum) through LDS, then, when the unit is
-// split over several workgroups, the hand-over of the partial and the last arriver's merge of all of
-// them.  `O`, `m`, `l` are the lane's online-softmax state with `l` already summed over the four
-// token groups; `smem` holds WAVES*G*130 floats, `s_last` one int.
-template <int WAVES>
-__device__ __forceinline__ void attend_merge(const CacheView& c, const AttendArgs& a, int unit, int split,
-                                             const f32x4 (&O)[8], float m, float l, float* smem,
+// Merges of one workgroup's result: the wavefronts' (O, max, sum) through LDS, then, when the unit's
+// list is split over several workgroups, the hand-over of the partial and the last arriver's merge of
+// all of them.  `O`, `m`, `l` are the lane's online-softmax state with `l` already summed over the four
+// token groups; `smem` holds WAVES*G*(CB*16+2) floats, `s_last` one int.  The workgroup owns output
+// channels cs*CB*16 .. +CB*16-1 of the unit; workgroups with different `cs` never meet.
+template <int WAVES, int CB = 8>
+__device__ __forceinline__ void attend_merge(const CacheView& c, const AttendArgs& a, int unit, int split, int cs,
+                                             const f32x4 (&O)[CB], float m, float l, float* smem,
                                              int* s_last, int b, int g) {
   constexpr int kThreads = WAVES * kWave;
+  constexpr int CW = CB * 16;  // output channels of this workgroup
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
   const int hn = lane % 16, kg = lane / 16;
   const int G = c.group;
   float* sO = smem;
-  float* sM = smem + WAVES * G * kHeadDim;
+  float* sM = smem + WAVES * G * CW;
   float* sL = sM + WAVES * G;
 
   // ---- merge the waves through LDS ---------------------------------------------------------------
   if (hn < G) {
 #pragma unroll
-    for (int cb = 0; cb < 8; ++cb)
-      *reinterpret_cast<float4*>(&sO[(wave * G + hn) * kHeadDim + cb * 16 + kg * 4]) =
+    for (int cb = 0; cb < CB; ++cb)
+      *reinterpret_cast<float4*>(&sO[(wave * G + hn) * CW + cb * 16 + kg * 4]) =
           make_float4(O[cb][0], O[cb][1], O[cb][2], O[cb][3]);
     if (kg == 0) {
       sM[wave * G + hn] = m;
@@ -246,9 +250,10 @@ __device__ __forceinline__ void attend_merge(const CacheView& c, const AttendArg
   }
   __syncthreads();
   RKV_STAMP(8);
-  const int64_t out_base = ((int64_t)b * c.n_q_heads + (int64_t)g * G) * kHeadDim;
-  for (int idx = tid; idx < G * kHeadDim; idx += kThreads) {
-    const int h = idx / kHeadDim, ch = idx % kHeadDim;
+  const int64_t out_base = ((int64_t)b * c.n_q_heads + (int64_t)g * G) * kHeadDim + cs * CW;
+  const int64_t group = (int64_t)unit * a.n_csplit + cs;  // the workgroups that merge with each other
+  for (int idx = tid; idx < G * CW; idx += kThreads) {
+    const int h = idx / CW, ch = idx % CW;
     float M = sM[h];
 #pragma unroll
     for (int w = 1; w < WAVES; ++w) M = fmaxf(M, sM[w * G + h]);
@@ -256,16 +261,16 @@ __device__ __forceinline__ void attend_merge(const CacheView& c, const AttendArg
 #pragma unroll
     for (int w = 0; w < WAVES; ++w) {
       const float f = fast_exp2(sM[w * G + h] - M);
-      num += f * sO[(w * G + h) * kHeadDim + ch];
+      num += f * sO[(w * G + h) * CW + ch];
       den += f * sL[w * G + h];
     }
     if (a.n_split == 1) {
-      a.out[out_base + idx] = f32_to_bf16(den > 0.f ? num / den : 0.f);
-      if (ch == 0 && a.out_lse)
+      a.out[out_base + h * kHeadDim + ch] = f32_to_bf16(den > 0.f ? num / den : 0.f);
+      if (ch == 0 && cs == 0 && a.out_lse)
         a.out_lse[(int64_t)b * c.n_q_heads + g * G + h] = den > 0.f ? (M + log2f(den)) * kLn2 : -INFINITY;
     } else {
       // write-through stores: visible device-wide once acknowledged, no cache flush needed
-      float* pr = a.partial + (((int64_t)unit * a.n_split + split) * G + h) * kPartialStride;
+      float* pr = a.partial + ((group * a.n_split + split) * G + h) * kPartialStride;
       st_agent(pr + ch, num);
       if (ch == 0) {
         st_agent(pr + kHeadDim, M);
@@ -275,21 +280,21 @@ __device__ __forceinline__ void attend_merge(const CacheView& c, const AttendArg
   }
   if (a.n_split == 1) return;
 
-  // ---- last workgroup of the unit merges the split partials --------------------------------------
+  // ---- last workgroup of the group merges the split partials -------------------------------------
   RKV_STAMP(9);
   drain_stores();   // this thread's partials (and whatever else it stored) have been acknowledged ...
   __syncthreads();  // ... and so have every other thread's, before thread 0 reports
   if (tid == 0) {
-    const uint32_t old = __hip_atomic_fetch_add(&a.counters[unit], 1u, __ATOMIC_RELAXED,
+    const uint32_t old = __hip_atomic_fetch_add(&a.counters[group], 1u, __ATOMIC_RELAXED,
                                                 __HIP_MEMORY_SCOPE_AGENT);
     *s_last = (old == (uint32_t)a.n_split - 1u);
   }
   __syncthreads();
   RKV_STAMP(10);
   if (!*s_last) return;
-  for (int idx = tid; idx < G * kHeadDim; idx += kThreads) {
-    const int h = idx / kHeadDim, ch = idx % kHeadDim;
-    const float* pr = a.partial + ((int64_t)unit * a.n_split * G + h) * kPartialStride;
+  for (int idx = tid; idx < G * CW; idx += kThreads) {
+    const int h = idx / CW, ch = idx % CW;
+    const float* pr = a.partial + (group * a.n_split * G + h) * kPartialStride;
     const int64_t sstride = (int64_t)G * kPartialStride;
     float M = kNegBig, num = 0.f, den = 0.f;
     // eight splits per batch, every load of a batch in flight before the first use
@@ -318,11 +323,11 @@ __device__ __forceinline__ void attend_merge(const CacheView& c, const AttendArg
       }
       M = Mb;
     }
-    a.out[out_base + idx] = f32_to_bf16(den > 0.f ? num / den : 0.f);
-    if (ch == 0 && a.out_lse)
+    a.out[out_base + h * kHeadDim + ch] = f32_to_bf16(den > 0.f ? num / den : 0.f);
+    if (ch == 0 && cs == 0 && a.out_lse)
       a.out_lse[(int64_t)b * c.n_q_heads + g * G + h] = den > 0.f ? (M + log2f(den)) * kLn2 : -INFINITY;
   }
-  if (tid == 0) __hip_atomic_store(&a.counters[unit], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (tid == 0) __hip_atomic_store(&a.counters[group], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   RKV_STAMP(11);
 }
 
@@ -335,10 +340,22 @@ struct NoHook {
 
 // `after_stream` runs once per thread after the last K/V tile has been consumed and before the
 // merges: a place for stores whose latency should hide under the merge.
-template <int WAVES, int NP, bool STREAM_K, typename Hook = NoHook>
-__device__ __forceinline__ void attend_block(const CacheView& c, const AttendArgs& a, int unit, int split,
+//
+// CB < 8: the unit's output channels are divided between 8 / CB workgroups (`cs` says which share is
+// this one's) instead of, or on top of, its page list.  Each of them reads every K tile of its pages
+// (the second reader of a tile finds it in the L2 of the XCD the unit's workgroups share, which is why
+// those loads are plain ones), forms the same logits and softmax weights, and takes only its own
+// channel blocks of the V tiles: the same HBM bytes, but workgroups that never have to meet, so a
+// unit split two ways needs no hand-over of partials through memory at all.
+//
+// `last_round` runs once per thread right after the loads of its last round have been requested (or
+// before `after_stream` if it has no round at all): a place for a memory operation whose answer
+// should travel with those loads instead of being waited for on its own.
+template <int WAVES, int NP, bool STREAM_K, int CB = 8, typename Hook = NoHook, typename Hook2 = NoHook>
+__device__ __forceinline__ void attend_block(const CacheView& c, const AttendArgs& a, int unit, int split, int cs,
                                              int n, const int32_t* list, float* smem, int* s_last,
-                                             const TailPatch& tp, const Hook& after_stream = Hook()) {
+                                             const TailPatch& tp, const Hook& after_stream = Hook(),
+                                             const Hook2& last_round = Hook2()) {
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
   const int hn = lane % 16, kg = lane / 16;
   const int b = unit / c.n_kv_heads, g = unit % c.n_kv_heads;
@@ -367,15 +384,15 @@ __device__ __forceinline__ void attend_block(const CacheView& c, const AttendArg
     }
   }
 
-  f32x4 O[8];
+  f32x4 O[CB];
 #pragma unroll
-  for (int cb = 0; cb < 8; ++cb) O[cb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  for (int cb = 0; cb < CB; ++cb) O[cb] = (f32x4){0.f, 0.f, 0.f, 0.f};
   float m = kNegBig, l = 0.f;
   bool have_acc = false;
   const float sc = kLog2e * 0.08838834764831845f;  // log2(e) / sqrt(128)
   // lane-dependent part of every tile address
   const bf16_t* k_lane = c.k_pool + (int64_t)g * c.stride_head + hn * kHeadDim + kg * 8;
-  const bf16_t* v_lane = c.v_pool + (int64_t)g * c.stride_head + hn * kAttnPage + kg * 4;
+  const bf16_t* v_lane = c.v_pool + (int64_t)g * c.stride_head + (cs * CB * 16 + hn) * kAttnPage + kg * 4;
 
   for (int base = wb; base < we; base += kWave) {
     if (base != wb) {
@@ -397,7 +414,7 @@ __device__ __forceinline__ void attend_block(const CacheView& c, const AttendArg
     // registers; the other wavefronts of the SIMD cover the gap.
     for (int i = 0; i < npairs; i += NP) {
       u32x4 kf[NP][2][4];
-      u32x2 vf[NP][2][8];
+      u32x2 vf[NP][2][CB];
       int ids[NP][2];
       const bf16_t* vt[NP][2];
       const int e0 = __builtin_amdgcn_readfirstlane(2 * i);
@@ -420,13 +437,14 @@ __device__ __forceinline__ void attend_block(const CacheView& c, const AttendArg
 #pragma unroll
         for (int x = 0; x < 2; ++x)
 #pragma unroll
-          for (int cb = 0; cb < 8; ++cb)
+          for (int cb = 0; cb < CB; ++cb)
             vf[u][x][cb] = ld_stream<u32x2>(vt[u][x] + cb * 16 * kAttnPage);
+      if (base + kWave >= we && i + NP >= npairs) last_round();
       const bool masked = ((special >> e0) & ((1ull << (2 * NP)) - 1ull)) != 0ull || e0 + 2 * NP > kWave;
       if (!masked)
-        softmax_round<NP, false>(kf, vf, ids, qf, O, m, l, have_acc, n, hn, kg, sc, tp);
+        softmax_round<NP, false, CB>(kf, vf, ids, qf, O, m, l, have_acc, n, hn, kg, sc, tp, cs);
       else
-        softmax_round<NP, true>(kf, vf, ids, qf, O, m, l, have_acc, n, hn, kg, sc, tp);
+        softmax_round<NP, true, CB>(kf, vf, ids, qf, O, m, l, have_acc, n, hn, kg, sc, tp, cs);
       if (!have_acc) RKV_STAMP(6);
       have_acc = true;
     }
@@ -434,8 +452,9 @@ __device__ __forceinline__ void attend_block(const CacheView& c, const AttendArg
   l += __shfl_xor(l, 16);
   l += __shfl_xor(l, 32);
   RKV_STAMP(7);
+  if (wb >= we) last_round();
   after_stream();
-  attend_merge<WAVES>(c, a, unit, split, O, m, l, smem, s_last, b, g);
+  attend_merge<WAVES, CB>(c, a, unit, split, cs, O, m, l, smem, s_last, b, g);
 }
 
 }  // namespace rkv

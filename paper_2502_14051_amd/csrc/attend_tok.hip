@@ -33,6 +33,7 @@ hipError_t launch_attend_tokens(const CacheView& c, const bf16_t* q, const int32
   a.n_split = plan.n_split;
   a.chunk = plan.chunk * kAttnPage;        // the plan counts 16-token entries
   a.per_wave = plan.per_wave * kAttnPage;  // even number of entries: a multiple of 32 slots
+  a.n_csplit = 1;
   TokenRun t;
   t.ps = lv ? lv->page_size : c.page_size;
   t.tokens = row_len * t.ps;

@@ -244,7 +244,7 @@ __device__ __forceinline__ void attend_tokens_block(const CacheView& c, const At
   l += __shfl_xor(l, 16);
   l += __shfl_xor(l, 32);
   after_stream();
-  attend_merge<WAVES>(c, a, unit, split, O, m, l, smem, s_last, b, g);
+  attend_merge<WAVES, 8>(c, a, unit, split, 0, O, m, l, smem, s_last, b, g);
 }
 
 }  // namespace rkv

@@ -68,6 +68,23 @@ static __device__ unsigned long long g_stamps[kStampSlots * 2 * kStampWaves * kS
 #define RKV_STAMP(k) do { } while (0)
 #endif
 
+// A zero the compiler cannot see through.  Added to an index whose value is the same for the whole
+// workgroup, it keeps the load a vector load issued where the source says, beside the other vector
+// loads of a phase (as a scalar load it may be issued, and waited for, only after them).
+__device__ __forceinline__ int opaque_zero() {
+  int z;
+  asm volatile("v_mov_b32 %0, 0" : "=v"(z));
+  return z;
+}
+
+// A loaded value that is not needed until much later: calling this where the value is first used keeps
+// the compiler from deriving anything from it (and hence from waiting for the load) any earlier, so the
+// load's latency hides under whatever lies between.
+__device__ __forceinline__ uint32_t use_late(uint32_t v) {
+  asm volatile("" : "+v"(v));
+  return v;
+}
+
 // Inclusive prefix sum over the 64 lanes of a wavefront with data-parallel-primitive moves (four
 // shifts inside each row of 16 lanes, then two row broadcasts): six adds and no LDS round trips.
 __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t x) {
@@ -78,6 +95,33 @@ __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t x) {
   x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x142, 0xa, 0xf, false);  // row_bcast:15 -> rows 1,3
   x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x143, 0xc, 0xf, false);  // row_bcast:31 -> rows 2,3
   return x;
+}
+
+// Minimum / maximum over the 64 lanes of a wavefront with the same lane moves (a lane that has no
+// source keeps its own value); every lane gets the result.
+__device__ __forceinline__ float wave_min_f32(float x) {
+#define RKV_DPP_MIN(ctrl, rows) \
+  x = fminf(x, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(x), __float_as_int(x), ctrl, rows, 0xf, false)))
+  RKV_DPP_MIN(0x111, 0xf);
+  RKV_DPP_MIN(0x112, 0xf);
+  RKV_DPP_MIN(0x114, 0xf);
+  RKV_DPP_MIN(0x118, 0xf);
+  RKV_DPP_MIN(0x142, 0xa);
+  RKV_DPP_MIN(0x143, 0xc);
+#undef RKV_DPP_MIN
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), kWave - 1));
+}
+__device__ __forceinline__ float wave_max_f32(float x) {
+#define RKV_DPP_MAX(ctrl, rows) \
+  x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(x), __float_as_int(x), ctrl, rows, 0xf, false)))
+  RKV_DPP_MAX(0x111, 0xf);
+  RKV_DPP_MAX(0x112, 0xf);
+  RKV_DPP_MAX(0x114, 0xf);
+  RKV_DPP_MAX(0x118, 0xf);
+  RKV_DPP_MAX(0x142, 0xa);
+  RKV_DPP_MAX(0x143, 0xc);
+#undef RKV_DPP_MAX
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), kWave - 1));
 }
 
 // Device view of a cache (copied by value into kernel arguments).
@@ -96,6 +140,17 @@ struct CacheView {
 __device__ __forceinline__ int64_t phys_page(const CacheView& c, int b, int p) {
   int64_t pp = c.block_table ? (int64_t)c.block_table[(int64_t)b * c.pages_cap + p]
                              : (int64_t)b * c.pages_cap + p;
+  return (pp >= 0 && pp < c.n_phys_pages) ? pp : -1;
+}
+
+// The same lookup in two parts, for a caller that needs the answer much later: phys_page_request
+// returns what the block table holds (or the identity mapping) without looking at it, so nothing waits
+// for the load; phys_page_resolve turns it into the page or -1.
+__device__ __forceinline__ int32_t phys_page_request(const CacheView& c, int b, int p) {
+  return c.block_table ? c.block_table[(int64_t)b * c.pages_cap + p] : b * c.pages_cap + p;
+}
+__device__ __forceinline__ int64_t phys_page_resolve(const CacheView& c, int32_t raw) {
+  const int64_t pp = (int32_t)use_late((uint32_t)raw);
   return (pp >= 0 && pp < c.n_phys_pages) ? pp : -1;
 }
 
@@ -150,14 +205,15 @@ hipError_t launch_hsa_select(const CacheView& c, const SelectArgs& a, hipStream_
 
 struct AttendPlan {
   int waves;          // wavefronts per workgroup (4 or 8)
-  int n_split;        // workgroups per (sequence, KV head)
+  int n_csplit;       // workgroups a unit's output channels are divided between (1 or 2)
+  int n_split;        // workgroups a unit's page list is divided between (each of the n_csplit shares)
   int chunk;          // page-list entries per workgroup
   int per_wave;       // page-list entries per wavefront (even)
   size_t partial_off; // workspace offsets (bytes)
   size_t counter_off;
   size_t total_bytes;
 };
-AttendPlan plan_attend(const CacheView& c, int row_len);
+AttendPlan plan_attend(const CacheView& c, int row_len, bool gather);
 hipError_t launch_attend(const CacheView& c, const bf16_t* q, const int32_t* pages, int row_len,
                          bf16_t* out, float* out_lse, void* ws, const AttendPlan& plan,
                          hipStream_t st);

@@ -21,14 +21,18 @@ __host__ __device__ constexpr size_t round16(size_t x) { return (x + 15) / 16 * 
 constexpr size_t kStageBytes = 2 * kHeadDim * sizeof(bf16_t);  // staged new key and value
 constexpr size_t kSeqCounterOff = ROCKETKV_WS_HEADER_BYTES / 2;  // per-sequence arrival counters
 
-template <int WAVES, bool APPEND, bool STREAM_K>
+// CB: channel blocks of the output a workgroup computes (8: all; 4: the unit's channels are divided
+// between two workgroups, see attend_block); blockIdx.y counts (list split, channel share) pairs.
+template <int WAVES, bool APPEND, bool STREAM_K, int CB>
 __global__ __launch_bounds__(WAVES* kWave) __attribute__((amdgpu_waves_per_eu(2)))
 void hsa_decode_kernel(CacheView c, SelectArgs sa, AttendArgs aa, AppendArgs ap, uint32_t* seq_counters) {
   constexpr int NT = WAVES * kWave;
   extern __shared__ __align__(16) unsigned char dsm[];  // [staged k,v][list][selection scratch | merge buffer]
   __shared__ int s_last;
   const int tid = threadIdx.x;
-  const int unit = blockIdx.x, split = blockIdx.y;
+  const int unit = blockIdx.x;
+  const int split = blockIdx.y / aa.n_csplit, cs = blockIdx.y % aa.n_csplit;
+  const bool first = blockIdx.y == 0;  // the workgroup of the unit that writes what is written once
   const int b = unit / c.n_kv_heads, g = unit % c.n_kv_heads;
   bf16_t* s_knew = reinterpret_cast<bf16_t*>(dsm);
   bf16_t* s_vnew = s_knew + kHeadDim;
@@ -47,15 +51,12 @@ void hsa_decode_kernel(CacheView c, SelectArgs sa, AttendArgs aa, AppendArgs ap,
   int n = 0;
   uint32_t arrivals = 0;
   bf16_t kb = 0, vb = 0;
-  if (!APPEND) {
-    n = c.seq_lens[b];  // in flight during the channel pick, which does not need it
-  } else {
-    // Every thread reads the old length itself (a vector load that travels with the others; a scalar
-    // load here would be waited for before the loads behind it are even issued).  After its K/V
-    // stream the workgroup reports that read to the per-sequence counter, and the one that finds every
-    // other workgroup of the sequence has reported stores the new length at its very end: no thread
-    // anywhere sees the length change under it.
-    n = __hip_atomic_load(&c.seq_lens[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  n = c.seq_lens[b + opaque_zero()];  // a vector load beside the others; not needed until the channels are picked
+  if (APPEND) {
+    // Every thread has read the old length.  Behind its K/V stream the workgroup reports that read to
+    // the per-sequence counter, and the one that finds every other workgroup of the sequence has
+    // reported stores the new length at its very end: no thread anywhere sees the length change
+    // under it.
     if (tid < kHeadDim) {
       const int64_t src = ((int64_t)b * c.n_kv_heads + g) * kHeadDim + tid;
       kb = ap.k_new[src];
@@ -64,7 +65,7 @@ void hsa_decode_kernel(CacheView c, SelectArgs sa, AttendArgs aa, AppendArgs ap,
       s_vnew[tid] = vb;
     }
   }
-  select_channels<NT>(c, sa, unit, sh, split == 0, qv);  // ends with a barrier: the staging is visible
+  select_channels<NT>(c, sa, unit, sh, first, qv);  // ends with a barrier: the staging is visible
   RKV_STAMP(1);
   bool room = false;
   if (APPEND) {
@@ -76,41 +77,59 @@ void hsa_decode_kernel(CacheView c, SelectArgs sa, AttendArgs aa, AppendArgs ap,
       n = n0 + 1;
     }
   }
-  // the summary column the new key goes into, fetched now (beside the row loads) and stored at the end
-  bf16_t old_max = 0, old_min = 0;
+  // the summary column the new key goes into, and where the token's page lives: requested behind the
+  // thread's last K/V tiles (see `report`), looked at in the write-back
+  uint32_t old_max = 0, old_min = 0;  // bf16 bits
   const auto summary_slot = [&]() {
     return ((int64_t)unit * kHeadDim + (tid & (kHeadDim - 1))) * c.pages_cap + (room ? tp.page : 0);
   };
-  int32_t pp_new = -1;  // where the new token's page lives (pools hold fewer than 2^31 pages): looked up now, needed at the end
-  if (APPEND && room && split == 0 && tid < kHeadDim) {
-    pp_new = (int32_t)phys_page(c, b, tp.page);
-    if (tp.slot != 0) {
-      old_max = ap.kmax[summary_slot()];
-      old_min = ap.kmin[summary_slot()];
-    }
-  }
-  select_pages<NT>(c, sa, unit, n, sh, keys, list, split == 0, tp);
+  int32_t pp_new = -1;
+  select_pages<NT>(c, sa, unit, n, sh, keys, list, first, tp);
   __syncthreads();  // list complete; the selection scratch is dead and becomes the merge buffer
   RKV_STAMP(5);
-  // Runs after this thread's last K/V tile, so that the stores drain under the merges: split 0 of the
-  // unit stores the key row, the value column and the updated summary column for later steps.
-  auto write_back = [&]() {
-    if (!APPEND) return;
-    if (tid == 0)  // this workgroup's read of the old length, reported where the answer's latency hides under the merges
-      arrivals = __hip_atomic_fetch_add(&seq_counters[b], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (room && split == 0 && tid < kHeadDim) {
+  // The token generated at this step goes to memory for later steps (the first workgroup of the unit
+  // writes the key row, the value column and the updated summary column), and the workgroup reports
+  // its read of the old length.  None of this is on the way of the result, so each piece sits where
+  // its memory latency hides:
+  //   request: what the write-back needs from memory (the page's old bounds, its place in the pools);
+  //   report:  the add to the sequence's counter, behind the loads of thread 0's last K/V tiles, so
+  //            that its answer travels with them;
+  //   store:   the write-back itself.
+  // The stores follow the thread's last tile and drain under the merges.  The request goes out with
+  // the report where the workgroup's registers allow (a share of the channels, CB < 8), otherwise in
+  // front of the stream, where its answers arrive with the first tiles.
+  auto request = [&]() {
+    if (APPEND && room && first && tid < kHeadDim) {
+      pp_new = phys_page_request(c, b, tp.page);
+      if (tp.slot != 0) {
+        old_max = ap.kmax[summary_slot()];
+        old_min = ap.kmin[summary_slot()];
+      }
+    }
+  };
+  auto store = [&]() {
+    if (APPEND && room && first && tid < kHeadDim) {
       const int64_t sum_off = summary_slot();
-      if (pp_new >= 0) {
-        const int64_t base = (int64_t)pp_new * c.stride_page + (int64_t)g * c.stride_head;
+      const int64_t pp = phys_page_resolve(c, pp_new);
+      if (pp >= 0) {
+        const int64_t base = pp * c.stride_page + (int64_t)g * c.stride_head;
         c.k_pool[base + tp.slot * kHeadDim + tid] = kb;
         c.v_pool[base + tid * kAttnPage + tp.slot] = vb;
       }
       const float x = bf16_to_f32(kb);
-      if (tp.slot == 0 || x > bf16_to_f32(old_max)) ap.kmax[sum_off] = kb;
-      if (tp.slot == 0 || x < bf16_to_f32(old_min)) ap.kmin[sum_off] = kb;
+      if (tp.slot == 0 || x > bf16_to_f32((bf16_t)use_late(old_max))) ap.kmax[sum_off] = kb;
+      if (tp.slot == 0 || x < bf16_to_f32((bf16_t)use_late(old_min))) ap.kmin[sum_off] = kb;
     }
   };
-  attend_block<WAVES, 1, STREAM_K>(c, aa, unit, split, n, list, reinterpret_cast<float*>(region), &s_last, tp, write_back);
+  auto last_round = [&]() {
+    if (!APPEND) return;
+    if (tid == 0)
+      arrivals = __hip_atomic_fetch_add(&seq_counters[b], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (CB < 8) request();
+  };
+  if (CB == 8) request();
+  attend_block<WAVES, 1, STREAM_K, CB>(c, aa, unit, split, cs, n, list, reinterpret_cast<float*>(region), &s_last, tp,
+                                       store, last_round);
 
   RKV_STAMP(12);
   if (APPEND) {
@@ -136,7 +155,7 @@ extern "C" int rocketkv_debug_stamps(void* host, size_t bytes, int clear) {
 size_t fused_decode_lds_bytes(const CacheView& c, int row_len, const AttendPlan& plan) {
   const size_t sel = round16(plan.waves == 8 ? sizeof(SelectShared<512>) : sizeof(SelectShared<256>)) +
                      (size_t)((c.pages_cap + 7) / 8 * 8) * sizeof(uint32_t);
-  const size_t mrg = (size_t)plan.waves * c.group * (kHeadDim + 2) * sizeof(float);
+  const size_t mrg = (size_t)plan.waves * c.group * (kHeadDim / plan.n_csplit + 2) * sizeof(float);
   return kStageBytes + round16((size_t)row_len * sizeof(int32_t)) + (sel > mrg ? sel : mrg);
 }
 
@@ -158,16 +177,21 @@ hipError_t launch_hsa_decode_fused(const CacheView& c, const SelectArgs& sa, con
   a.n_split = plan.n_split;
   a.chunk = plan.chunk;
   a.per_wave = plan.per_wave;
+  a.n_csplit = plan.n_csplit;
   uint32_t* seq_counters = decode_seq_counters(ws, plan);
   const size_t smem = fused_decode_lds_bytes(c, sa.row_len, plan);
-  const dim3 grid(c.batch * c.n_kv_heads, plan.n_split);
+  const dim3 grid(c.batch * c.n_kv_heads, plan.n_split * plan.n_csplit);
   const bool append = ap.k_new != nullptr;
   const bool stream_k = wants_stream_k(c, sa.row_len);
-#define RKV_LAUNCH_DECODE(W, A, S) \
-  hipLaunchKernelGGL((hsa_decode_kernel<W, A, S>), grid, dim3(W * kWave), smem, st, c, sa, a, ap, seq_counters)
+#define RKV_LAUNCH_DECODE(W, A, S, CB) \
+  hipLaunchKernelGGL((hsa_decode_kernel<W, A, S, CB>), grid, dim3(W * kWave), smem, st, c, sa, a, ap, seq_counters)
 #define RKV_LAUNCH_DECODE_S(W, A) \
-  do { if (stream_k) RKV_LAUNCH_DECODE(W, A, true); else RKV_LAUNCH_DECODE(W, A, false); } while (0)
-  if (plan.waves == 8) {
+  do { if (stream_k) RKV_LAUNCH_DECODE(W, A, true, 8); else RKV_LAUNCH_DECODE(W, A, false, 8); } while (0)
+  if (plan.n_csplit == 2) {
+    // (eight wavefronts by the plan.  K tiles are read by both workgroups of a pair: plain loads, so that
+    // the second reader finds them in L2; with the streaming hint it does not, measured 2.7 us slower.)
+    if (append) RKV_LAUNCH_DECODE(8, true, false, 4); else RKV_LAUNCH_DECODE(8, false, false, 4);
+  } else if (plan.waves == 8) {
     if (append) RKV_LAUNCH_DECODE_S(8, true); else RKV_LAUNCH_DECODE_S(8, false);
   } else {
     if (append) RKV_LAUNCH_DECODE_S(4, true); else RKV_LAUNCH_DECODE_S(4, false);

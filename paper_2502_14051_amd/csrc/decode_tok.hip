@@ -50,13 +50,10 @@ void hsa_decode_tok_kernel(CacheView c, CacheView lc, SelectArgs sa, AttendArgs 
   int pos0 = 0;  // where the new token goes in the cache
   uint32_t arrivals = 0;
   bf16_t kb = 0, vb = 0;
-  if (!APPEND) {
-    n = lc.seq_lens[b];  // in flight during the channel pick, which does not need it
-  } else {
-    // every thread reads the old lengths itself, with vector loads that travel with the others (see
-    // the header comment for how the workgroup reports these reads)
-    n = __hip_atomic_load(&lc.seq_lens[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (INDEXED) pos0 = __hip_atomic_load(&c.seq_lens[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  n = lc.seq_lens[b + opaque_zero()];  // a vector load beside the others; not needed until the channels are picked
+  if (APPEND) {
+    // every thread has read the old lengths (see the header comment for how the workgroup reports that)
+    if (INDEXED) pos0 = c.seq_lens[b + opaque_zero()];
     if (tid < kHeadDim) {
       const int64_t src = (int64_t)unit * kHeadDim + tid;
       kb = ap.k_new[src];
@@ -79,7 +76,7 @@ void hsa_decode_tok_kernel(CacheView c, CacheView lc, SelectArgs sa, AttendArgs 
     }
   }
   // the summary column the new key goes into, fetched now (beside the row loads) and stored at the end
-  bf16_t old_max = 0, old_min = 0;
+  uint32_t old_max = 0, old_min = 0;  // bf16 bits, not looked at before the write-back
   const int64_t sum_off = ((int64_t)unit * kHeadDim + (tid & (kHeadDim - 1))) * lc.pages_cap + (room ? tp.page : 0);
   if (APPEND && room && split == 0 && tid < kHeadDim && tp.slot != 0) {
     old_max = ap.kmax[sum_off];
@@ -89,7 +86,7 @@ void hsa_decode_tok_kernel(CacheView c, CacheView lc, SelectArgs sa, AttendArgs 
   __syncthreads();  // list complete; the selection scratch is dead and becomes the merge buffer
   auto write_back = [&]() {
     if (!APPEND) return;
-    if (tid == 0)  // this workgroup's read of the old length, reported where the answer's latency hides under the merges
+    if (tid == 0)  // this workgroup's read of the old lengths, reported where the answer's latency hides under the merges
       arrivals = __hip_atomic_fetch_add(&seq_counters[b], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (room && split == 0 && tid < kHeadDim) {
       const int sp = pos0 / c.page_size, ss = pos0 % c.page_size;
@@ -102,8 +99,8 @@ void hsa_decode_tok_kernel(CacheView c, CacheView lc, SelectArgs sa, AttendArgs 
       if (INDEXED && tid == 0)
         const_cast<int32_t*>(t.index)[(int64_t)unit * t.index_stride + tokp.j_new] = pos0;
       const float x = bf16_to_f32(kb);
-      if (tp.slot == 0 || x > bf16_to_f32(old_max)) ap.kmax[sum_off] = kb;
-      if (tp.slot == 0 || x < bf16_to_f32(old_min)) ap.kmin[sum_off] = kb;
+      if (tp.slot == 0 || x > bf16_to_f32((bf16_t)use_late(old_max))) ap.kmax[sum_off] = kb;
+      if (tp.slot == 0 || x < bf16_to_f32((bf16_t)use_late(old_min))) ap.kmin[sum_off] = kb;
     }
   };
   attend_tokens_block<WAVES, INDEXED, APPEND>(c, aa, t, unit, split, n, list, reinterpret_cast<float*>(region),
@@ -147,6 +144,7 @@ hipError_t launch_hsa_decode_tok_fused(const CacheView& c, const LogicalView* lv
   a.n_split = plan.n_split;
   a.chunk = plan.chunk * kAttnPage;
   a.per_wave = plan.per_wave * kAttnPage;
+  a.n_csplit = 1;
   TokenRun t;
   t.ps = lc.page_size;
   t.tokens = sa.row_len * t.ps;

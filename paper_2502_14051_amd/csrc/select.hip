@@ -60,11 +60,8 @@ __global__ __launch_bounds__(NT) void hsa_score_kernel(CacheView c, SelectArgs a
   load_q_column(c, a, unit, qv);
   int n = 0;
   bf16_t kb = 0, vb = 0;
-  if (!APPEND) {
-    n = c.seq_lens[b];  // not needed until the channels are picked
-  } else {
-    // every thread reads the old length itself: a vector load that travels with the others
-    n = __hip_atomic_load(&c.seq_lens[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  n = c.seq_lens[b + opaque_zero()];  // a vector load beside the others; not needed until the channels are picked
+  if (APPEND) {
     if (tid < kHeadDim) {
       kb = ap.k_new[(int64_t)unit * kHeadDim + tid];
       if (blockIdx.x == 0) vb = ap.v_new[(int64_t)unit * kHeadDim + tid];

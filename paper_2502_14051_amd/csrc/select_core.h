@@ -52,7 +52,8 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* wsum) 
 // then the same for every thread (a scalar branch), and a thread whose own row falls beyond k1 reads
 // the last picked row with weight zero.  The channel / weight lookups (LDS) all come first and the
 // eight 16-byte loads go out back to back, so the batch costs one LDS and one memory round trip.
-// (The page that is receiving a token in the same launch gets its score from the tail-page routines.)
+// (In the general routine the page that is receiving a token in the same launch gets its score from
+// the tail-page routines below instead.)
 template <bool STREAM = false>
 __device__ __forceinline__ void score_rows8(const SelectArgs& a, const int* s_chan, const float* s_wgt,
                                             int64_t rows, int pages_cap, int o, int j0, int jbase, int jstep,
@@ -96,17 +97,17 @@ __device__ __forceinline__ void score_rows8(const SelectArgs& a, const int* s_ch
 // for both): tail_page_load returns the old bound's bits, tail_page_finish leaves the two wavefronts'
 // partial sums in out2[0..1]; the caller adds them (fixed order) after a barrier.
 template <int NT>
-__device__ __forceinline__ bf16_t tail_page_load(const SelectArgs& a, const int* s_chan, const float* s_wgt,
+__device__ __forceinline__ uint32_t tail_page_load(const SelectArgs& a, const int* s_chan, const float* s_wgt,
                                                  int64_t rows, int pages_cap, const TailPatch& tp) {
   const int tid = threadIdx.x;
-  bf16_t old = 0;
+  uint32_t old = 0;
   if (tp.page >= 0 && tp.slot != 0 && tid < a.k1)
     old = ((s_wgt[tid] >= 0.f) ? a.kmax : a.kmin)[(rows + s_chan[tid]) * pages_cap + tp.page];
   return old;
 }
 template <int NT>
 __device__ __forceinline__ void tail_page_finish(const SelectArgs& a, const int* s_chan, const float* s_wgt,
-                                                 const TailPatch& tp, bf16_t old, float* out2) {
+                                                 const TailPatch& tp, uint32_t old, float* out2) {
   const int tid = threadIdx.x;
   if (tp.page < 0 || tid >= 2 * kWave) return;
   float contrib = 0.f;
@@ -114,7 +115,7 @@ __device__ __forceinline__ void tail_page_finish(const SelectArgs& a, const int*
     const float w = s_wgt[tid];
     float f = bf16_to_f32(tp.knew[s_chan[tid]]);
     if (tp.slot != 0) {
-      const float fo = bf16_to_f32(old);
+      const float fo = bf16_to_f32((bf16_t)use_late(old));
       f = (w >= 0.f) ? fmaxf(fo, f) : fminf(fo, f);
     }
     contrib = w * f;
@@ -286,6 +287,11 @@ __device__ __forceinline__ void radix_threshold(const uint32_t* keys, int P, int
   need_eq = k;
 }
 
+template <int NT, int ROUNDS>
+__device__ __forceinline__ int select_pages_small(const CacheView& c, const SelectArgs& a, int unit, int n,
+                                                  SelectShared<NT>& sh, uint32_t* keys, int32_t* list_lds,
+                                                  bool write_global, const TailPatch& tp);
+
 // Step 2, second half for a sequence of n tokens: page scores from the picked summary rows, exact
 // top-kp pages.  `keys` is LDS scratch of ceil8(pages_cap) words.  The ascending list goes to
 // `list_lds` (if not null, kp entries) and, when `write_global`, to a.out_pages / a.out_pages2 (-1
@@ -295,6 +301,9 @@ template <int NT>
 __device__ __forceinline__ int select_pages(const CacheView& c, const SelectArgs& a, int unit, int n,
                                             SelectShared<NT>& sh, uint32_t* keys, int32_t* list_lds,
                                             bool write_global, const TailPatch& tp) {
+  // (the same for the whole launch)
+  if (c.pages_cap <= 2 * NT) return select_pages_small<NT, 2>(c, a, unit, n, sh, keys, list_lds, write_global, tp);
+  if (c.pages_cap <= 5 * NT) return select_pages_small<NT, 5>(c, a, unit, n, sh, keys, list_lds, write_global, tp);
   const int tid = threadIdx.x;
   const int ps = c.page_size;
   int P = (n + ps - 1) / ps;
@@ -318,7 +327,7 @@ __device__ __forceinline__ int select_pages(const CacheView& c, const SelectArgs
   float* out_scores = write_global ? a.out_scores : nullptr;
   float* tail2 = sh.s_abs;  // free since the channel pick ended; [0..1]: the two halves of tp.page's score
   // the old bounds of tp.page: requested ahead of the row loads, used after them
-  const bf16_t tail_old = tail_page_load<NT>(a, sh.s_chan, sh.s_wgt, rows, c.pages_cap, tp);
+  const uint32_t tail_old = tail_page_load<NT>(a, sh.s_chan, sh.s_wgt, rows, c.pages_cap, tp);
   if (n_oct < NT) {
     int npow = 1;
     while (npow < n_oct) npow <<= 1;
@@ -410,6 +419,343 @@ __device__ __forceinline__ int select_pages(const CacheView& c, const SelectArgs
     }
     if (key > tau) ++gt;
   }
+  return kp;
+}
+
+// Step 2, second half, for caches of at most ROUNDS * NT pages (every fused decode launch of the usual
+// shapes): the same result as select_pages, arranged for latency.  The routine sits in front of the
+// K/V stream with HBM idle, so what counts is the number of dependent steps, not the work:
+//   - eight neighbouring lanes share an eight-page run and split the picked rows between them; the
+//     row sums meet in three lane-exchange steps (no LDS, no barrier) and lane r keeps page r of the
+//     run, so thread t holds the scores of pages t, NT + t, ... (one per round); the stale
+//     bound of a page that is receiving a token is patched in the loaded rows, no extra loads;
+//   - the kp-th largest score is found by counting into 1024 equal-width value bins between the
+//     smallest and the largest finite score (the forced recent pages, +inf, in the top bin): one
+//     histogram, scanned by every wavefront for itself.  Binning is monotone, so every page above the
+//     threshold's bin is in, every page below is out, and only the few pages sharing that bin are
+//     ranked exactly (by order key, ties to the lower page).  Page scores of one cache differ in
+//     their mantissas, not their exponents: radix digits pile them onto a few counters (hundreds of
+//     LDS atomics on one address), value bins spread them;
+//   - scores without a finite range, or more than 64 pages in the threshold's bin, go through the
+//     radix passes of the general routine instead.
+// Ends WITHOUT a final barrier, like select_pages.
+template <int NT, int ROUNDS>
+__device__ __forceinline__ int select_pages_small(const CacheView& c, const SelectArgs& a, int unit, int n,
+                                                  SelectShared<NT>& sh, uint32_t* keys, int32_t* list_lds,
+                                                  bool write_global, const TailPatch& tp) {
+  constexpr int kRuns = NT / 8;   // eight-page runs per round
+  constexpr int kRounds = ROUNDS;
+  constexpr int kWaves = NT / kWave;
+  constexpr int kCandMax = 64;
+  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+  const int ps = c.page_size;
+  int P = (n + ps - 1) / ps;
+  if (P > c.pages_cap) P = c.pages_cap;
+  int kp = pages_to_pick(n, ps, a.T);
+  if (kp > P) kp = P;
+  if (kp > a.row_len) kp = a.row_len;
+  if (write_global) {
+    if (a.out_pages)
+      for (int i = kp + tid; i < a.row_len; i += NT) a.out_pages[(int64_t)unit * a.row_len + i] = -1;
+    if (a.out_pages2)
+      for (int i = kp + tid; i < a.row_len2; i += NT) a.out_pages2[(int64_t)unit * a.row_len2 + i] = -1;
+  }
+  if (P == 0) return 0;
+  const int n_rec = min(a.n_recent, kp);  // no more forced pages than pages picked: the newest ones win
+  const int n_oct = (P + 7) / 8;
+  const int64_t rows = (int64_t)unit * kHeadDim;
+  const int o = tid / 8, r = tid % 8;
+  // scratch words in sh.partial (unused by the channel pick): candidate keys, their counter, the
+  // wavefronts' score ranges and emission counts
+  uint32_t* scr = reinterpret_cast<uint32_t*>(sh.partial);
+  uint32_t* cand = scr;                                         // [kCandMax]
+  uint32_t* cand_n = scr + kCandMax;                            // [1]
+  float* wlo = reinterpret_cast<float*>(scr + kCandMax + 8);    // [kWaves]
+  float* whi = wlo + kWaves;                                    // [kWaves]
+  uint32_t* wcnt = scr + kCandMax + 8 + 2 * kWaves;             // [kRounds][kWaves]
+
+  // ---- s1: page scores.  Thread (o, r) = (tid / 8, tid % 8) takes the rows r, r + 8, ... of the picked
+  // channels for the runs o, o + kRuns, ... (one per round); the loads of every round go out before the
+  // first is used, so the rounds share one memory round trip.
+  float score[kRounds];
+  {
+    constexpr int kBatch = 4;  // rows of a thread whose loads are in flight together, for every round (registers)
+    float acc[kRounds][8];
+    float tail_acc = 0.f;  // the score of the page that is receiving a token, if this thread's run holds it
+#pragma unroll
+    for (int i = 0; i < kRounds; ++i)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[i][e] = 0.f;
+    const int patch_round = tp.page >= 0 ? (tp.page / 8) / kRuns : -1;
+    const int patch_col = (tp.page >= 0 && (tp.page / 8) % kRuns == o) ? tp.page % 8 : -1;  // in round patch_round
+    for (int jb = 0; jb < a.k1; jb += 8 * kBatch) {
+      float w[kBatch];
+      int ch[kBatch];
+      uint32_t knew[kBatch];  // the new key at the rows' channels (only with a token being appended)
+#pragma unroll
+      for (int t = 0; t < kBatch; ++t) {
+        const int j = jb + r + t * 8;
+        const int jj = j < a.k1 ? j : a.k1 - 1;  // a row beyond k1: the last picked row again, weight zero
+        ch[t] = sh.s_chan[jj];
+        w[t] = sh.s_wgt[jj];
+        if (j >= a.k1) w[t] = 0.f;
+      }
+#pragma unroll
+      for (int t = 0; t < kBatch; ++t) knew[t] = tp.page >= 0 ? (uint32_t)tp.knew[ch[t]] : 0u;
+      const bf16_t* row[kBatch];
+#pragma unroll
+      for (int t = 0; t < kBatch; ++t) row[t] = (w[t] >= 0.f ? a.kmax : a.kmin) + (rows + ch[t]) * c.pages_cap + o * 8;
+      uint4 v[kRounds][kBatch];
+#pragma unroll
+      for (int i = 0; i < kRounds; ++i)
+#pragma unroll
+        for (int t = 0; t < kBatch; ++t) {
+          v[i][t] = make_uint4(0, 0, 0, 0);
+          // (the first two conditions are the same for the whole workgroup)
+          if (i * kRuns < n_oct && jb + t * 8 < a.k1 && i * kRuns + o < n_oct) v[i][t] = ld16<false>(row[t] + i * NT);
+        }
+      // The bound the rows hold for a page that is receiving a token is stale: the threads whose run
+      // holds it also fetch that one bound of each of their rows on its own (a 2-byte load out of a
+      // line the row load brings in anyway) and sum up the page's score from the bounds folded with the
+      // new key, or from the new key alone when the token opens the page (slot 0: what memory holds
+      // for that column is not looked at).  Only the wavefront that holds the page takes the branch.
+      if (tp.page >= 0 && __any(patch_col >= 0)) {
+        uint32_t old[kBatch];
+#pragma unroll
+        for (int t = 0; t < kBatch; ++t) {
+          old[t] = 0;
+          if (patch_col >= 0 && tp.slot != 0 && jb + t * 8 < a.k1) old[t] = row[t][patch_round * NT + patch_col];
+        }
+        float sum = 0.f;
+#pragma unroll
+        for (int t = 0; t < kBatch; ++t) {
+          const float fn = bf16_to_f32((bf16_t)knew[t]);
+          float f = fn;
+          if (tp.slot != 0) {
+            const float fo = bf16_to_f32((bf16_t)old[t]);
+            f = w[t] >= 0.f ? fmaxf(fo, fn) : fminf(fo, fn);
+          }
+          sum = fmaf(w[t], f, sum);
+        }
+        if (patch_col >= 0) tail_acc += sum;
+      }
+#pragma unroll
+      for (int i = 0; i < kRounds; ++i)
+#pragma unroll
+        for (int t = 0; t < kBatch; ++t) {
+          const uint32_t x[4] = {v[i][t].x, v[i][t].y, v[i][t].z, v[i][t].w};
+#pragma unroll
+          for (int q4 = 0; q4 < 4; ++q4) {
+            acc[i][2 * q4] = fmaf(w[t], bf16lo_to_f32(x[q4]), acc[i][2 * q4]);
+            acc[i][2 * q4 + 1] = fmaf(w[t], bf16hi_to_f32(x[q4]), acc[i][2 * q4 + 1]);
+          }
+        }
+    }
+    // the eight lanes of a run add up their row groups: lane pairs, quads, then the two quads; every
+    // lane ends with the same sums, formed in the same order; lane r keeps page r of the run
+    const auto lanes8 = [](float x) {
+      x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0xB1, 0xf, 0xf, false));   // quad_perm 1,0,3,2
+      x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x4E, 0xf, 0xf, false));   // quad_perm 2,3,0,1
+      x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x141, 0xf, 0xf, false));  // row_half_mirror
+      return x;
+    };
+    if (tp.page >= 0) tail_acc = lanes8(tail_acc);  // (the same for the whole workgroup)
+#pragma unroll
+    for (int i = 0; i < kRounds; ++i) {
+      score[i] = 0.f;
+      if (i * kRuns < n_oct) {  // the same for the whole workgroup
+        float mine = lanes8(acc[i][0]);
+#pragma unroll
+        for (int e = 1; e < 8; ++e) {
+          const float x = lanes8(acc[i][e]);
+          mine = r == e ? x : mine;
+        }
+        if (i == patch_round && patch_col == r) mine = tail_acc;
+        score[i] = mine;
+      }
+    }
+  }
+  RKV_STAMP(2);
+
+  // ---- order keys, and the range of the finite scores ---------------------------------------------
+  float* out_scores = write_global ? a.out_scores : nullptr;
+  uint32_t key[kRounds];
+  float val[kRounds];
+  bool live[kRounds];
+  float lo = INFINITY, hi = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < kRounds; ++i) {
+    const int p = i * NT + tid;
+    live[i] = p < P;
+    float sc = score[i];
+    if (live[i] && out_scores) out_scores[(int64_t)unit * c.pages_cap + p] = sc;
+    if (live[i] && p >= P - n_rec) sc = INFINITY;
+    val[i] = sc;
+    key[i] = live[i] ? f32_order_key(sc) : 0u;
+    if (live[i] && fabsf(sc) < INFINITY) {
+      lo = fminf(lo, sc);
+      hi = fmaxf(hi, sc);
+    }
+  }
+  uint32_t tau = 0, need_eq = (uint32_t)P;  // defaults select everything (kp == P)
+  bool by_bin = false;                     // picked by bin alone: every page of the threshold's bin is in
+  int bstar = 0;
+  int bin[kRounds];
+#pragma unroll
+  for (int i = 0; i < kRounds; ++i) bin[i] = 0;
+  if (kp < P) {
+    lo = wave_min_f32(lo);
+    hi = wave_max_f32(hi);
+    if (lane == 0) {
+      wlo[wave] = lo;
+      whi[wave] = hi;
+    }
+    if (tid == 0) *cand_n = 0;
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      lo = fminf(lo, wlo[w]);
+      hi = fmaxf(hi, whi[w]);
+    }
+    constexpr int NB = 1024, BPL = NB / kWave;  // bins, bins per lane of a scanning wavefront
+    const float scale = (float)(NB - 2) / (hi - lo);
+    bool decided = (hi > lo) && (scale < 3.0e38f);  // the same for every thread
+    if (decided) {
+      uint32_t* hist = &sh.hist[0][0];  // 4 x 256 counters, all zero since the channel pick
+#pragma unroll
+      for (int i = 0; i < kRounds; ++i) {
+        // clamped as a float, so that -inf, +inf and NaN never reach the conversion
+        int b = (int)fminf(fmaxf((val[i] - lo) * scale, 0.f), (float)(NB - 2));
+        if (val[i] == INFINITY) b = NB - 1;
+        bin[i] = b;
+        if (live[i]) atomicAdd(&hist[b], 1u);
+      }
+      __syncthreads();
+      // every wavefront finds the bin of the kp-th largest for itself: lane L owns the BPL bins below
+      // NB - L * BPL, so a prefix sum over the lanes counts the pages in higher bins
+      const int btop = NB - 1 - lane * BPL;  // the lane's highest bin
+      uint32_t hc[BPL], total = 0;
+#pragma unroll
+      for (int v = 0; v < BPL / 4; ++v) {
+        const uint4 h = *reinterpret_cast<const uint4*>(&hist[btop - 4 * v - 3]);
+        hc[4 * v + 0] = h.w;
+        hc[4 * v + 1] = h.z;
+        hc[4 * v + 2] = h.y;
+        hc[4 * v + 3] = h.x;
+        total += h.x + h.y + h.z + h.w;
+      }
+      uint32_t above = wave_incl_scan(total) - total;
+      int found = -1;
+      uint32_t need = 0, cnum = 0;
+#pragma unroll
+      for (int j = 0; j < BPL; ++j) {  // j = 0: the lane's highest bin
+        if (above < (uint32_t)kp && (uint32_t)kp <= above + hc[j]) {
+          found = btop - j;
+          need = (uint32_t)kp - above;
+          cnum = hc[j];
+        }
+        above += hc[j];
+      }
+      const int src = __ffsll((long long)__ballot(found >= 0)) - 1;
+      bstar = __builtin_amdgcn_readlane(found, src);
+      need = (uint32_t)__builtin_amdgcn_readlane((int)need, src);
+      cnum = (uint32_t)__builtin_amdgcn_readlane((int)cnum, src);
+      if (cnum == need) {
+        by_bin = true;
+      } else if (cnum <= (uint32_t)kCandMax) {
+        // exact rank among the pages of the threshold's bin
+#pragma unroll
+        for (int i = 0; i < kRounds; ++i)
+          if (live[i] && bin[i] == bstar) cand[atomicAdd(cand_n, 1u)] = key[i];
+        __syncthreads();
+        const uint32_t ki = lane < (int)cnum ? cand[lane] : 0u;
+        uint32_t gt = 0, ge = 0;
+        for (uint32_t j = 0; j < cnum; ++j) {
+          const uint32_t kj = cand[j];
+          gt += kj > ki;
+          ge += kj >= ki;
+        }
+        const bool is_tau = lane < (int)cnum && gt < need && need <= ge;  // equal keys give the same pair
+        const int who = __ffsll((long long)__ballot(is_tau)) - 1;
+        tau = (uint32_t)__builtin_amdgcn_readlane((int)ki, who);
+        need_eq = need - (uint32_t)__builtin_amdgcn_readlane((int)gt, who);
+      } else {
+        decided = false;
+      }
+    }
+    if (!decided) {
+      // the general routine's radix passes, on the keys in LDS
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < kRounds; ++i)
+        if (live[i]) keys[i * NT + tid] = key[i];
+      for (int i = tid; i < 4 * 256; i += NT) (&sh.hist[0][0])[i] = 0;
+      __syncthreads();
+      radix_threshold<NT, false>(keys, P, kp, sh.hist, tau, need_eq);
+      bstar = -1;  // every live page is ranked by its key
+    }
+  }
+  RKV_STAMP(3);
+
+  // ---- emit ascending.  Page order is (round, thread) order: a prefix sum over the threads per round.
+  // In: every page above the threshold (by bin, then by key), plus the first need_eq pages equal to it.
+  uint32_t cnt[kRounds];  // low 16 bits: pages above the threshold, high 16 bits: pages equal to it
+  bool above_t[kRounds], equal_t[kRounds];
+#pragma unroll
+  for (int i = 0; i < kRounds; ++i) {
+    if (kp >= P) {
+      above_t[i] = false;
+      equal_t[i] = live[i];  // key == tau is not needed: need_eq == P takes every live page
+    } else if (by_bin) {
+      above_t[i] = live[i] && bin[i] >= bstar;
+      equal_t[i] = false;
+    } else if (bstar >= 0) {
+      above_t[i] = live[i] && (bin[i] > bstar || (bin[i] == bstar && key[i] > tau));
+      equal_t[i] = live[i] && bin[i] == bstar && key[i] == tau;
+    } else {
+      above_t[i] = live[i] && key[i] > tau;
+      equal_t[i] = live[i] && key[i] == tau;
+    }
+    cnt[i] = (above_t[i] ? 1u : 0u) + (equal_t[i] ? 0x10000u : 0u);
+  }
+  if (by_bin) need_eq = 0;
+  uint32_t inc[kRounds];
+#pragma unroll
+  for (int i = 0; i < kRounds; ++i) {
+    inc[i] = 0;
+    if (i * NT < P) {  // the same for the whole workgroup
+      inc[i] = wave_incl_scan(cnt[i]);
+      if (lane == kWave - 1) wcnt[i * kWaves + wave] = inc[i];
+    }
+  }
+  __syncthreads();
+  uint32_t base = 0;  // counts of everything in front of this thread's page of the round at hand
+#pragma unroll
+  for (int i = 0; i < kRounds; ++i) {
+    if (i * NT >= P) break;
+    uint32_t before = base;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      const uint32_t x = wcnt[i * kWaves + w];
+      if (w < wave) before += x;
+      base += x;
+    }
+    before += inc[i] - cnt[i];
+    const uint32_t gt = before & 0xffffu, eq = before >> 16;
+    const bool take = above_t[i] || (equal_t[i] && eq < need_eq);
+    if (take) {
+      const uint32_t pos = gt + (equal_t[i] ? eq : min(eq, need_eq));
+      const int p = i * NT + tid;
+      if ((int)pos < kp) {
+        if (list_lds) list_lds[pos] = p;
+        if (write_global) {
+          if (a.out_pages) a.out_pages[(int64_t)unit * a.row_len + pos] = p;
+          if (a.out_pages2 && (int)pos < a.row_len2) a.out_pages2[(int64_t)unit * a.row_len2 + pos] = p;
+        }
+      }
+    }
+  }
+  RKV_STAMP(4);
   return kp;
 }
 
@@ -706,7 +1052,7 @@ __device__ __forceinline__ void score_chunk(const CacheView& c, const SelectArgs
   const bool owns_tail = tail_local >= 0 && tail_local < n_runs * 8;  // same for the whole workgroup
   TailPatch mine = tp;
   if (!owns_tail) mine.page = -1;
-  const bf16_t tail_old = tail_page_load<NT>(a, sh.s_chan, sh.s_wgt, rows, c.pages_cap, mine);
+  const uint32_t tail_old = tail_page_load<NT>(a, sh.s_chan, sh.s_wgt, rows, c.pages_cap, mine);
   if (o < n_runs)
     for (int jb = 0; jb < a.k1; jb += 8 * R)  // each slice of the rows has this one reader: streamed
       score_rows8<true>(a, sh.s_chan, sh.s_wgt, rows, c.pages_cap, o_begin + o, jb + r, jb, R, acc);

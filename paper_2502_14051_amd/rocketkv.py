@@ -26,7 +26,7 @@ EXPORTS = [
     "rocketkv_attend", "rocketkv_hsa_decode", "rocketkv_hsa_decode_append", "rocketkv_dense_decode", "rocketkv_append_kv",
     "rocketkv_snapkv_compress", "rocketkv_decompose", "rocketkv_last_error", "rocketkv_version",
     "rocketkv_snapkv_filter", "rocketkv_mt_build_page_summaries", "rocketkv_mt_workspace_bytes", "rocketkv_mt_hsa_decode",
-    "rocketkv_mt_append_kv", "rocketkv_mt_hsa_decode_append", "rocketkv_tune_attend",
+    "rocketkv_mt_append_kv", "rocketkv_mt_hsa_decode_append",
     "rocketkv_stream_read", "rocketkv_stream_read_sink_bytes",
 ]
 
@@ -119,8 +119,6 @@ def lib():
         L.rocketkv_last_error.argtypes = []
         L.rocketkv_version.restype = i32
         L.rocketkv_version.argtypes = []
-        L.rocketkv_tune_attend.restype = None
-        L.rocketkv_tune_attend.argtypes = [i32, i32, i32]
         L.rocketkv_stream_read.restype = i32
         L.rocketkv_stream_read.argtypes = [vp, C.c_size_t, vp, vp]
         L.rocketkv_stream_read_sink_bytes.restype = C.c_size_t
@@ -432,10 +430,6 @@ def decompose(seq_len: int, token_budget: int, head_dim: int = 128) -> dict:
 def pages_row_len(cache: Cache, token_budget: int) -> int:
     """Row length of the page list hsa_decode / hsa_select write for this budget."""
     return max(1, min(cache.pages_cap, (token_budget + cache.page_size - 1) // cache.page_size))
-
-
-def tune_attend(waves: int = 0, pairs_per_wave: int = 0, max_wgs: int = 0):
-    lib().rocketkv_tune_attend(waves, pairs_per_wave, max_wgs)
 
 
 def stream_read(buf, sink=None, stream=None):
