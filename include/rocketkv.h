@@ -187,6 +187,26 @@ int32_t rocketkv_hsa_decode(const rocketkv_cache_t* cache, const void* q, const 
                             size_t workspace_bytes, void* stream);
 
 /*
+ * rocketkv_hsa_decode for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments, same
+ * kernels and the same results as rocketkv_hsa_decode, minus the workspace: the scratch memory (arrival
+ * counters, split partials, the page list and page scores of the multi-launch paths) is a buffer of
+ * ROCKETKV_NOALLOC_SCRATCH_BYTES that is part of the library's device code, one copy per GPU, held
+ * until the process ends.  The call allocates and frees nothing.  It clears the buffer's counter
+ * header with a small fill kernel on `stream` first, so it costs one short launch more than
+ * rocketkv_hsa_decode.  A shape whose scratch need (rocketkv_workspace_bytes(ROCKETKV_OP_HSA_DECODE,
+ * ...)) exceeds the buffer is refused with ROCKETKV_UNSUPPORTED.  Every call on a GPU uses that GPU's
+ * one buffer: calls that overlap in time on one GPU (two streams, two threads) race and must be
+ * serialised by the caller; calls on different GPUs are independent.  The device current at the call
+ * must be the one `stream` and the buffers belong to.
+ */
+#define ROCKETKV_NOALLOC_SCRATCH_BYTES (4u << 20)
+int32_t rocketkv_hsa_decode_noalloc(const rocketkv_cache_t* cache, const void* q, const void* kmax,
+                                    const void* kmin, int32_t channel_budget, int32_t token_budget,
+                                    int32_t n_recent_pages, void* out, float* out_lse,
+                                    int32_t* out_pages, int32_t* out_channels, void* stream);
+
+/*
  * One decode step including the token generated at it (Section 3.4 Step 1, last
  * sentence, then Algorithm 1): the result, the caches, the summaries and
  * seq_lens end up exactly as after rocketkv_append_kv(k_new, v_new) followed by

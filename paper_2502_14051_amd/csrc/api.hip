@@ -1,6 +1,7 @@
 // C-ABI front end: argument validation on the host, workspace carving, kernel launches.
 // Every exported function validates before it enqueues anything and never synchronises.
 #include <math.h>
+#include <mutex>
 #include <stdarg.h>
 #include <stdio.h>
 #include <string.h>
@@ -377,6 +378,64 @@ int32_t rocketkv_hsa_decode(const rocketkv_cache_t* cache, const void* q, const 
   return decode_impl("rocketkv_hsa_decode", cache, q, nullptr, nullptr, const_cast<void*>(kmax),
                      const_cast<void*>(kmin), channel_budget, token_budget, n_recent_pages, out, out_lse,
                      out_pages, out_channels, workspace, workspace_bytes, stream);
+}
+
+// ---- rocketkv_hsa_decode with the library's own scratch memory ------------------------------------
+// One array per GPU, owned by the library's code object on that GPU until the process ends.  In host
+// code the array's name is only a handle for the runtime: the device address comes from
+// hipGetSymbolAddress, once per device, and only that address is ever handed to a kernel.
+static __device__ __align__(256) unsigned char scratch[ROCKETKV_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each device, null until first use there
+
+// The address of `scratch` on the current device (looked up on the first call there), or null with
+// the reason in g_err.
+void* scratch_on_current_device(const char* who) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) { hip_fail(e, who); return nullptr; }
+  if (dev < 0 || dev >= kMaxDevices) {
+    fail(ROCKETKV_UNSUPPORTED, "%s: device ordinal %d outside [0, %d)", who, dev, kMaxDevices);
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) { hip_fail(e, who); return nullptr; }
+    g_scratch_ptr[dev] = p;
+  }
+  return g_scratch_ptr[dev];
+}
+}  // namespace
+
+int32_t rocketkv_hsa_decode_noalloc(const rocketkv_cache_t* cache, const void* q, const void* kmax,
+                                    const void* kmin, int32_t channel_budget, int32_t token_budget,
+                                    int32_t n_recent_pages, void* out, float* out_lse,
+                                    int32_t* out_pages, int32_t* out_channels, void* stream) {
+  g_err[0] = 0;
+  const char* who = "rocketkv_hsa_decode_noalloc";
+  if (int r = check_cache(cache, true, who)) return r;
+  if (token_budget < 1) return fail(ROCKETKV_INVALID_ARG, "%s: token_budget must be >= 1", who);
+  const size_t need = plan_decode(cache, token_budget).total;
+  if (need > (size_t)ROCKETKV_NOALLOC_SCRATCH_BYTES)
+    return fail(ROCKETKV_UNSUPPORTED,
+                "%s: this shape needs %zu bytes of scratch, the built-in buffer holds %zu; use "
+                "rocketkv_hsa_decode with a workspace of the caller's", who, need,
+                (size_t)ROCKETKV_NOALLOC_SCRATCH_BYTES);
+  void* ws = scratch_on_current_device(who);
+  if (!ws) return g_err[0] ? ROCKETKV_HIP_ERROR : ROCKETKV_HIP_ERROR;
+  // The buffer keeps whatever the last call on this GPU left in it.  What a call expects to find at
+  // zero, the arrival counters in the leading header, is cleared here by a fill kernel (a launch, not a
+  // memset node, so the call can be captured into a graph); everything else is written before it is read.
+  const hipError_t e = launch_zero(ws, ROCKETKV_WS_HEADER_BYTES, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return hip_fail(e, who);
+  return decode_impl(who, cache, q, nullptr, nullptr, const_cast<void*>(kmax), const_cast<void*>(kmin),
+                     channel_budget, token_budget, n_recent_pages, out, out_lse, out_pages, out_channels, ws,
+                     (size_t)ROCKETKV_NOALLOC_SCRATCH_BYTES, stream);
 }
 
 int32_t rocketkv_hsa_decode_append(const rocketkv_cache_t* cache, const void* q, const void* k_new,

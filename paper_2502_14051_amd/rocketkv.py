@@ -27,8 +27,9 @@ EXPORTS = [
     "rocketkv_snapkv_compress", "rocketkv_decompose", "rocketkv_last_error", "rocketkv_version",
     "rocketkv_snapkv_filter", "rocketkv_mt_build_page_summaries", "rocketkv_mt_workspace_bytes", "rocketkv_mt_hsa_decode",
     "rocketkv_mt_append_kv", "rocketkv_mt_hsa_decode_append",
-    "rocketkv_stream_read", "rocketkv_stream_read_sink_bytes",
+    "rocketkv_stream_read", "rocketkv_stream_read_sink_bytes", "rocketkv_hsa_decode_noalloc",
 ]
+NOALLOC_SCRATCH_BYTES = 4 << 20
 
 
 class RocketKVError(RuntimeError):
@@ -92,6 +93,8 @@ def lib():
         L.rocketkv_attend.argtypes = [cp, vp, vp, i32, vp, vp, vp, sz, vp]
         L.rocketkv_hsa_decode.restype = i32
         L.rocketkv_hsa_decode.argtypes = [cp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+        L.rocketkv_hsa_decode_noalloc.restype = i32
+        L.rocketkv_hsa_decode_noalloc.argtypes = [cp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp]
         L.rocketkv_hsa_decode_append.restype = i32
         L.rocketkv_hsa_decode_append.argtypes = [cp, vp, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
         L.rocketkv_dense_decode.restype = i32
@@ -310,6 +313,15 @@ def hsa_decode(cache: Cache, q, kmax, kmin, channel_budget: int, token_budget: i
                                      token_budget, n_recent_pages, _ptr(out), _ptr(out_lse),
                                      _ptr(out_pages), _ptr(out_channels), _ptr(workspace),
                                      workspace.numel(), _stream(stream)))
+
+
+def hsa_decode_noalloc(cache: Cache, q, kmax, kmin, channel_budget: int, token_budget: int,
+                       n_recent_pages: int, out, out_lse, out_pages, out_channels, stream=None):
+    """rocketkv_hsa_decode on the library's own scratch buffer (no workspace, no allocation)."""
+    st = cache.struct()
+    _check(lib().rocketkv_hsa_decode_noalloc(C.byref(st), _ptr(q), _ptr(kmax), _ptr(kmin), channel_budget,
+                                             token_budget, n_recent_pages, _ptr(out), _ptr(out_lse),
+                                             _ptr(out_pages), _ptr(out_channels), _stream(stream)))
 
 
 def hsa_decode_append(cache: Cache, q, k_new, v_new, kmax, kmin, channel_budget: int, token_budget: int,
