@@ -31,9 +31,24 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published peak
-# HBM bytes per launch of the fused kernel on this workload from rocprofv3 FETCH_SIZE / WRITE_SIZE
-# (profiles/bench_llama8b_step_b16_pmc.txt): (FETCH_SIZE x 2.0 + WRITE_SIZE) KiB.
-TRAFFIC_BYTES_PER_LAUNCH = 75157197
+# HBM bytes per launch of the fused kernel on the default workload, from rocprofv3 FETCH_SIZE /
+# WRITE_SIZE counters: read at run time from the committed summary of that counter run (its line
+# "roofline.traffic: kernel=<name> batch=<B> bytes_per_launch=<N>"), never a literal here.
+PMC_SUMMARY = os.path.join(ROOT, "profiles", "bench_llama8b_step_b16_pmc.txt")
+
+
+def measured_traffic(batch):
+    """(kernel name, HBM bytes per launch) recorded for this batch size, or (None, None)."""
+    try:
+        for line in open(PMC_SUMMARY):
+            if line.startswith("roofline.traffic:"):
+                f = dict(kv.split("=", 1) for kv in line.split(":", 1)[1].split(";"))
+                f = {k.strip(): v.strip() for k, v in f.items()}
+                if int(f["batch"]) == batch:
+                    return f["kernel"], int(f["bytes_per_launch"])
+    except (OSError, KeyError, ValueError):
+        pass
+    return None, None
 
 
 def parse():
@@ -313,7 +328,8 @@ def main():
                             + k12 * ((P2 + 7) // 8 * 8) * 2 + P2 * 4 * 2 + kp2 * 4 * 2  # Step 2: rows, scores, list
                             + 2 * D * 2 + 2 * D * 2 * 2)                        # the appended token
         pt_gbs = pt_bytes / (pt_us * 1e-6) / 1e9
-        dec_pt = {"workload": f"same shape, t = {2 * T} split by Section 3.6: SnapKV keeps {N2}, page {ps2}, "
+        dec_pt = {"paper_equivalent_budget": round(T2 + P2 * k12 / (2.0 * D), 1),
+                  "workload": f"same shape, t = {2 * T} split by Section 3.6: SnapKV keeps {N2}, page {ps2}, "
                               f"k1 {k12}, {T2} tokens attended, token-major V, {len(pl)} layers",
                   "us_per_layer_step": round(pt_us, 3), "us_per_layer_step_no_append": round(pt_plain_us, 3),
                   "bytes_per_layer_step": pt_bytes, "achieved_GBs": round(pt_gbs, 1),
@@ -545,6 +561,32 @@ def main():
                          f"attention) on {nb} of {B} sequences x {Hkv} KV heads of layer 0 at n={n_now}, "
                          f"scaled by {B}/{nb}; {el:.1f} s of CPU time"}
 
+    # Stage 1 on the CPU: one oracle call on two sequences of the uncompressed prompt (16 units),
+    # scaled to the batch: an extrapolated figure for one layer's SnapKV stage.
+    cpu_snap = None
+    if not args.no_cpu and n_dense > 0:
+        Ld = dense_layers[0]
+        nb = min(2, B)
+        Kc, _ = rk.unpack_cache(Ld["cache"])
+        Kh = wl.to_bits(Kc[:nb, :, :w.context])
+        del Kc
+        qo = wl.to_bits(Ld["qobs"][:nb])
+        lens = np.full(nb, w.context, dtype=np.int32)
+        t_s0 = time.perf_counter()
+        oracle.snapkv(qo, Kh, lens, ks=w.pool_kernel, N=N)
+        el_s = time.perf_counter() - t_s0
+        cpu_snap = {"value": round(el_s * (B / nb) * 1e3, 1), "unit": "ms/layer (SnapKV stage)", "cores": oracle.num_threads(),
+                    "kind": "oracle", "extrapolated": True,
+                    "sample": f"one call of the fp64 oracle's Stage 1 (window scores, votes, pooling, top-k) on {nb} of {B} "
+                              f"sequences x {Hkv} KV heads of layer 0, prompt {w.context}, window {W}, pooling {w.pool_kernel}, "
+                              f"keep {N}, scaled by {B}/{nb}; {el_s:.1f} s of CPU time; the GPU stage takes "
+                              f"{float(np.median(snap_ms)):.3f} ms"}
+
+    # the paper's own budget t counts Step 2 and Step 3 traffic together (Section 3.6): tokens of exact
+    # attention plus the summary rows read, in key/value-pair equivalents of 2 D values
+    t_eq = T + P_now * k1 / (2.0 * D)
+    kernel_name, traffic = measured_traffic(B)
+
     out = {
         "metric": "hsa_decode_us_per_layer_step",
         "value": round(us_layer, 3),
@@ -563,7 +605,8 @@ def main():
         "config": {"workload": f"llama8b_step_b16: {w.n_layers} layers x (32q/8kv heads, d128), batch {B}, "
                                f"ctx {w.context} -> SnapKV {N} (+{n_now - N} appended), HSA budget {T}, "
                                f"page {ps}, k1 {k1}",
-                   "graph": graph is not None, "query_sets_cycled": n_var},
+                   "graph": graph is not None, "query_sets_cycled": n_var,
+                   "paper_equivalent_budget": round(t_eq, 1)},
         "decode_tokens_per_s_attention_only": round(B / (ms_per_step * 1e-3), 1),
         "hsa_achieved_GBs": round(hsa_gbs, 1),
         "hsa_frac_of_hbm_peak": round(hsa_gbs / HBM_PEAK_GBS, 4),
@@ -579,9 +622,10 @@ def main():
                                "attend_only_GBs": round(att_gbs, 1)},
         # the step is one launch of the fused kernel per layer, so its average launch time is the
         # timed region divided by the number of launches
-        "roofline": {"bound": "hbm", "kernel": "hsa_decode_kernel<8, true, true>", "achieved": round(hsa_gbs, 1),
+        "roofline": {"bound": "hbm", "kernel": kernel_name or "hsa_decode_kernel", "achieved": round(hsa_gbs, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(hsa_gbs / HBM_PEAK_GBS, 4),
-                     "traffic": TRAFFIC_BYTES_PER_LAUNCH, "us_per_launch": round(us_layer, 3),
+                     # from the committed counter summary when it covers this batch size, else null
+                     "traffic": traffic, "us_per_launch": round(us_layer, 3),
                      "bytes_per_launch": hsa_bytes,
                      # what a plain streaming read reaches on this GPU, and the fraction of that
                      "measured_read_GBs": None if read_gbs is None else round(read_gbs, 1),
@@ -592,6 +636,7 @@ def main():
         "single_layer_batch1": single,
         "other_shapes_and_batches": big,
         "cpu_baseline": cpu,
+        "cpu_baseline_snapkv": cpu_snap,
     }
     print(json.dumps(out))
 
