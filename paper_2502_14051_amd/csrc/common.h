@@ -64,8 +64,15 @@ static __device__ unsigned long long g_stamps[kStampSlots * 2 * kStampWaves * kS
       rkv::g_stamps[(((blockIdx.x / 16) * 2 + blockIdx.y) * rkv::kStampWaves + threadIdx.x / 64) *            \
                         rkv::kStampMarks + (k)] = __builtin_amdgcn_s_memrealtime();                          \
   } while (0)
+#define RKV_STAMP_VAL(k, v)                                                                                   \
+  do {                                                                                                        \
+    if (threadIdx.x % 64 == 0 && blockIdx.x % 16 == 3 && blockIdx.x / 16 < rkv::kStampSlots && blockIdx.y < 2) \
+      rkv::g_stamps[(((blockIdx.x / 16) * 2 + blockIdx.y) * rkv::kStampWaves + threadIdx.x / 64) *            \
+                        rkv::kStampMarks + (k)] = (unsigned long long)(v);                                    \
+  } while (0)
 #else
 #define RKV_STAMP(k) do { } while (0)
+#define RKV_STAMP_VAL(k, v) do { } while (0)
 #endif
 
 // A zero the compiler cannot see through.  Added to an index whose value is the same for the whole

@@ -66,6 +66,7 @@ void hsa_decode_kernel(CacheView c, SelectArgs sa, AttendArgs aa, AppendArgs ap,
     }
   }
   select_channels<NT>(c, sa, unit, sh, first, qv);  // ends with a barrier: the staging is visible
+  n = __builtin_amdgcn_readfirstlane(n);  // the same in every lane: a scalar from here on
   RKV_STAMP(1);
   bool room = false;
   if (APPEND) {

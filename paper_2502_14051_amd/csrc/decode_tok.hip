@@ -63,6 +63,8 @@ void hsa_decode_tok_kernel(CacheView c, CacheView lc, SelectArgs sa, AttendArgs 
     }
   }
   select_channels<NT>(lc, sa, unit, sh, split == 0, qv);  // ends with a barrier: the staging is visible
+  n = __builtin_amdgcn_readfirstlane(n);  // the same in every lane: scalars from here on
+  pos0 = __builtin_amdgcn_readfirstlane(pos0);
   bool room = false;
   if (APPEND) {
     const int n0 = n;

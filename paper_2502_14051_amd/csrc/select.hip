@@ -69,6 +69,7 @@ __global__ __launch_bounds__(NT) void hsa_score_kernel(CacheView c, SelectArgs a
     }
   }
   select_channels<NT>(c, a, unit, sh, blockIdx.x == 0, qv);  // its barriers publish s_knew
+  n = __builtin_amdgcn_readfirstlane(n);  // the same in every lane: a scalar from here on
   TailPatch tp = {-1, 0, s_knew, nullptr};
   bool room = false;
   if (APPEND) {
