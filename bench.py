@@ -259,6 +259,14 @@ def main():
             rk.append_kv(L["cache"], L["new_k"], L["new_v"], L["kmax"], L["kmin"], stream)
 
     attend_us = timed_graph(attend_all, args.kernel_reps) * 1e3 / w.n_layers
+    # the floor under the attention routine: the same page lists, the same work split and loads, nothing computed
+    gather_sink = rk.stream_gather(layers[0]["cache"], lists[0])
+
+    def gather_all():
+        for L, pg in zip(layers, lists):
+            rk.stream_gather(L["cache"], pg, gather_sink, stream)
+
+    gather_us = timed_graph(gather_all, args.kernel_reps) * 1e3 / w.n_layers
     select_us = timed_graph(select_all, args.kernel_reps) * 1e3 / w.n_layers
     decode_us = timed_graph(decode_all, args.kernel_reps) * 1e3 / w.n_layers
     n_before = int(layers[0]["cache"].seq_lens[0].item())
@@ -455,6 +463,20 @@ def main():
                                          0, L["out"], None, None, None, L["ws"], stream)
 
             big_us = timed_graph(big_all, max(2, args.kernel_reps // 2)) * 1e3 / nlb
+            rowb = rk.pages_row_len(bl[0]["cache"], T)
+            big_lists = []
+            for L in bl:
+                pgb = torch.empty((Bb, Hkv_b, rowb), dtype=torch.int32, device=dev)
+                rk.hsa_select(L["cache"], L["q"], L["kmax"], L["kmin"], k1, T, 0, pgb, None, None, stream)
+                big_lists.append(pgb)
+            big_sink = rk.stream_gather(bl[0]["cache"], big_lists[0])
+
+            def big_gather():
+                for L, pgb in zip(bl, big_lists):
+                    rk.stream_gather(L["cache"], pgb, big_sink, stream)
+
+            big_gather_us = timed_graph(big_gather, max(2, args.kernel_reps // 2)) * 1e3 / nlb
+            del big_lists
             nb_now = int(bl[0]["cache"].seq_lens[0].item())
             Pb = (nb_now + ps - 1) // ps
             kpb = min(Pb, max(1, T // ps))
@@ -463,7 +485,8 @@ def main():
                                     + (2 * D * 2 + 2 * D * 2 * 2))
             big_gbs = big_bytes / (big_us * 1e-6) / 1e9
             big.append({"workload": f"{label}, batch {Bb}, {nlb} layers",
-                        "us_per_layer_step": round(big_us, 3), "bytes_per_layer_step": big_bytes,
+                        "us_per_layer_step": round(big_us, 3), "gather_probe_us": round(big_gather_us, 3),
+                        "bytes_per_layer_step": big_bytes,
                         "achieved_GBs": round(big_gbs, 1), "frac_of_hbm_peak": round(big_gbs / HBM_PEAK_GBS, 4),
                         "decode_tokens_per_s_attention_only_all_layers":
                             round(Bb / (big_us * 1e-6 * wbase.n_layers), 1)})
@@ -617,7 +640,9 @@ def main():
         "snapkv_ms_per_layer": round(float(np.median(snap_ms)), 3),
         "host_wall_ms_per_step": round(wall_ms / args.steps, 4),
         "setup_s": round(t_setup, 1),
-        "stage_us_per_layer": {"attend_only": round(attend_us, 3), "select_only": round(select_us, 3),
+        "stage_us_per_layer": {"attend_only": round(attend_us, 3), "gather_probe": round(gather_us, 3),
+                               "gather_probe_GBs": round(units * kp * ps * D * 2 * 2 / (gather_us * 1e-6) / 1e9, 1),
+                               "select_only": round(select_us, 3),
                                "decode_no_append": round(decode_us, 3), "append_only": round(append_us, 3),
                                "attend_only_GBs": round(att_gbs, 1)},
         # the step is one launch of the fused kernel per layer, so its average launch time is the

@@ -371,6 +371,20 @@ int32_t rocketkv_decompose(int64_t seq_len, int32_t token_budget, int32_t head_d
 int32_t rocketkv_stream_read(const void* src, size_t bytes, void* sink, void* stream);
 size_t rocketkv_stream_read_sink_bytes(void);
 
+/*
+ * Measurement aid (no step of the method): read the K and V tiles of the listed pages (the list
+ * rocketkv_hsa_select writes: int32 [batch][n_kv_heads][pages_row_len], entries < 0 skipped) with the
+ * work split and the load pattern of the attention kernels, and compute nothing: no logits, no
+ * softmax, no merge.  Timed beside rocketkv_attend on the same list it gives the floor this GPU puts
+ * under Step 3 (Algorithm 1, y = attn(q, K[i2], V[i2])) for that list: the gather of 4 KiB tiles
+ * itself, plus one launch.  Channel-major V, 16-token pages.  `sink`: device, at least
+ * rocketkv_stream_gather_sink_bytes(cache, pages_row_len) bytes, one checksum word per wavefront.
+ * Asynchronous on `stream`.
+ */
+int32_t rocketkv_stream_gather(const rocketkv_cache_t* cache, const int32_t* pages, int32_t pages_row_len,
+                               void* sink, void* stream);
+size_t rocketkv_stream_gather_sink_bytes(const rocketkv_cache_t* cache, int32_t pages_row_len);
+
 /* Thread-local description of the last error returned on this thread ("" if none). */
 const char* rocketkv_last_error(void);
 

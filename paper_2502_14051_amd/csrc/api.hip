@@ -477,6 +477,28 @@ int32_t rocketkv_stream_read(const void* src, size_t bytes, void* sink, void* st
   return e == hipSuccess ? ROCKETKV_OK : hip_fail(e, who);
 }
 
+size_t rocketkv_stream_gather_sink_bytes(const rocketkv_cache_t* cache, int32_t pages_row_len) {
+  g_err[0] = 0;
+  if (check_cache(cache, false, "rocketkv_stream_gather_sink_bytes")) return 0;
+  if (pages_row_len < 1) { fail(ROCKETKV_INVALID_ARG, "rocketkv_stream_gather_sink_bytes: pages_row_len must be >= 1"); return 0; }
+  return probe_gather_sink_words(view_of(cache), pages_row_len) * sizeof(uint32_t);
+}
+
+int32_t rocketkv_stream_gather(const rocketkv_cache_t* cache, const int32_t* pages, int32_t pages_row_len,
+                               void* sink, void* stream) {
+  g_err[0] = 0;
+  const char* who = "rocketkv_stream_gather";
+  if (int r = check_cache(cache, true, who)) return r;
+  if (int r = check_attend_shape(cache, who)) return r;
+  if (cache->v_layout != ROCKETKV_V_CHANNEL_MAJOR)
+    return fail(ROCKETKV_UNSUPPORTED, "%s: the probe reads channel-major V tiles of 16-token pages", who);
+  if (!pages || !sink) return fail(ROCKETKV_INVALID_ARG, "%s: pages / sink must not be NULL", who);
+  if (pages_row_len < 1) return fail(ROCKETKV_INVALID_ARG, "%s: pages_row_len must be >= 1", who);
+  const hipError_t e = launch_stream_gather(view_of(cache), pages, pages_row_len, static_cast<uint32_t*>(sink),
+                                            static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? ROCKETKV_OK : hip_fail(e, who);
+}
+
 int32_t rocketkv_snapkv_compress(const void* q_obs, const rocketkv_cache_t* src, int32_t window,
                                  int32_t pool_kernel, int32_t keep_budget,
                                  const rocketkv_cache_t* dst, int32_t* kept_idx, void* workspace,

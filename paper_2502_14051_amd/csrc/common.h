@@ -266,6 +266,10 @@ uint32_t* attend_counters(void* ws, const AttendPlan& plan);
 // measurement aid: one streaming read of a buffer; `sink` holds a word per wavefront launched
 int probe_read_workgroups();
 hipError_t launch_stream_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t st);
+// measurement aid: the K/V tiles of a page list read with the attention kernels' work split and load
+// pattern, nothing computed; `sink` holds probe_gather_sink_words() words
+size_t probe_gather_sink_words(const CacheView& c, int row_len);
+hipError_t launch_stream_gather(const CacheView& c, const int32_t* pages, int row_len, uint32_t* sink, hipStream_t st);
 
 hipError_t launch_append(const CacheView& c, const bf16_t* k_new, const bf16_t* v_new, bf16_t* kmax,
                          bf16_t* kmin, hipStream_t st);

@@ -28,6 +28,7 @@ EXPORTS = [
     "rocketkv_snapkv_filter", "rocketkv_mt_build_page_summaries", "rocketkv_mt_workspace_bytes", "rocketkv_mt_hsa_decode",
     "rocketkv_mt_append_kv", "rocketkv_mt_hsa_decode_append",
     "rocketkv_stream_read", "rocketkv_stream_read_sink_bytes", "rocketkv_hsa_decode_noalloc",
+    "rocketkv_stream_gather", "rocketkv_stream_gather_sink_bytes",
 ]
 NOALLOC_SCRATCH_BYTES = 4 << 20
 
@@ -93,6 +94,10 @@ def lib():
         L.rocketkv_attend.argtypes = [cp, vp, vp, i32, vp, vp, vp, sz, vp]
         L.rocketkv_hsa_decode.restype = i32
         L.rocketkv_hsa_decode.argtypes = [cp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+        L.rocketkv_stream_gather.restype = i32
+        L.rocketkv_stream_gather.argtypes = [cp, vp, i32, vp, vp]
+        L.rocketkv_stream_gather_sink_bytes.restype = sz
+        L.rocketkv_stream_gather_sink_bytes.argtypes = [cp, i32]
         L.rocketkv_hsa_decode_noalloc.restype = i32
         L.rocketkv_hsa_decode_noalloc.argtypes = [cp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp]
         L.rocketkv_hsa_decode_append.restype = i32
@@ -442,6 +447,18 @@ def decompose(seq_len: int, token_budget: int, head_dim: int = 128) -> dict:
 def pages_row_len(cache: Cache, token_budget: int) -> int:
     """Row length of the page list hsa_decode / hsa_select write for this budget."""
     return max(1, min(cache.pages_cap, (token_budget + cache.page_size - 1) // cache.page_size))
+
+
+def stream_gather(cache: Cache, pages, sink=None, stream=None):
+    """Measurement aid: the K/V tiles of a page list read the way the attention kernels read them, nothing
+    computed (see rocketkv_stream_gather).  Returns the sink tensor."""
+    import torch
+    st = cache.struct()
+    if sink is None:
+        sink = torch.empty((lib().rocketkv_stream_gather_sink_bytes(C.byref(st), pages.shape[-1]),), dtype=torch.uint8,
+                           device=pages.device)
+    _check(lib().rocketkv_stream_gather(C.byref(st), _ptr(pages), pages.shape[-1], _ptr(sink), _stream(stream)))
+    return sink
 
 
 def stream_read(buf, sink=None, stream=None):
