@@ -7,11 +7,11 @@
 // splits of a unit land on the same XCD and the second reader of the summary rows hits in L2.
 //
 // The APPEND variant also takes in the token generated at this step (Section 3.4 Step 1: the
-// summaries are updated each time a new key is generated): split 0 of each unit writes the key row,
-// the value column and the updated summary column for later steps, while every workgroup patches the
-// new key / value into what it reads from LDS copies, so nobody depends on those writes having
-// landed.  The sequence length is bumped by whichever workgroup of the sequence is last to have read
-// the old one (a per-sequence arrival counter in the workspace header).
+// summaries are updated each time a new key is generated): the first workgroup of each unit writes
+// the key row, the value column and the updated summary column for later steps, while every
+// workgroup patches the new key / value into what it reads from LDS copies, so nobody depends on
+// those writes having landed.  The sequence length is bumped by whichever workgroup of the sequence
+// is last to have read the old one (a per-sequence arrival counter in the workspace header).
 #include "attend_core.h"
 #include "select_core.h"
 
