@@ -287,15 +287,36 @@ DECODE_CASES = [
     ("tiny", dict(n_q_heads=2, n_kv_heads=1, context=32768 * 16 - 5, token_budget=4096, n_heavy=32), None, 1, False),
     # more (sequence, KV head) units than compute units: the four-wavefront launch geometry
     ("tiny", dict(batch=40, n_q_heads=32, n_kv_heads=8, context=1100, token_budget=512, n_heavy=4), None, 0, True),
+    # the page counts at which the selection changes its form, on either side of each step: two and five
+    # pages per thread in registers, then scores through LDS (512-thread workgroups: 1024 / 2560 pages) ...
+    ("tiny", dict(n_q_heads=4, n_kv_heads=2, context=1024 * 16, token_budget=1024, n_heavy=16), None, 0, False),
+    ("tiny", dict(n_q_heads=4, n_kv_heads=2, context=1025 * 16 - 3, token_budget=1024, n_heavy=16), None, 1, True),
+    ("tiny", dict(n_q_heads=4, n_kv_heads=2, context=2560 * 16, token_budget=1024, n_heavy=16), None, 0, True),
+    ("tiny", dict(n_q_heads=4, n_kv_heads=2, context=2561 * 16 - 9, token_budget=1024, n_heavy=16), None, 2, False),
+    ("tiny", dict(n_q_heads=4, n_kv_heads=2, context=8192 * 16, token_budget=2048, n_heavy=16), None, 0, False),
+    # ... and the same steps for the 256-thread workgroups of launches with more than 256 units
+    # (512 / 1280 pages; `tile`: the host generator draws a third of the batch and the rest are copies,
+    # which keeps it to seconds at 264 units)
+    ("tiny", dict(batch=33, tile=11, n_q_heads=8, n_kv_heads=8, context=512 * 16, token_budget=512, n_heavy=4), None, 0, False),
+    ("tiny", dict(batch=33, tile=11, n_q_heads=8, n_kv_heads=8, context=513 * 16 - 1, token_budget=512, n_heavy=4), None, 1, False),
+    ("tiny", dict(batch=33, tile=11, n_q_heads=8, n_kv_heads=8, context=1280 * 16, token_budget=512, n_heavy=4), None, 0, False),
+    ("tiny", dict(batch=33, tile=11, n_q_heads=8, n_kv_heads=8, context=1281 * 16 - 7, token_budget=512, n_heavy=4), None, 0, False),
 ]
 
 
 @pytest.mark.parametrize("name,over,lens,n_recent,shuffle", DECODE_CASES)
 def test_hsa_decode(env, oracle, name, over, lens, n_recent, shuffle):
     torch, rk, dev = env
+    over = dict(over)
+    tile = over.pop("tile", 1)
     w = small(name, **over)
-    say("decode", name, over, lens, n_recent, shuffle)
-    d = wl.generate(w)
+    say("decode", name, over, lens, n_recent, shuffle, "tile", tile)
+    if tile > 1:
+        d = wl.generate(wl.scaled(w, batch=w.batch // tile))
+        d = {k: (np.concatenate([v] * tile, axis=0) if isinstance(v, np.ndarray) and v.ndim >= 1 and
+                 v.shape[0] == w.batch // tile else v) for k, v in d.items()}
+    else:
+        d = wl.generate(w)
     if lens is not None:
         d = ragged(d, lens)
     rng = np.random.default_rng(5) if shuffle else None
@@ -505,6 +526,12 @@ def test_snapkv_then_decode_pipeline(env, oracle):
     ("tiny", dict(batch=3, context=300, token_budget=96, heavy_nats=2.0), (250, 239, 0), True),
     ("llama8b_step_b16", dict(batch=2, context=4200, n_layers=1, token_budget=1024), (4090, 4096), False),
     ("llama70b_step_b16", dict(batch=1, context=600, n_layers=1, token_budget=128, n_heavy=4), (555,), False),
+    # the receiving page in the second round of the two-round register selection, crossing a page boundary
+    ("tiny", dict(batch=2, context=700 * 16 + 40, token_budget=512, n_heavy=8), (700 * 16 - 10, 520 * 16 + 3), False),
+    # five rounds: receiving pages in rounds 2 and 4
+    ("tiny", dict(batch=2, context=2100 * 16 + 40, token_budget=512, n_heavy=8), (1500 * 16 - 10, 2100 * 16 - 3), True),
+    # scores through LDS (more than 2560 pages)
+    ("tiny", dict(batch=2, context=3000 * 16 + 40, token_budget=512, n_heavy=8), (3000 * 16 - 10, 2600 * 16), False),
 ])
 def test_decode_append_equals_append_then_decode(env, oracle, name, over, lens0, shuffle):
     """rocketkv_hsa_decode_append must leave everything exactly as rocketkv_append_kv followed by
