@@ -85,20 +85,7 @@ void hsa_decode_kernel(CacheView c, SelectArgs sa, AttendArgs aa, AppendArgs ap,
     return ((int64_t)unit * kHeadDim + (tid & (kHeadDim - 1))) * c.pages_cap + (room ? tp.page : 0);
   };
   int32_t pp_new = -1;
-  select_pages<NT>(c, sa, unit, n, sh, keys, list, first, tp);
-  __syncthreads();  // list complete; the selection scratch is dead and becomes the merge buffer
-  RKV_STAMP(5);
-  // The token generated at this step goes to memory for later steps (the first workgroup of the unit
-  // writes the key row, the value column and the updated summary column), and the workgroup reports
-  // its read of the old length.  None of this is on the way of the result, so each piece sits where
-  // its memory latency hides:
-  //   request: what the write-back needs from memory (the page's old bounds, its place in the pools);
-  //   report:  the add to the sequence's counter, behind the loads of thread 0's last K/V tiles, so
-  //            that its answer travels with them;
-  //   store:   the write-back itself.
-  // The stores follow the thread's last tile and drain under the merges.  The request goes out with
-  // the report where the workgroup's registers allow (a share of the channels, CB < 8), otherwise in
-  // front of the stream, where its answers arrive with the first tiles.
+  // what the write-back needs from memory (the page's old bounds, its place in the pools)
   auto request = [&]() {
     if (APPEND && room && first && tid < kHeadDim) {
       pp_new = phys_page_request(c, b, tp.page);
@@ -108,6 +95,27 @@ void hsa_decode_kernel(CacheView c, SelectArgs sa, AttendArgs aa, AppendArgs ap,
       }
     }
   };
+  // One workgroup per compute unit (eight wavefronts, all channels): the request goes out here, while
+  // memory is idle, and its 256 scattered lines per unit are long back when the stream starts
+  // (0.3 us off the step at the benchmark shape).  With two workgroups per compute unit the other
+  // one is streaming at this point and the same move costs 0.5 us; there, and where the registers of
+  // the selection are needed (a share of the channels), it goes out later (see below).
+  constexpr bool kRequestEarly = CB == 8 && WAVES == 8;
+  if (kRequestEarly) request();
+  select_pages<NT>(c, sa, unit, n, sh, keys, list, first, tp);
+  __syncthreads();  // list complete; the selection scratch is dead and becomes the merge buffer
+  RKV_STAMP(5);
+  // The token generated at this step goes to memory for later steps (the first workgroup of the unit
+  // writes the key row, the value column and the updated summary column), and the workgroup reports
+  // its read of the old length.  None of this is on the way of the result, so each piece sits where
+  // its memory latency hides:
+  //   request: the loads above;
+  //   report:  the add to the sequence's counter, behind the loads of thread 0's last K/V tiles, so
+  //            that its answer travels with them;
+  //   store:   the write-back itself.
+  // The stores follow the thread's last tile and drain under the merges.  Where the request has not
+  // gone out yet, it goes out with the report if the workgroup's registers allow (a share of the
+  // channels, CB < 8), otherwise in front of the stream, where its answers arrive with the first tiles.
   auto store = [&]() {
     if (APPEND && room && first && tid < kHeadDim) {
       const int64_t sum_off = summary_slot();
@@ -128,7 +136,7 @@ void hsa_decode_kernel(CacheView c, SelectArgs sa, AttendArgs aa, AppendArgs ap,
       arrivals = __hip_atomic_fetch_add(&seq_counters[b], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (CB < 8) request();
   };
-  if (CB == 8) request();
+  if (CB == 8 && !kRequestEarly) request();
   attend_block<WAVES, 1, STREAM_K, CB>(c, aa, unit, split, cs, n, list, reinterpret_cast<float*>(region), &s_last, tp,
                                        store, last_round);
 
