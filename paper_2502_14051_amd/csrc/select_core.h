@@ -617,7 +617,10 @@ __device__ __forceinline__ int select_pages_small(const CacheView& c, const Sele
       lo = fminf(lo, wlo[w]);
       hi = fmaxf(hi, whi[w]);
     }
-    constexpr int NB = 1024, BPL = NB / kWave;  // bins, bins per lane of a scanning wavefront
+    // bins, and bins per lane of a scanning wavefront.  Every wavefront walks its lanes' bins one after
+    // the other, so fewer bins make a shorter scan and more pages per bin a longer exact rank; with at
+    // most two pages per thread 256 bins measured 0.4 us ahead of 1024 at the benchmark shape.
+    constexpr int NB = ROUNDS <= 2 ? 256 : 1024, BPL = NB / kWave;
     const float scale = (float)(NB - 2) / (hi - lo);
     bool decided = (hi > lo) && (scale < 3.0e38f);  // the same for every thread
     if (decided) {
