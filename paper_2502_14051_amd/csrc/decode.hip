@@ -31,39 +31,40 @@ void hsa_decode_kernel(CacheView c, SelectArgs sa, AttendArgs aa, AppendArgs ap,
   __shared__ int s_last;
   const int tid = threadIdx.x;
   const int unit = blockIdx.x;
+  const int b = unit / c.n_kv_heads, g = unit % c.n_kv_heads;
+  RKV_STAMP(0);
+  // Everything the selection starts from is requested before anything else is done or used, so that q,
+  // the new key / value and the length cost one memory round trip together, and so that the kernel
+  // arguments they go through are the first ones fetched (the rest of the set-up below runs while
+  // the loads travel).
+  uint32_t qv[kMaxGroup];  // one bf16 each, kept in a register of its own (no packing, hence no early use)
+  load_q_column(c, sa, unit, qv);
+  int n = c.seq_lens[b + opaque_zero()];  // a vector load beside the others; not needed until the channels are picked
+  uint32_t arrivals = 0;
+  bf16_t kb = 0, vb = 0;
+  if (APPEND && tid < kHeadDim) {
+    const int64_t src = ((int64_t)b * c.n_kv_heads + g) * kHeadDim + tid;
+    kb = ap.k_new[src];
+    vb = ap.v_new[src];
+  }
+
   const int split = blockIdx.y / aa.n_csplit, cs = blockIdx.y % aa.n_csplit;
   const bool first = blockIdx.y == 0;  // the workgroup of the unit that writes what is written once
-  const int b = unit / c.n_kv_heads, g = unit % c.n_kv_heads;
   bf16_t* s_knew = reinterpret_cast<bf16_t*>(dsm);
   bf16_t* s_vnew = s_knew + kHeadDim;
   int32_t* list = reinterpret_cast<int32_t*>(dsm + kStageBytes);
   unsigned char* region = dsm + kStageBytes + round16((size_t)sa.row_len * sizeof(int32_t));
   SelectShared<NT>& sh = *reinterpret_cast<SelectShared<NT>*>(region);
   uint32_t* keys = reinterpret_cast<uint32_t*>(region + round16(sizeof(SelectShared<NT>)));
-
-  RKV_STAMP(0);
   TailPatch tp = {-1, 0, s_knew, s_vnew};
   for (int i = tid; i < sa.row_len; i += NT) list[i] = -1;
-  // Everything the selection starts from is requested before anything is used, so that q, the new
-  // key / value and the length cost one memory round trip together.
-  uint32_t qv[kMaxGroup];  // one bf16 each, kept in a register of its own (no packing, hence no early use)
-  load_q_column(c, sa, unit, qv);
-  int n = 0;
-  uint32_t arrivals = 0;
-  bf16_t kb = 0, vb = 0;
-  n = c.seq_lens[b + opaque_zero()];  // a vector load beside the others; not needed until the channels are picked
-  if (APPEND) {
+  if (APPEND && tid < kHeadDim) {
     // Every thread has read the old length.  Behind its K/V stream the workgroup reports that read to
     // the per-sequence counter, and the one that finds every other workgroup of the sequence has
     // reported stores the new length at its very end: no thread anywhere sees the length change
     // under it.
-    if (tid < kHeadDim) {
-      const int64_t src = ((int64_t)b * c.n_kv_heads + g) * kHeadDim + tid;
-      kb = ap.k_new[src];
-      vb = ap.v_new[src];
-      s_knew[tid] = kb;
-      s_vnew[tid] = vb;
-    }
+    s_knew[tid] = kb;
+    s_vnew[tid] = vb;
   }
   select_channels<NT>(c, sa, unit, sh, first, qv);  // ends with a barrier: the staging is visible
   n = __builtin_amdgcn_readfirstlane(n);  // the same in every lane: a scalar from here on

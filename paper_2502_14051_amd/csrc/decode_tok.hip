@@ -32,25 +32,14 @@ void hsa_decode_tok_kernel(CacheView c, CacheView lc, SelectArgs sa, AttendArgs 
   const int tid = threadIdx.x;
   const int unit = blockIdx.x, split = blockIdx.y;
   const int b = unit / c.n_kv_heads, g = unit % c.n_kv_heads;
-  bf16_t* s_knew = reinterpret_cast<bf16_t*>(dsm);
-  bf16_t* s_vnew = s_knew + kHeadDim;
-  int32_t* list = reinterpret_cast<int32_t*>(dsm + kTokStageBytes);
-  unsigned char* region = dsm + kTokStageBytes + tok_round16((size_t)sa.row_len * sizeof(int32_t));
-  SelectShared<NT>& sh = *reinterpret_cast<SelectShared<NT>*>(region);
-  uint32_t* keys = reinterpret_cast<uint32_t*>(region + tok_round16(sizeof(SelectShared<NT>)));
-  const int ps = lc.page_size;
-
-  TailPatch tp = {-1, 0, s_knew, s_vnew};
-  TokenPatch tokp = {-1, s_knew, s_vnew};
-  for (int i = tid; i < sa.row_len; i += NT) list[i] = -1;
-  // q, the new key / value and the lengths: all requested before anything is used (one round trip)
+  // q, the new key / value and the lengths: all requested before anything else is done or used (one
+  // round trip, through the first kernel arguments fetched; the set-up below runs while they travel)
   uint32_t qv[kMaxGroup];  // one bf16 each, kept in a register of its own (no packing, hence no early use)
   load_q_column(lc, sa, unit, qv);
-  int n = 0;
+  int n = lc.seq_lens[b + opaque_zero()];  // a vector load beside the others; not needed until the channels are picked
   int pos0 = 0;  // where the new token goes in the cache
   uint32_t arrivals = 0;
   bf16_t kb = 0, vb = 0;
-  n = lc.seq_lens[b + opaque_zero()];  // a vector load beside the others; not needed until the channels are picked
   if (APPEND) {
     // every thread has read the old lengths (see the header comment for how the workgroup reports that)
     if (INDEXED) pos0 = c.seq_lens[b + opaque_zero()];
@@ -58,9 +47,22 @@ void hsa_decode_tok_kernel(CacheView c, CacheView lc, SelectArgs sa, AttendArgs 
       const int64_t src = (int64_t)unit * kHeadDim + tid;
       kb = ap.k_new[src];
       vb = ap.v_new[src];
-      s_knew[tid] = kb;
-      s_vnew[tid] = vb;
     }
+  }
+
+  bf16_t* s_knew = reinterpret_cast<bf16_t*>(dsm);
+  bf16_t* s_vnew = s_knew + kHeadDim;
+  int32_t* list = reinterpret_cast<int32_t*>(dsm + kTokStageBytes);
+  unsigned char* region = dsm + kTokStageBytes + tok_round16((size_t)sa.row_len * sizeof(int32_t));
+  SelectShared<NT>& sh = *reinterpret_cast<SelectShared<NT>*>(region);
+  uint32_t* keys = reinterpret_cast<uint32_t*>(region + tok_round16(sizeof(SelectShared<NT>)));
+  const int ps = lc.page_size;
+  TailPatch tp = {-1, 0, s_knew, s_vnew};
+  TokenPatch tokp = {-1, s_knew, s_vnew};
+  for (int i = tid; i < sa.row_len; i += NT) list[i] = -1;
+  if (APPEND && tid < kHeadDim) {
+    s_knew[tid] = kb;
+    s_vnew[tid] = vb;
   }
   select_channels<NT>(lc, sa, unit, sh, split == 0, qv);  // ends with a barrier: the staging is visible
   n = __builtin_amdgcn_readfirstlane(n);  // the same in every lane: scalars from here on
