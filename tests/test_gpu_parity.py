@@ -181,6 +181,47 @@ def test_select_breaks_ties_towards_lower_index(env, oracle):
     assert np.array_equal(ref["pages"][:, :, :10], pages.cpu().numpy())
 
 
+@pytest.mark.parametrize("P,T", [(300, 640), (1000, 1600), (1500, 640), (2600, 1024)])
+def test_pick_with_crowded_threshold(env, oracle, P, T):
+    """Most pages score exactly the same and the threshold falls among them (far more ties than the
+    exact-rank step of the register selection takes on, so it hands over to the radix passes), a few
+    pages score higher, a few lower: the higher ones and the lowest-indexed ties must come out, in the
+    fused kernel's own selection, for page counts on each of its paths."""
+    torch, rk, dev = env
+    say("crowded threshold", P, T)
+    B, Hkv, G, D, ps = 1, 2, 2, 128, 16
+    n = P * ps - 3
+    rng = np.random.default_rng(P)
+    level = np.ones(P, dtype=np.float32)
+    special = rng.choice(P, size=24, replace=False)
+    level[special[:12]] = 2.0
+    level[special[12:]] = 0.5
+    K = np.repeat(level, ps)[:n][None, None, :, None] * np.ones((B, Hkv, 1, D), dtype=np.float32)
+    d = dict(q=wl.f32_to_bf16_bits(np.ones((B, Hkv * G, D), dtype=np.float32)), K=wl.f32_to_bf16_bits(K),
+             V=wl.f32_to_bf16_bits(rng.standard_normal((B, Hkv, n, D)).astype(np.float32)),
+             seq_lens=np.array([n], dtype=np.int32))
+    cache, q = to_device_cache(rk, torch, d, Hkv * G, ps, dev)
+    kmax, kmin = rk.alloc_summaries(cache)
+    rk.build_page_summaries(cache, kmax, kmin)
+    row = rk.pages_row_len(cache, T)
+    out = torch.empty((B, Hkv * G, D), dtype=torch.bfloat16, device=dev)
+    pages = torch.empty((B, Hkv, row), dtype=torch.int32, device=dev)
+    ws = rk.alloc_workspace(rk.OP_HSA_DECODE, cache, T)
+    rk.hsa_decode(cache, q, kmax, kmin, 32, T, 0, out, None, pages, None, ws)
+    torch.cuda.synchronize()
+    kp = T // ps
+    big = np.sort(special[:12])
+    ties = np.array([p for p in range(P) if level[p] == 1.0])[:kp - 12]
+    want = np.sort(np.concatenate([big, ties]))
+    got = pages.cpu().numpy()
+    for g in range(Hkv):
+        assert got[0, g, :kp].tolist() == want.tolist()
+    ref = oracle.hsa_decode(d["q"], d["K"], d["V"], d["seq_lens"], ps, 32, T)
+    assert np.array_equal(ref["pages"][:, :, :kp], got[:, :, :kp])
+    want_y, _ = oracle.attend_given(d["q"], d["K"], d["V"], d["seq_lens"], ps, got)
+    assert_attention_close(wl.to_bits(out), want_y, "y, crowded threshold")
+
+
 # ------------------------------------------------------------------ Step 3 and the dense baseline
 ATTEND_CASES = [
     ("tiny", dict(n_heavy=0), None, False),                      # diffuse softmax
