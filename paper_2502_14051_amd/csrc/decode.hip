@@ -103,7 +103,46 @@ void hsa_decode_kernel(CacheView c, SelectArgs sa, AttendArgs aa, AppendArgs ap,
   // the selection are needed (a share of the channels), it goes out later (see below).
   constexpr bool kRequestEarly = CB == 8 && WAVES == 8;
   if (kRequestEarly) request();
+  // Launches of more than 256 units (four wavefronts, two workgroups per compute unit) are bound by
+  // bandwidth from start to end, and there the 256 lines per unit that hold the old bounds, two useful
+  // bytes each, are worth avoiding.  The same bounds are the extremes of the rows the receiving page
+  // already holds, at most 15 rows of 256 contiguous bytes: the thread of a channel reads its column
+  // of them here, all loads in flight across the selection, and folds them when the selection is
+  // done (1-2 us off the step at batch 64-128).  A page without storage keeps to the summary column.
+  // (With one workgroup per compute unit the extra instructions in front of the stream cost more
+  // than the lines: 26.6 against 26.0 us at the benchmark shape when it was tried.)
+  constexpr bool kBoundsFromRows = APPEND && CB == 8 && WAVES == 4;
+  constexpr int kOldRows = kAttnPage - 1;
+  uint32_t old_row[kBoundsFromRows ? kOldRows : 1];
+  bool from_rows = false;
+  if (kBoundsFromRows && room && first && tid < kHeadDim) {
+    pp_new = phys_page_request(c, b, tp.page);
+    if (tp.slot != 0) {
+      const int64_t pp = phys_page_resolve(c, pp_new);
+      if (pp >= 0) {
+        from_rows = true;
+        const bf16_t* col = c.k_pool + pp * c.stride_page + (int64_t)g * c.stride_head + tid;
+#pragma unroll
+        for (int r = 0; r < kOldRows; ++r)  // rows beyond the last one held repeat it: harmless, and no branch
+          old_row[r] = col[min(r, tp.slot - 1) * kHeadDim];
+      } else {
+        old_max = ap.kmax[summary_slot()];
+        old_min = ap.kmin[summary_slot()];
+      }
+    }
+  }
   select_pages<NT>(c, sa, unit, n, sh, keys, list, first, tp);
+  if (kBoundsFromRows && from_rows) {
+    float mx = -INFINITY, mn = INFINITY;
+#pragma unroll
+    for (int r = 0; r < kOldRows; ++r) {
+      const float x = bf16_to_f32((bf16_t)use_late(old_row[r]));
+      mx = fmaxf(mx, x);
+      mn = fminf(mn, x);
+    }
+    old_max = __float_as_uint(mx) >> 16;
+    old_min = __float_as_uint(mn) >> 16;
+  }
   __syncthreads();  // list complete; the selection scratch is dead and becomes the merge buffer
   RKV_STAMP(5);
   // The token generated at this step goes to memory for later steps (the first workgroup of the unit
@@ -137,7 +176,7 @@ void hsa_decode_kernel(CacheView c, SelectArgs sa, AttendArgs aa, AppendArgs ap,
       arrivals = __hip_atomic_fetch_add(&seq_counters[b], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (CB < 8) request();
   };
-  if (CB == 8 && !kRequestEarly) request();
+  if (CB == 8 && !kRequestEarly && !kBoundsFromRows) request();
   attend_block<WAVES, 1, STREAM_K, CB>(c, aa, unit, split, cs, n, list, reinterpret_cast<float*>(region), &s_last, tp,
                                        store, last_round);
 

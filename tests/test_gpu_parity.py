@@ -573,6 +573,12 @@ def test_snapkv_then_decode_pipeline(env, oracle):
     ("tiny", dict(batch=2, context=2100 * 16 + 40, token_budget=512, n_heavy=8), (1500 * 16 - 10, 2100 * 16 - 3), True),
     # scores through LDS (more than 2560 pages)
     ("tiny", dict(batch=2, context=3000 * 16 + 40, token_budget=512, n_heavy=8), (3000 * 16 - 10, 2600 * 16), False),
+    # more than 256 units: the four-wavefront kernel, which takes the receiving page's old bounds from the
+    # page's own rows; every slot of a page and both sides of a page boundary, with and without a block table
+    ("tiny", dict(batch=33, n_q_heads=8, n_kv_heads=8, context=420, token_budget=128, n_heavy=2),
+     tuple(300 + (7 * i) % 61 for i in range(33)), False),
+    ("tiny", dict(batch=33, n_q_heads=16, n_kv_heads=8, context=420, token_budget=96, n_heavy=2),
+     tuple([0, 1, 15, 16, 17] + [200 + (11 * i) % 97 for i in range(28)]), True),
 ])
 def test_decode_append_equals_append_then_decode(env, oracle, name, over, lens0, shuffle):
     """rocketkv_hsa_decode_append must leave everything exactly as rocketkv_append_kv followed by
